@@ -1,0 +1,291 @@
+"""CPU oracle for bucketed gradient synchronization.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+HIP path is checked against.  Only the tests, the smoke check and the
+benchmark's cpu_baseline leg may import it; the product never does, and this
+file imports nothing from the product.
+
+What is computed (paper: "PyTorch Distributed: Experiences on Accelerating
+Data Parallel Training", arXiv 2006.15704):
+
+  * Section 3.2.3 / Algorithm 1, constructor: parameters are allocated to
+    flat buckets in the reverse order of net.parameters() under a bucket
+    size cap c.
+  * Algorithm 1, autograd_hook: the gradient of parameter i is copied into
+    view = b_i.narrow(offset, size) of its bucket; a bucket whose gradients
+    are all ready is marked ready; ready buckets are launched in order.
+  * Section 4.2, "Autograd Hook": each bucket keeps a count of pending
+    gradients, every hook decrements it, the bucket is ready at zero.
+  * Section 2.3 / 3.2.1: AllReduce sums equally sized tensors over all
+    participants; DDP turns the sum into the average and writes it back to
+    the gradient tensors (the finalizing step described after Algorithm 1).
+  * Section 3.2.3, second caveat: parameters that take no part in an
+    iteration must not keep their bucket from becoming ready.  Here they
+    contribute zeros and receive zeros.
+  * Section 3.2.4: under no_sync, gradients of several backward passes
+    accumulate into the same tensor and are synchronized once afterwards.
+
+The method is an exact reorganisation of the plain definition
+
+    out_p[j] = (1/R) * sum_{r=0}^{R-1} g_{r,p}[j]
+
+so `mean_definition_f64` writes that definition out in float64, and the
+step-by-step functions (assign, pack, reduce, unpack) follow the paper's
+steps so that bucket indices and offsets can be compared bit for bit.
+`reduce_average` fixes what the definition leaves open: the sum runs over
+r = 0, 1, ..., R-1 in IEEE binary32 (round to nearest even), starts from
+the r = 0 value, is divided by float32(R), and is rounded once to the
+storage format.
+
+Pins (tests/test_oracle_*.py): the hand-derived Tiny assignment, maximal
+greedy-partition brute force, unique-tag round trips, integer-valued inputs
+against exact integer arithmetic, the float64 definition within the textbook
+summation bound, exhaustive 16-bit conversion checks against library
+conversions, the tiny linear-regression mean-gradient identity, the no_sync
+identity and hand-worked launch schedules.
+
+Not pinned by anything in the paper: absolute timings and the best bucket
+size (the paper's curves are figures that are not available) -- "parity
+unpinned" for those; they are measured, not checked.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+DT_FP32, DT_FP16, DT_BF16 = 0, 1, 2
+ESIZE = {DT_FP32: 4, DT_FP16: 2, DT_BF16: 2}
+STORAGE = {DT_FP32: np.float32, DT_FP16: np.float16, DT_BF16: np.uint16}
+CAP_WHOLE_MODEL = (1 << 64) - 1
+
+
+# --------------------------------------------------------------------------
+# storage formats
+# --------------------------------------------------------------------------
+def to_f32(x: np.ndarray, dtype: int) -> np.ndarray:
+    """Exact widening of a storage array to binary32."""
+    if dtype == DT_FP32:
+        return np.asarray(x, dtype=np.float32)
+    if dtype == DT_FP16:
+        return np.asarray(x, dtype=np.float16).astype(np.float32)
+    if dtype == DT_BF16:
+        bits = np.asarray(x, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+        return bits.view(np.float32)
+    raise ValueError(f"unknown dtype code {dtype}")
+
+
+def from_f32(y: np.ndarray, dtype: int) -> np.ndarray:
+    """Round binary32 to the storage format, to nearest, ties to even.
+    bf16 is the upper half of binary32: add 0x7FFF plus the lowest kept bit,
+    then drop the lower 16 bits; NaN stays NaN (quiet bit set)."""
+    y = np.asarray(y, dtype=np.float32)
+    if dtype == DT_FP32:
+        return y
+    if dtype == DT_FP16:
+        with np.errstate(over="ignore"):
+            return y.astype(np.float16)
+    if dtype == DT_BF16:
+        u = y.view(np.uint32).astype(np.uint64)
+        lsb = (u >> np.uint64(16)) & np.uint64(1)
+        rounded = ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint16)
+        nan = np.isnan(y)
+        quiet = ((u >> np.uint64(16)) | np.uint64(0x0040)).astype(np.uint16)
+        return np.where(nan, quiet, rounded).astype(np.uint16)
+    raise ValueError(f"unknown dtype code {dtype}")
+
+
+# --------------------------------------------------------------------------
+# bucket assignment  (Algorithm 1, constructor; Section 4.2)
+# --------------------------------------------------------------------------
+@dataclass
+class Bucket:
+    params: List[int] = field(default_factory=list)  # in fill order
+    elems: int = 0
+    dtype: int = DT_FP32
+
+    @property
+    def nbytes(self) -> int:
+        return self.elems * ESIZE[self.dtype]
+
+
+@dataclass
+class Assignment:
+    bucket_of: np.ndarray   # int32 [n]
+    offset_of: np.ndarray   # int64 [n], in elements from the bucket start
+    buckets: List[Bucket]
+    numel: np.ndarray       # int64 [n]
+    dtype: np.ndarray       # int32 [n]
+
+
+def assign_buckets(numel: Sequence[int], dtype: Sequence[int],
+                   cap_bytes: int) -> Assignment:
+    """Visit parameters n-1, n-2, ..., 0.  A parameter joins the open bucket
+    unless the bucket is non-empty and would then exceed cap_bytes, or holds
+    another element type; in that case the open bucket is closed first.  A
+    total equal to the cap fits.  Buckets are numbered in the order they are
+    opened, so bucket 0 holds the parameters registered last.  Offsets are
+    dense (no padding) and counted in elements."""
+    n = len(numel)
+    if n != len(dtype):
+        raise ValueError("numel and dtype differ in length")
+    bucket_of = np.full(n, -1, dtype=np.int32)
+    offset_of = np.zeros(n, dtype=np.int64)
+    buckets: List[Bucket] = []
+    cur: Optional[Bucket] = None
+    for i in range(n - 1, -1, -1):
+        size = int(numel[i]) * ESIZE[int(dtype[i])]
+        if cur is not None and cur.params and (
+                cur.nbytes + size > cap_bytes or cur.dtype != int(dtype[i])):
+            cur = None
+        if cur is None:
+            cur = Bucket(dtype=int(dtype[i]))
+            buckets.append(cur)
+        bucket_of[i] = len(buckets) - 1
+        offset_of[i] = cur.elems
+        cur.params.append(i)
+        cur.elems += int(numel[i])
+    return Assignment(bucket_of, offset_of, buckets,
+                      np.asarray(numel, dtype=np.int64),
+                      np.asarray(dtype, dtype=np.int32))
+
+
+# --------------------------------------------------------------------------
+# pack / reduce / unpack
+# --------------------------------------------------------------------------
+def pack_bucket(asg: Assignment, b: int, grads: Sequence[np.ndarray],
+                unused: Sequence[int] = ()) -> np.ndarray:
+    """flat[offset_of[i] + j] = grads[i][j] for every parameter i of bucket
+    b (Algorithm 1, autograd_hook: view = b_i.narrow(offset, size);
+    view.copy_(grad)).  Parameters listed in `unused` are not read and
+    their slots hold zeros."""
+    bk = asg.buckets[b]
+    flat = np.zeros(bk.elems, dtype=STORAGE[bk.dtype])
+    skip = set(int(i) for i in unused)
+    for i in bk.params:
+        if i in skip:
+            continue
+        off = int(asg.offset_of[i])
+        g = np.asarray(grads[i]).reshape(-1)
+        if g.size != int(asg.numel[i]) or g.dtype != STORAGE[bk.dtype]:
+            raise ValueError(f"gradient {i} has the wrong size or type")
+        flat[off:off + g.size] = g
+    return flat
+
+
+def reduce_average(flats: Sequence[np.ndarray], dtype: int) -> np.ndarray:
+    """Elementwise over the R replica copies of one bucket:
+    s = x_0; s = s + x_r for r = 1..R-1 (binary32); y = s / float32(R);
+    result = y rounded to the storage format."""
+    R = len(flats)
+    if R < 1:
+        raise ValueError("need at least one replica")
+    with np.errstate(over="ignore", invalid="ignore"):
+        s = to_f32(flats[0], dtype).copy()
+        for r in range(1, R):
+            s = s + to_f32(flats[r], dtype)
+        y = s / np.float32(R)
+    return from_f32(y.astype(np.float32), dtype)
+
+
+def unpack_bucket(asg: Assignment, b: int, avg: np.ndarray,
+                  outs: List[Optional[np.ndarray]]) -> None:
+    """outs[i][j] = avg[offset_of[i] + j]: the write-back of the averaged
+    bucket into the per-parameter gradient tensors (finalizing step)."""
+    bk = asg.buckets[b]
+    for i in bk.params:
+        off = int(asg.offset_of[i])
+        outs[i] = np.array(avg[off:off + int(asg.numel[i])], copy=True)
+
+
+# --------------------------------------------------------------------------
+# no_sync accumulation  (Section 3.2.4)
+# --------------------------------------------------------------------------
+def accumulate(acc: List[np.ndarray], micro: Sequence[Optional[np.ndarray]],
+               dtype: Sequence[int]) -> None:
+    """acc[i] <- round(acc[i] + micro[i]) for every parameter that produced
+    a gradient in this micro-step (micro[i] is not None).  The sum is formed
+    in binary32 and stored in the gradient's own format, because a gradient
+    tensor has its parameter's type."""
+    for i, m in enumerate(micro):
+        if m is None:
+            continue
+        d = int(dtype[i])
+        with np.errstate(over="ignore", invalid="ignore"):
+            acc[i] = from_f32(to_f32(acc[i], d) + to_f32(m, d), d)
+
+
+# --------------------------------------------------------------------------
+# ready marks and in-order launch  (Algorithm 1 hook; Sections 3.2.3, 4.2)
+# --------------------------------------------------------------------------
+def launch_schedule(asg: Assignment,
+                    ready_sequence: Sequence[int]) -> List[Tuple[int, int]]:
+    """Replay a sequence of ready marks.  Returns [(bucket, call)] in launch
+    order, where `call` is the position in ready_sequence of the mark that
+    made the launch possible, or len(ready_sequence) for buckets that only
+    the finalizing step launches (they still hold parameters that were never
+    marked).  A bucket is launched when its pending count is zero and every
+    lower-numbered bucket has been launched."""
+    nb = len(asg.buckets)
+    pending = [len(bk.params) for bk in asg.buckets]
+    seen = set()
+    log: List[Tuple[int, int]] = []
+    nxt = 0
+    for call, p in enumerate(ready_sequence):
+        p = int(p)
+        if p < 0 or p >= len(asg.bucket_of):
+            raise ValueError(f"parameter id {p} out of range")
+        if p in seen:
+            raise ValueError(f"parameter {p} marked ready twice")
+        seen.add(p)
+        pending[int(asg.bucket_of[p])] -= 1
+        while nxt < nb and pending[nxt] == 0:
+            log.append((nxt, call))
+            nxt += 1
+    while nxt < nb:
+        log.append((nxt, len(ready_sequence)))
+        nxt += 1
+    return log
+
+
+# --------------------------------------------------------------------------
+# the whole path
+# --------------------------------------------------------------------------
+def synchronize(numel: Sequence[int], dtype: Sequence[int], cap_bytes: int,
+                replica_grads: Sequence[Sequence[np.ndarray]],
+                ready_sequence: Optional[Sequence[int]] = None):
+    """One synchronization: assign, then per bucket in launch order pack the
+    R replica copies, reduce and average, and unpack.  `replica_grads[r][i]`
+    is replica r's gradient of parameter i.  Parameters missing from
+    `ready_sequence` (default: all are marked, in reverse registration
+    order) are reduced as zeros and are not read.
+    Returns (outs, assignment, launch_log)."""
+    n = len(numel)
+    R = len(replica_grads)
+    asg = assign_buckets(numel, dtype, cap_bytes)
+    if ready_sequence is None:
+        ready_sequence = list(range(n - 1, -1, -1))
+    marked = set(int(p) for p in ready_sequence)
+    unused = [i for i in range(n) if i not in marked]
+    log = launch_schedule(asg, ready_sequence)
+    outs: List[Optional[np.ndarray]] = [None] * n
+    for b, _ in log:
+        flats = [pack_bucket(asg, b, replica_grads[r], unused) for r in range(R)]
+        avg = reduce_average(flats, asg.buckets[b].dtype)
+        unpack_bucket(asg, b, avg, outs)
+    return outs, asg, log
+
+
+def mean_definition_f64(replica_grads: Sequence[Sequence[np.ndarray]],
+                        dtype: Sequence[int]) -> List[np.ndarray]:
+    """The plain definition, out_p = (1/R) sum_r g_{r,p}, in float64 and
+    without any bucketing."""
+    R = len(replica_grads)
+    outs = []
+    for i in range(len(replica_grads[0])):
+        acc = np.zeros(np.asarray(replica_grads[0][i]).size, dtype=np.float64)
+        for r in range(R):
+            acc += to_f32(replica_grads[r][i], int(dtype[i])).astype(np.float64).reshape(-1)
+        outs.append(acc / R)
+    return outs
