@@ -1,0 +1,229 @@
+/*
+ * ddp_gfx950 -- bucketed gradient synchronization for one MI355X (gfx950).
+ *
+ * C ABI of the data-parallel hot path of "PyTorch Distributed: Experiences on
+ * Accelerating Data Parallel Training" (arXiv 2006.15704).  The R training
+ * processes of the paper are stood in for by R replica copies of every
+ * gradient, all resident in one GPU's HBM; the AllReduce of a bucket
+ * (Section 2.3: every participant provides an equally sized tensor and
+ * collects the global sum) becomes an R-way sum kernel, followed by the
+ * division by R that turns the sum into DDP's average (Section 3.2.1).
+ *
+ * Conventions
+ *   - Every function returns an int32_t status: >= 0 success (DDP_OK unless
+ *     stated otherwise), < 0 one of the DDP_ERR_* codes.  Nothing aborts,
+ *     throws or blocks forever.  ddp_last_error() returns a text for the most
+ *     recent failure on that context (or, with ctx == NULL, of the most recent
+ *     failed ddp_create on this thread).
+ *   - "device pointer" = address in the GPU's global memory; "host pointer" =
+ *     ordinary process memory.  Host arrays passed in are copied before the
+ *     call returns.  Gradient memory is owned by the caller and borrowed until
+ *     ddp_destroy; bucket storage is owned by the library.
+ *   - Streams are hipStream_t values passed as void* (NULL = the null stream).
+ *     The library creates no streams of its own and never changes priorities.
+ *   - A context is not thread-safe (the paper's hooks fire from one autograd
+ *     thread).  Different contexts may be used from different threads.
+ *   - All compute calls are asynchronous with respect to the host unless
+ *     stated otherwise.
+ */
+#ifndef DDP_GFX950_H
+#define DDP_GFX950_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ddp_ctx ddp_ctx;
+
+/* status codes */
+#define DDP_OK                  0
+#define DDP_ERR_ARG            -1  /* invalid argument (null, out of range, unknown code) */
+#define DDP_ERR_STATE          -2  /* call out of order (e.g. mark before build, register twice) */
+#define DDP_ERR_ALREADY_READY  -3  /* parameter already marked ready in this iteration */
+#define DDP_ERR_HIP            -4  /* a HIP runtime call failed; text in ddp_last_error */
+#define DDP_ERR_NO_DEVICE      -5  /* compute requested on a plan-only context */
+#define DDP_ERR_UNSUPPORTED    -6  /* combination not supported (e.g. R above DDP_MAX_REPLICAS) */
+
+/* element types of gradients */
+#define DDP_FP32 0
+#define DDP_FP16 1
+#define DDP_BF16 2
+
+#define DDP_MAX_REPLICAS 64
+
+/* device == DDP_DEVICE_NONE makes a plan-only context: bucket assignment and
+ * the ready/launch state machine run and can be inspected, no device memory is
+ * touched, nothing is computed, and ddp_no_sync_accumulate / ddp_synchronize /
+ * ddp_synth_backward return DDP_ERR_NO_DEVICE.  It exists so that the host
+ * logic can be tested on machines without a GPU; it is not a CPU fallback. */
+#define DDP_DEVICE_NONE (-1)
+
+/* ddp_build_buckets cap meaning "one bucket per run of equal element type" */
+#define DDP_CAP_WHOLE_MODEL UINT64_MAX
+
+/* options for ddp_set_option (set before ddp_build_buckets unless noted) */
+#define DDP_OPT_PIPELINE       1  /* DDP_PIPELINE_STAGED (default) or DDP_PIPELINE_FUSED */
+#define DDP_OPT_WRITE_ALL      2  /* 0 (default): the average is written to replica 0's gradient
+                                     tensors only (one rank's view); 1: to all R replicas' tensors */
+#define DDP_OPT_TIMING         3  /* 0/1, any time: bracket every kernel launch with HIP events
+                                     on its stream; read back with ddp_get_kernel_times */
+#define DDP_OPT_REDUCE_BLOCKS  4  /* any time: upper bound on thread blocks per reduce launch
+                                     (0 = one block per tile) */
+#define DDP_OPT_NONTEMPORAL    5  /* any time: 1 (default) = read-once inputs are loaded with the
+                                     non-temporal hint, 0 = plain loads */
+
+/* DDP_PIPELINE_STAGED follows the paper's data flow literally: gradients are
+ * copied into flat per-replica bucket buffers (Algorithm 1, autograd_hook),
+ * the bucket is reduced, and the averaged bucket is copied back to the
+ * gradient tensors by the finalizing step.  DDP_PIPELINE_FUSED computes the
+ * same values in one pass per bucket: the kernel gathers each replica's
+ * gradients through the bucket's segment table, sums and averages in
+ * registers, and writes straight to the gradient tensors; the flat bucket is
+ * virtual.  Bucket assignment, launch order and results are identical. */
+#define DDP_PIPELINE_STAGED 0
+#define DDP_PIPELINE_FUSED  1
+
+/* kernel kinds for ddp_get_kernel_times */
+#define DDP_K_PACK       0
+#define DDP_K_REDUCE     1   /* staged reduce, or the fused gather-reduce-scatter */
+#define DDP_K_UNPACK     2
+#define DDP_K_ACCUMULATE 3
+
+/* Create a context for R >= 1 replicas on HIP device `device` (or
+ * DDP_DEVICE_NONE).  `reduce_stream` is the dedicated stream the bucket
+ * kernels run on (Section 3.3: communication gets its own streams so that it
+ * does not block computation); `backward_stream` is the stream on which the
+ * caller produces gradients.  They may be equal.  *out receives the handle. */
+int32_t ddp_create(ddp_ctx** out, int32_t R, int32_t device,
+                   void* reduce_stream, void* backward_stream);
+
+/* Waits for the context's outstanding work, frees library-owned memory and
+ * events.  Gradient memory is untouched. */
+int32_t ddp_destroy(ddp_ctx* ctx);
+
+const char* ddp_last_error(const ddp_ctx* ctx);
+
+int32_t ddp_set_option(ddp_ctx* ctx, int32_t option, int64_t value);
+
+/* Algorithm 1, constructor loop over net.parameters(): registers n parameters
+ * in registration order (index = position in net.parameters()).
+ *   numel[n]      host, element count of each gradient (0 allowed)
+ *   dtype[n]      host, DDP_FP32 / DDP_FP16 / DDP_BF16
+ *   grad_ptrs     host array of R*n device pointers, row-major [r][i]: replica
+ *                 r's gradient of parameter i; contiguous, aligned at least to
+ *                 its element size (16-byte alignment is exploited, not
+ *                 required).  Ignored (may be NULL) on a plan-only context.
+ * Errors: n <= 0, null arrays or pointers, unknown dtype -> DDP_ERR_ARG;
+ * second call -> DDP_ERR_STATE. */
+int32_t ddp_register_params(ddp_ctx* ctx, int32_t n, const int64_t* numel,
+                            const int32_t* dtype, void* const* grad_ptrs);
+
+/* Algorithm 1, constructor: buckets are filled with the parameters taken in
+ * reverse registration order, under the size cap `cap_bytes` (Section 4.2,
+ * bucket_cap_mb; 0 = every gradient alone, Section 5.2; DDP_CAP_WHOLE_MODEL =
+ * no cap).  Parameters are visited n-1 ... 0; a parameter that would push a
+ * non-empty bucket past the cap, or whose element type differs from the
+ * bucket's, closes it first, so a bucket exceeds the cap only if it holds a
+ * single parameter.  Offsets inside a bucket are dense.  Allocates the flat
+ * bucket storage (staged pipeline) and the device segment tables.
+ * Returns the number of buckets (>= 1).  Errors: before register or called
+ * twice -> DDP_ERR_STATE; allocation failure -> DDP_ERR_HIP. */
+int32_t ddp_build_buckets(ddp_ctx* ctx, uint64_t cap_bytes);
+
+/* bucket_of[n], elem_offset[n] (host, caller-allocated): bucket index and
+ * element offset inside the bucket for every parameter. */
+int32_t ddp_get_assignment(const ddp_ctx* ctx, int32_t* bucket_of, int64_t* elem_offset);
+
+/* Element count, number of parameters and element type of bucket b. */
+int32_t ddp_get_bucket_info(const ddp_ctx* ctx, int32_t b, int64_t* elems,
+                            int32_t* n_params, int32_t* dtype);
+
+/* Staged pipeline only: device address of bucket b's flat buffer of replica r
+ * (0 <= r < R), or of the averaged bucket (r == -1).  For tests. */
+int32_t ddp_get_bucket_ptr(const ddp_ctx* ctx, int32_t b, int32_t r, void** ptr);
+
+/* Algorithm 1, autograd_hook(param_index), with the pending counts of
+ * Section 4.2: records that all R replica gradients of `param_id` have been
+ * produced by work already enqueued on backward_stream, decrements the
+ * bucket's pending count, and launches on reduce_stream, in bucket order,
+ * every bucket that is complete and whose predecessors have all been launched
+ * (Section 3.2.3: no bucket i+1 before bucket i).  A launch first makes
+ * reduce_stream wait for backward_stream's work enqueued so far, then copies
+ * the bucket's gradients into the flat buffers and reduces them (staged), or
+ * runs the one-pass kernel (fused).  Returns after enqueueing.
+ * Errors: buckets not built -> DDP_ERR_STATE; id out of range -> DDP_ERR_ARG;
+ * marked twice in one iteration -> DDP_ERR_ALREADY_READY (no state change). */
+int32_t ddp_mark_ready(ddp_ctx* ctx, int32_t param_id);
+
+/* Same as calling ddp_mark_ready for ids[0..count) in order; stops at the
+ * first error and returns it.  Saves per-call binding overhead. */
+int32_t ddp_mark_ready_many(ddp_ctx* ctx, const int32_t* ids, int32_t count);
+
+/* The finalizing step described after Algorithm 1 (wait for the reductions and
+ * write the averages back to the gradients), plus Section 3.2.3's handling of
+ * absent gradients: parameters not marked in this iteration are treated as
+ * ready with all-zero gradients (their memory is not read) and receive zeros;
+ * remaining buckets are launched in order; the averaged buckets are copied
+ * into the gradient tensors; backward_stream is made to wait for all of it, so
+ * work enqueued on backward_stream afterwards sees the averaged gradients;
+ * pending counts are replenished for the next iteration (Section 4.2).
+ * Host-asynchronous: use ddp_synchronize for host-visible completion. */
+int32_t ddp_finalize_backward(ddp_ctx* ctx);
+
+/* Blocks the host until everything enqueued by this context has finished. */
+int32_t ddp_synchronize(ddp_ctx* ctx);
+
+/* Launch log of the running iteration (which == 0: buckets launched since the
+ * last ddp_finalize_backward) or of the iteration closed by the latest
+ * ddp_finalize_backward (which == 1).  bucket_ids[i] is the i-th bucket
+ * launched; after_call[i] is the 0-based index of the ready mark that
+ * triggered the launch, or the total number of marks for buckets launched by
+ * the finalizing step.  Arrays (host, may be NULL) hold `cap` entries; *n
+ * receives the number of launches. */
+int32_t ddp_get_launch_log(const ddp_ctx* ctx, int32_t which, int32_t* bucket_ids,
+                           int32_t* after_call, int32_t cap, int32_t* n);
+
+/* Section 3.2.4, no_sync: adds one micro-step's gradients into the registered
+ * gradient tensors, grad[r][i] += micro[r][i] (sum in fp32, stored in the
+ * gradient's type), on backward_stream.  No ready marks, no reduction.
+ *   micro_grad_ptrs  host array of R*n device pointers, [r][i]; a NULL entry
+ *                    means parameter i produced no gradient in this micro-step.
+ * The micro buffers may be reused once work enqueued on backward_stream after
+ * this call has started (stream order). */
+int32_t ddp_no_sync_accumulate(ddp_ctx* ctx, void* const* micro_grad_ptrs);
+
+/* used[n] (host): 1 if the parameter received a gradient through
+ * ddp_no_sync_accumulate or a ready mark, else 0 -- since the last finalize
+ * (which == 0) or in the synchronization closed by the latest finalize
+ * (which == 1).  Section 3.2.4: participation information accumulates across
+ * no_sync iterations and serves when the next synchronization takes place. */
+int32_t ddp_get_used_map(const ddp_ctx* ctx, int32_t which, uint8_t* used);
+
+/* Synthetic backward pass (stands in for the autograd engine, Section 3.2.3):
+ * for k = 0..count-1, enqueue on backward_stream a kernel that busy-waits
+ * delay_ns[k] nanoseconds (bounded) and then, if src_ptrs != NULL, copies
+ * src_ptrs[r*n + order[k]] into the registered gradient of parameter order[k]
+ * for every replica r ("the gradient is produced"); then call
+ * ddp_mark_ready(order[k]).  delay_ns may be NULL (no delay).  With
+ * mark == 0 the ready marks are left out (backward alone, for timing). */
+int32_t ddp_synth_backward(ddp_ctx* ctx, const int32_t* order, int32_t count,
+                           const int64_t* delay_ns, void* const* src_ptrs,
+                           int32_t mark);
+
+/* With DDP_OPT_TIMING on: durations in milliseconds of the launches of `kind`
+ * since the option was last set, in launch order.  Call after
+ * ddp_synchronize.  ms holds `cap` entries; *n receives the count available.
+ * ids (may be NULL) receives the bucket index of each launch (-1 if the launch
+ * covered several buckets). */
+int32_t ddp_get_kernel_times(ddp_ctx* ctx, int32_t kind, float* ms, int32_t* ids,
+                             int32_t cap, int32_t* n);
+
+/* Library version string. */
+const char* ddp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDP_GFX950_H */

@@ -1,0 +1,639 @@
+// C ABI of the library: context, registration, bucket building, ready marks,
+// finalize, no_sync accumulation and the synthetic backward emitter.  Host
+// code only; the kernels are in ddp_kernels.hip.
+#include "../../include/ddp_gfx950.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "bucket_plan.h"
+#include "ddp_kernels.h"
+
+namespace {
+
+thread_local std::string g_create_error;
+
+struct TimedLaunch {
+    int32_t kind;
+    int32_t bucket;
+    hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct ddp_ctx {
+    int32_t R = 0;
+    int32_t device = DDP_DEVICE_NONE;
+    bool plan_only = true;
+    hipStream_t reduce = nullptr, backward = nullptr;
+    int64_t wall_clock_khz = 100000;
+
+    // options
+    int32_t pipeline = DDP_PIPELINE_STAGED;
+    int32_t write_all = 0;
+    int32_t timing = 0;
+    int32_t reduce_blocks = 0;
+    int32_t nontemporal = 1;
+
+    bool registered = false, built = false;
+    ddp::BucketPlan plan;
+    ddp::ReadyTracker tracker;
+    std::vector<void*> grad_ptrs;            // [R][n], registration order
+
+    // device memory owned by the library
+    char* slabs = nullptr;                   // R input slabs followed by the output slab
+    int64_t slab_stride = 0;
+    std::vector<int64_t> bucket_slab_off;    // byte offset of each bucket inside a slab
+    std::vector<int64_t> bucket_vecs;        // 16-byte vectors per bucket (padded)
+    std::vector<int64_t> h_tile0;            // [G+1]
+    void* d_tables = nullptr;                // one allocation holding all segment tables
+    ddp::SegTables tables{};
+    uint8_t* d_unused = nullptr;
+    uint8_t* h_unused = nullptr;             // pinned
+    void** d_micro = nullptr;
+    void** h_micro = nullptr;                // pinned
+    void** d_emit = nullptr;
+    void** h_emit = nullptr;                 // pinned
+    int64_t emit_cap = 0;                    // pointers
+    std::vector<hipEvent_t> ev_ready;        // one per bucket
+    hipEvent_t ev_done = nullptr, ev_flags = nullptr, ev_micro = nullptr, ev_emit = nullptr;
+    bool flags_in_flight = false, micro_in_flight = false, emit_in_flight = false;
+
+    std::vector<std::pair<int32_t, int32_t>> log_running, log_closed;
+    std::vector<uint8_t> used_running, used_closed;
+    std::vector<TimedLaunch> timed;
+    std::string err;
+};
+
+namespace {
+
+int32_t fail(ddp_ctx* c, int32_t code, const std::string& msg) {
+    if (c) c->err = msg;
+    else g_create_error = msg;
+    return code;
+}
+
+#define HIPCHK(c, expr)                                                                    \
+    do {                                                                                   \
+        hipError_t e_ = (expr);                                                            \
+        if (e_ != hipSuccess)                                                              \
+            return fail((c), DDP_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+ddp::Scale make_scale(int R) {
+    ddp::Scale sc;
+    sc.div = static_cast<float>(R);
+    sc.mul = 1.0f / static_cast<float>(R);
+    sc.use_mul = (R & (R - 1)) == 0;   // power of two: the reciprocal is exact, same bits as dividing
+    return sc;
+}
+
+int32_t timed_begin(ddp_ctx* c, int32_t kind, int32_t bucket, hipStream_t s, size_t* slot) {
+    *slot = static_cast<size_t>(-1);
+    if (!c->timing) return DDP_OK;
+    TimedLaunch t{kind, bucket, nullptr, nullptr};
+    HIPCHK(c, hipEventCreate(&t.start));
+    HIPCHK(c, hipEventCreate(&t.stop));
+    HIPCHK(c, hipEventRecord(t.start, s));
+    c->timed.push_back(t);
+    *slot = c->timed.size() - 1;
+    return DDP_OK;
+}
+
+int32_t timed_end(ddp_ctx* c, size_t slot, hipStream_t s) {
+    if (slot == static_cast<size_t>(-1)) return DDP_OK;
+    HIPCHK(c, hipEventRecord(c->timed[slot].stop, s));
+    return DDP_OK;
+}
+
+void drop_timed(ddp_ctx* c) {
+    for (TimedLaunch& t : c->timed) {
+        if (t.start) (void)hipEventDestroy(t.start);
+        if (t.stop) (void)hipEventDestroy(t.stop);
+    }
+    c->timed.clear();
+}
+
+// Enqueue everything bucket b needs on the reduce stream.
+int32_t launch_bucket(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t call_index) {
+    c->log_running.emplace_back(b, call_index);
+    if (c->plan_only) return DDP_OK;
+    const ddp::BucketInfo& bk = c->plan.buckets[b];
+    const int seg_begin = bk.seg_begin;
+    const int seg_end = seg_begin + static_cast<int>(bk.params.size());
+    const int64_t tile_base = c->h_tile0[seg_begin];
+    const int64_t ntiles = c->h_tile0[seg_end] - tile_base;
+    if (c->backward != c->reduce) {
+        HIPCHK(c, hipEventRecord(c->ev_ready[b], c->backward));
+        HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_ready[b], 0));
+    }
+    const ddp::Scale sc = make_scale(c->R);
+    size_t slot;
+    int32_t rc;
+    if (c->pipeline == DDP_PIPELINE_STAGED) {
+        char* in0 = c->slabs + c->bucket_slab_off[b];
+        char* out = c->slabs + static_cast<int64_t>(c->R) * c->slab_stride + c->bucket_slab_off[b];
+        if ((rc = timed_begin(c, DDP_K_PACK, b, c->reduce, &slot)) != DDP_OK) return rc;
+        HIPCHK(c, ddp::launch_pack(c->tables, seg_begin, seg_end, tile_base, ntiles, c->slabs,
+                                   c->slab_stride, c->R, d_unused, c->reduce));
+        if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
+        if ((rc = timed_begin(c, DDP_K_REDUCE, b, c->reduce, &slot)) != DDP_OK) return rc;
+        HIPCHK(c, ddp::launch_flat_reduce(bk.dtype, in0, c->slab_stride, out, c->bucket_vecs[b],
+                                          c->R, sc, c->reduce_blocks, c->nontemporal != 0,
+                                          c->reduce));
+        if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
+    } else {
+        if ((rc = timed_begin(c, DDP_K_REDUCE, b, c->reduce, &slot)) != DDP_OK) return rc;
+        HIPCHK(c, ddp::launch_fused_reduce(bk.dtype, c->tables, seg_begin, seg_end, tile_base,
+                                           ntiles, c->R, c->write_all ? c->R : 1, d_unused, sc,
+                                           c->nontemporal != 0, c->reduce));
+        if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
+    }
+    return DDP_OK;
+}
+
+void release_device(ddp_ctx* c) {
+    if (c->plan_only) return;
+    (void)hipSetDevice(c->device);
+    if (c->reduce) (void)hipStreamSynchronize(c->reduce);
+    if (c->backward) (void)hipStreamSynchronize(c->backward);
+    if (!c->reduce || !c->backward) (void)hipStreamSynchronize(nullptr);
+    drop_timed(c);
+    for (hipEvent_t e : c->ev_ready) (void)hipEventDestroy(e);
+    c->ev_ready.clear();
+    for (hipEvent_t* e : {&c->ev_done, &c->ev_flags, &c->ev_micro, &c->ev_emit})
+        if (*e) { (void)hipEventDestroy(*e); *e = nullptr; }
+    if (c->slabs) (void)hipFree(c->slabs);
+    if (c->d_tables) (void)hipFree(c->d_tables);
+    if (c->d_unused) (void)hipFree(c->d_unused);
+    if (c->d_micro) (void)hipFree(c->d_micro);
+    if (c->d_emit) (void)hipFree(c->d_emit);
+    if (c->h_unused) (void)hipHostFree(c->h_unused);
+    if (c->h_micro) (void)hipHostFree(c->h_micro);
+    if (c->h_emit) (void)hipHostFree(c->h_emit);
+    c->slabs = nullptr; c->d_tables = nullptr; c->d_unused = nullptr; c->d_micro = nullptr;
+    c->d_emit = nullptr; c->h_unused = nullptr; c->h_micro = nullptr; c->h_emit = nullptr;
+}
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+const char* ddp_version(void) { return "ddp_gfx950 0.1"; }
+
+const char* ddp_last_error(const ddp_ctx* ctx) {
+    return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+int32_t ddp_create(ddp_ctx** out, int32_t R, int32_t device, void* reduce_stream,
+                   void* backward_stream) {
+    if (!out) return fail(nullptr, DDP_ERR_ARG, "ddp_create: out is null");
+    *out = nullptr;
+    if (R < 1) return fail(nullptr, DDP_ERR_ARG, "ddp_create: R must be at least 1");
+    if (R > DDP_MAX_REPLICAS) return fail(nullptr, DDP_ERR_UNSUPPORTED, "ddp_create: R above DDP_MAX_REPLICAS");
+    if (device < DDP_DEVICE_NONE) return fail(nullptr, DDP_ERR_ARG, "ddp_create: bad device");
+    ddp_ctx* c = new ddp_ctx();
+    c->R = R;
+    c->device = device;
+    c->plan_only = device == DDP_DEVICE_NONE;
+    c->reduce = static_cast<hipStream_t>(reduce_stream);
+    c->backward = static_cast<hipStream_t>(backward_stream);
+    if (!c->plan_only) {
+        int count = 0;
+        hipError_t e = hipGetDeviceCount(&count);
+        if (e != hipSuccess || device >= count) {
+            delete c;
+            return fail(nullptr, DDP_ERR_HIP, "ddp_create: no such HIP device (the library needs a GPU; "
+                                              "use DDP_DEVICE_NONE only for plan inspection)");
+        }
+        e = hipSetDevice(device);
+        int khz = 0;
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device);
+        if (e == hipSuccess && khz > 0) c->wall_clock_khz = khz;
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_done, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_flags, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_micro, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_emit, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            std::string msg = std::string("ddp_create: ") + hipGetErrorString(e);
+            release_device(c);
+            delete c;
+            return fail(nullptr, DDP_ERR_HIP, msg);
+        }
+    }
+    *out = c;
+    return DDP_OK;
+}
+
+int32_t ddp_destroy(ddp_ctx* ctx) {
+    if (!ctx) return DDP_ERR_ARG;
+    release_device(ctx);
+    delete ctx;
+    return DDP_OK;
+}
+
+int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
+    if (!c) return DDP_ERR_ARG;
+    switch (option) {
+        case DDP_OPT_PIPELINE:
+            if (c->built) return fail(c, DDP_ERR_STATE, "pipeline must be chosen before ddp_build_buckets");
+            if (value != DDP_PIPELINE_STAGED && value != DDP_PIPELINE_FUSED)
+                return fail(c, DDP_ERR_ARG, "unknown pipeline");
+            c->pipeline = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_WRITE_ALL:
+            if (c->built) return fail(c, DDP_ERR_STATE, "write-all must be chosen before ddp_build_buckets");
+            c->write_all = value != 0;
+            return DDP_OK;
+        case DDP_OPT_TIMING:
+            if (!c->plan_only) {
+                (void)hipSetDevice(c->device);
+                drop_timed(c);
+            }
+            c->timing = value != 0 && !c->plan_only;
+            return DDP_OK;
+        case DDP_OPT_REDUCE_BLOCKS:
+            if (value < 0 || value > (1 << 30)) return fail(c, DDP_ERR_ARG, "bad block bound");
+            c->reduce_blocks = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_NONTEMPORAL:
+            c->nontemporal = value != 0;
+            return DDP_OK;
+        default:
+            return fail(c, DDP_ERR_ARG, "unknown option");
+    }
+}
+
+int32_t ddp_register_params(ddp_ctx* c, int32_t n, const int64_t* numel, const int32_t* dtype,
+                            void* const* grad_ptrs) {
+    if (!c) return DDP_ERR_ARG;
+    if (c->registered) return fail(c, DDP_ERR_STATE, "ddp_register_params called twice");
+    if (n <= 0 || !numel || !dtype) return fail(c, DDP_ERR_ARG, "ddp_register_params: n <= 0 or null array");
+    if (!c->plan_only && !grad_ptrs) return fail(c, DDP_ERR_ARG, "ddp_register_params: grad_ptrs is null");
+    for (int32_t i = 0; i < n; ++i) {
+        if (numel[i] < 0) return fail(c, DDP_ERR_ARG, "ddp_register_params: negative numel");
+        if (dtype[i] != DDP_FP32 && dtype[i] != DDP_FP16 && dtype[i] != DDP_BF16)
+            return fail(c, DDP_ERR_ARG, "ddp_register_params: unknown dtype");
+    }
+    if (!c->plan_only) {
+        for (int32_t r = 0; r < c->R; ++r)
+            for (int32_t i = 0; i < n; ++i) {
+                const void* p = grad_ptrs[static_cast<int64_t>(r) * n + i];
+                if (numel[i] > 0 && !p) return fail(c, DDP_ERR_ARG, "ddp_register_params: null gradient pointer");
+                if (reinterpret_cast<uintptr_t>(p) % static_cast<uintptr_t>(ddp::elem_size(dtype[i])) != 0)
+                    return fail(c, DDP_ERR_ARG, "ddp_register_params: gradient pointer not aligned to its element size");
+            }
+        c->grad_ptrs.assign(grad_ptrs, grad_ptrs + static_cast<int64_t>(c->R) * n);
+    }
+    c->plan.params.resize(n);
+    for (int32_t i = 0; i < n; ++i) {
+        c->plan.params[i].numel = numel[i];
+        c->plan.params[i].dtype = dtype[i];
+    }
+    c->registered = true;
+    return DDP_OK;
+}
+
+int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->registered) return fail(c, DDP_ERR_STATE, "ddp_build_buckets before ddp_register_params");
+    if (c->built) return fail(c, DDP_ERR_STATE, "ddp_build_buckets called twice");
+    c->plan.assign(cap_bytes);
+    c->tracker.reset(c->plan);
+    const int32_t n = static_cast<int32_t>(c->plan.params.size());
+    const int32_t nb = static_cast<int32_t>(c->plan.buckets.size());
+    c->used_running.assign(n, 0);
+    c->used_closed.assign(n, 0);
+
+    if (!c->plan_only) {
+        // slab layout: bucket bases aligned to 256 bytes, lengths padded to 16
+        c->bucket_slab_off.resize(nb);
+        c->bucket_vecs.resize(nb);
+        int64_t off = 0;
+        for (int32_t b = 0; b < nb; ++b) {
+            c->bucket_slab_off[b] = off;
+            const int64_t bytes = static_cast<int64_t>(c->plan.buckets[b].bytes());
+            c->bucket_vecs[b] = (bytes + 15) / 16;
+            off = round_up(off + c->bucket_vecs[b] * 16, 256);
+        }
+        c->slab_stride = round_up(off > 0 ? off : 256, 4096);
+
+        // segment tables in bucket-major fill order
+        std::vector<int64_t> numel(n), flat_byte(n);
+        std::vector<int32_t> param(n), dtype(n);
+        c->h_tile0.assign(n + 1, 0);
+        for (int32_t b = 0; b < nb; ++b) {
+            const ddp::BucketInfo& bk = c->plan.buckets[b];
+            for (size_t k = 0; k < bk.params.size(); ++k) {
+                const int32_t i = bk.params[k];
+                const int32_t g = bk.seg_begin + static_cast<int32_t>(k);
+                const ddp::ParamInfo& p = c->plan.params[i];
+                numel[g] = p.numel;
+                flat_byte[g] = c->bucket_slab_off[b] + p.offset * ddp::elem_size(p.dtype);
+                param[g] = i;
+                dtype[g] = p.dtype;
+                c->h_tile0[g + 1] = c->h_tile0[g] + ddp::tiles_for(p.numel, ddp::elem_size(p.dtype));
+            }
+        }
+        if (c->h_tile0[n] >= (int64_t(1) << 31)) {
+            c->built = false;
+            return fail(c, DDP_ERR_UNSUPPORTED, "model too large for one launch grid");
+        }
+        HIPCHK(c, hipSetDevice(c->device));
+        // one allocation for all tables: numel, flat_byte, tile0, grad pointers, param, dtype
+        const int64_t R = c->R;
+        const size_t bytes = sizeof(int64_t) * (n + n + (n + 1)) + sizeof(void*) * R * n +
+                             sizeof(int32_t) * (n + n);
+        std::vector<char> host(bytes);
+        char* h = host.data();
+        size_t at = 0;
+        auto put = [&](const void* src, size_t len) { std::memcpy(h + at, src, len); size_t o = at; at += len; return o; };
+        const size_t o_numel = put(numel.data(), sizeof(int64_t) * n);
+        const size_t o_flat = put(flat_byte.data(), sizeof(int64_t) * n);
+        const size_t o_tile0 = put(c->h_tile0.data(), sizeof(int64_t) * (n + 1));
+        std::vector<void*> grad(static_cast<size_t>(R) * n);
+        for (int64_t r = 0; r < R; ++r)
+            for (int32_t g = 0; g < n; ++g) grad[r * n + g] = c->grad_ptrs[r * n + param[g]];
+        const size_t o_grad = put(grad.data(), sizeof(void*) * R * n);
+        const size_t o_param = put(param.data(), sizeof(int32_t) * n);
+        const size_t o_dtype = put(dtype.data(), sizeof(int32_t) * n);
+        HIPCHK(c, hipMalloc(&c->d_tables, bytes));
+        HIPCHK(c, hipMemcpy(c->d_tables, h, bytes, hipMemcpyHostToDevice));
+        char* d = static_cast<char*>(c->d_tables);
+        c->tables.numel = reinterpret_cast<const int64_t*>(d + o_numel);
+        c->tables.flat_byte = reinterpret_cast<const int64_t*>(d + o_flat);
+        c->tables.tile0 = reinterpret_cast<const int64_t*>(d + o_tile0);
+        c->tables.grad = reinterpret_cast<void* const*>(d + o_grad);
+        c->tables.param = reinterpret_cast<const int32_t*>(d + o_param);
+        c->tables.dtype = reinterpret_cast<const int32_t*>(d + o_dtype);
+        c->tables.G = n;
+
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_unused), static_cast<size_t>(n)));
+        HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_unused), static_cast<size_t>(n), hipHostMallocDefault));
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_micro), sizeof(void*) * R * n));
+        HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_micro), sizeof(void*) * R * n, hipHostMallocDefault));
+        c->ev_ready.resize(nb, nullptr);
+        for (int32_t b = 0; b < nb; ++b)
+            HIPCHK(c, hipEventCreateWithFlags(&c->ev_ready[b], hipEventDisableTiming));
+        if (c->pipeline == DDP_PIPELINE_STAGED) {
+            const size_t total = static_cast<size_t>(c->slab_stride) * static_cast<size_t>(R + 1);
+            HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->slabs), total));
+            HIPCHK(c, hipMemset(c->slabs, 0, total));
+        }
+        HIPCHK(c, hipDeviceSynchronize());
+    }
+    c->built = true;
+    return nb;
+}
+
+int32_t ddp_get_assignment(const ddp_ctx* c, int32_t* bucket_of, int64_t* elem_offset) {
+    if (!c || !bucket_of || !elem_offset) return DDP_ERR_ARG;
+    if (!c->built) return DDP_ERR_STATE;
+    for (size_t i = 0; i < c->plan.params.size(); ++i) {
+        bucket_of[i] = c->plan.params[i].bucket;
+        elem_offset[i] = c->plan.params[i].offset;
+    }
+    return DDP_OK;
+}
+
+int32_t ddp_get_bucket_info(const ddp_ctx* c, int32_t b, int64_t* elems, int32_t* n_params,
+                            int32_t* dtype) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->built) return DDP_ERR_STATE;
+    if (b < 0 || b >= static_cast<int32_t>(c->plan.buckets.size())) return DDP_ERR_ARG;
+    const ddp::BucketInfo& bk = c->plan.buckets[b];
+    if (elems) *elems = bk.elems;
+    if (n_params) *n_params = static_cast<int32_t>(bk.params.size());
+    if (dtype) *dtype = bk.dtype;
+    return DDP_OK;
+}
+
+int32_t ddp_get_bucket_ptr(const ddp_ctx* c, int32_t b, int32_t r, void** ptr) {
+    if (!c || !ptr) return DDP_ERR_ARG;
+    if (!c->built) return DDP_ERR_STATE;
+    if (c->plan_only) return DDP_ERR_NO_DEVICE;
+    if (c->pipeline != DDP_PIPELINE_STAGED || !c->slabs) return DDP_ERR_STATE;
+    if (b < 0 || b >= static_cast<int32_t>(c->plan.buckets.size()) || r < -1 || r >= c->R) return DDP_ERR_ARG;
+    const int64_t slab = r < 0 ? c->R : r;
+    *ptr = c->slabs + slab * c->slab_stride + c->bucket_slab_off[b];
+    return DDP_OK;
+}
+
+int32_t ddp_mark_ready(ddp_ctx* c, int32_t param_id) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready before ddp_build_buckets");
+    std::vector<int32_t> launch;
+    const int rc = c->tracker.mark(param_id, launch);
+    if (rc == -1) return fail(c, DDP_ERR_ARG, "ddp_mark_ready: parameter id out of range");
+    if (rc == -2) return fail(c, DDP_ERR_ALREADY_READY, "ddp_mark_ready: parameter already marked in this iteration");
+    c->used_running[param_id] = 1;
+    if (!launch.empty() && !c->plan_only) HIPCHK(c, hipSetDevice(c->device));
+    for (int32_t b : launch) {
+        const int32_t st = launch_bucket(c, b, nullptr, c->tracker.marks() - 1);
+        if (st != DDP_OK) return st;
+    }
+    return DDP_OK;
+}
+
+int32_t ddp_mark_ready_many(ddp_ctx* c, const int32_t* ids, int32_t count) {
+    if (!c || (count > 0 && !ids) || count < 0) return DDP_ERR_ARG;
+    for (int32_t k = 0; k < count; ++k) {
+        const int32_t st = ddp_mark_ready(c, ids[k]);
+        if (st != DDP_OK) return st;
+    }
+    return DDP_OK;
+}
+
+int32_t ddp_finalize_backward(ddp_ctx* c) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_finalize_backward before ddp_build_buckets");
+    const int32_t n = static_cast<int32_t>(c->plan.params.size());
+    const int32_t marks = c->tracker.marks();
+    std::vector<int32_t> launch;
+    c->tracker.drain(launch);
+    const uint8_t* flags = nullptr;
+    if (!c->plan_only) {
+        HIPCHK(c, hipSetDevice(c->device));
+        if (marks < n) {
+            // Parameters never marked: reduce as zeros without reading them.
+            // Every bucket launched before this point was complete, so only
+            // the buckets in `launch` can contain such parameters.
+            if (c->flags_in_flight) HIPCHK(c, hipEventSynchronize(c->ev_flags));
+            for (int32_t i = 0; i < n; ++i) c->h_unused[i] = c->tracker.marked(i) ? 0 : 1;
+            HIPCHK(c, hipMemcpyAsync(c->d_unused, c->h_unused, static_cast<size_t>(n),
+                                     hipMemcpyHostToDevice, c->reduce));
+            HIPCHK(c, hipEventRecord(c->ev_flags, c->reduce));
+            c->flags_in_flight = true;
+            flags = c->d_unused;
+        }
+    }
+    for (int32_t b : launch) {
+        const int32_t st = launch_bucket(c, b, flags, marks);
+        if (st != DDP_OK) return st;
+    }
+    if (!c->plan_only) {
+        if (c->pipeline == DDP_PIPELINE_STAGED) {
+            size_t slot;
+            int32_t rc;
+            if ((rc = timed_begin(c, DDP_K_UNPACK, -1, c->reduce, &slot)) != DDP_OK) return rc;
+            HIPCHK(c, ddp::launch_unpack(c->tables, 0, n, 0, c->h_tile0[n],
+                                         c->slabs + static_cast<int64_t>(c->R) * c->slab_stride,
+                                         c->write_all ? c->R : 1, c->reduce));
+            if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
+        }
+        if (c->backward != c->reduce) {
+            HIPCHK(c, hipEventRecord(c->ev_done, c->reduce));
+            HIPCHK(c, hipStreamWaitEvent(c->backward, c->ev_done, 0));
+        }
+    }
+    c->log_closed.swap(c->log_running);
+    c->log_running.clear();
+    c->used_closed = c->used_running;
+    std::fill(c->used_running.begin(), c->used_running.end(), 0);
+    c->tracker.new_iteration();
+    return DDP_OK;
+}
+
+int32_t ddp_synchronize(ddp_ctx* c) {
+    if (!c) return DDP_ERR_ARG;
+    if (c->plan_only) return fail(c, DDP_ERR_NO_DEVICE, "plan-only context has nothing to wait for");
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->backward));
+    HIPCHK(c, hipStreamSynchronize(c->reduce));
+    return DDP_OK;
+}
+
+int32_t ddp_get_launch_log(const ddp_ctx* c, int32_t which, int32_t* bucket_ids,
+                           int32_t* after_call, int32_t cap, int32_t* n) {
+    if (!c || !n || cap < 0 || (which != 0 && which != 1)) return DDP_ERR_ARG;
+    const auto& log = which == 0 ? c->log_running : c->log_closed;
+    *n = static_cast<int32_t>(log.size());
+    for (int32_t i = 0; i < *n && i < cap; ++i) {
+        if (bucket_ids) bucket_ids[i] = log[i].first;
+        if (after_call) after_call[i] = log[i].second;
+    }
+    return DDP_OK;
+}
+
+int32_t ddp_no_sync_accumulate(ddp_ctx* c, void* const* micro) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_no_sync_accumulate before ddp_build_buckets");
+    if (c->plan_only) return fail(c, DDP_ERR_NO_DEVICE, "plan-only context cannot accumulate");
+    if (!micro) return fail(c, DDP_ERR_ARG, "ddp_no_sync_accumulate: null pointer array");
+    const int32_t n = static_cast<int32_t>(c->plan.params.size());
+    const int64_t R = c->R;
+    for (int64_t r = 0; r < R; ++r)
+        for (int32_t i = 0; i < n; ++i) {
+            const void* p = micro[r * n + i];
+            if (p && reinterpret_cast<uintptr_t>(p) % static_cast<uintptr_t>(ddp::elem_size(c->plan.params[i].dtype)) != 0)
+                return fail(c, DDP_ERR_ARG, "ddp_no_sync_accumulate: pointer not aligned to its element size");
+        }
+    HIPCHK(c, hipSetDevice(c->device));
+    if (c->micro_in_flight) HIPCHK(c, hipEventSynchronize(c->ev_micro));
+    std::memcpy(c->h_micro, micro, sizeof(void*) * R * n);
+    HIPCHK(c, hipMemcpyAsync(c->d_micro, c->h_micro, sizeof(void*) * R * n, hipMemcpyHostToDevice, c->backward));
+    HIPCHK(c, hipEventRecord(c->ev_micro, c->backward));
+    c->micro_in_flight = true;
+    size_t slot;
+    int32_t rc;
+    if ((rc = timed_begin(c, DDP_K_ACCUMULATE, -1, c->backward, &slot)) != DDP_OK) return rc;
+    HIPCHK(c, ddp::launch_accumulate(c->tables, c->h_tile0[n], c->R, n, c->d_micro, c->backward));
+    if ((rc = timed_end(c, slot, c->backward)) != DDP_OK) return rc;
+    for (int32_t i = 0; i < n; ++i)
+        for (int64_t r = 0; r < R; ++r)
+            if (micro[r * n + i]) { c->used_running[i] = 1; break; }
+    return DDP_OK;
+}
+
+int32_t ddp_get_used_map(const ddp_ctx* c, int32_t which, uint8_t* used) {
+    if (!c || !used || (which != 0 && which != 1)) return DDP_ERR_ARG;
+    if (!c->built) return DDP_ERR_STATE;
+    const auto& m = which == 0 ? c->used_running : c->used_closed;
+    std::memcpy(used, m.data(), m.size());
+    return DDP_OK;
+}
+
+int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, const int64_t* delay_ns,
+                           void* const* src_ptrs, int32_t mark) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_synth_backward before ddp_build_buckets");
+    if (c->plan_only) return fail(c, DDP_ERR_NO_DEVICE, "plan-only context cannot run a backward pass");
+    if (count < 0 || (count > 0 && !order)) return fail(c, DDP_ERR_ARG, "ddp_synth_backward: bad order");
+    const int32_t n = static_cast<int32_t>(c->plan.params.size());
+    const int64_t R = c->R;
+    for (int32_t k = 0; k < count; ++k) {
+        if (order[k] < 0 || order[k] >= n) return fail(c, DDP_ERR_ARG, "ddp_synth_backward: id out of range");
+        if (delay_ns && (delay_ns[k] < 0 || delay_ns[k] > 100000000))
+            return fail(c, DDP_ERR_ARG, "ddp_synth_backward: delay outside [0, 100 ms]");
+    }
+    HIPCHK(c, hipSetDevice(c->device));
+    void** d_rows = nullptr;
+    if (src_ptrs && count > 0) {
+        const int64_t need = 2 * R * count;
+        if (c->emit_in_flight) HIPCHK(c, hipEventSynchronize(c->ev_emit));
+        if (need > c->emit_cap) {
+            HIPCHK(c, hipStreamSynchronize(c->backward));
+            if (c->d_emit) HIPCHK(c, hipFree(c->d_emit));
+            if (c->h_emit) HIPCHK(c, hipHostFree(c->h_emit));
+            c->d_emit = nullptr; c->h_emit = nullptr; c->emit_cap = 0;
+            HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_emit), sizeof(void*) * need));
+            HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_emit), sizeof(void*) * need, hipHostMallocDefault));
+            c->emit_cap = need;
+        }
+        for (int32_t k = 0; k < count; ++k)
+            for (int64_t r = 0; r < R; ++r) {
+                void* src = src_ptrs[r * n + order[k]];
+                if (!src && c->plan.params[order[k]].numel > 0)
+                    return fail(c, DDP_ERR_ARG, "ddp_synth_backward: null source pointer");
+                c->h_emit[2 * R * k + r] = c->grad_ptrs[r * n + order[k]];
+                c->h_emit[2 * R * k + R + r] = src;
+            }
+        HIPCHK(c, hipMemcpyAsync(c->d_emit, c->h_emit, sizeof(void*) * need, hipMemcpyHostToDevice, c->backward));
+        HIPCHK(c, hipEventRecord(c->ev_emit, c->backward));
+        c->emit_in_flight = true;
+        d_rows = c->d_emit;
+    }
+    for (int32_t k = 0; k < count; ++k) {
+        const int32_t p = order[k];
+        const int64_t ticks = delay_ns ? delay_ns[k] * c->wall_clock_khz / 1000000 : 0;
+        if (ticks > 0 || d_rows) {
+            HIPCHK(c, ddp::launch_emit(ticks, d_rows ? d_rows + 2 * R * k : nullptr, c->R,
+                                       c->plan.params[p].numel, ddp::elem_size(c->plan.params[p].dtype),
+                                       c->backward));
+        }
+        if (mark) {
+            const int32_t st = ddp_mark_ready(c, p);
+            if (st != DDP_OK) return st;
+        }
+    }
+    return DDP_OK;
+}
+
+int32_t ddp_get_kernel_times(ddp_ctx* c, int32_t kind, float* ms, int32_t* ids, int32_t cap,
+                             int32_t* n) {
+    if (!c || !n || cap < 0) return DDP_ERR_ARG;
+    if (c->plan_only) return fail(c, DDP_ERR_NO_DEVICE, "plan-only context has no kernel times");
+    HIPCHK(c, hipSetDevice(c->device));
+    int32_t k = 0;
+    for (const TimedLaunch& t : c->timed) {
+        if (t.kind != kind) continue;
+        if (k < cap) {
+            float v = 0.f;
+            HIPCHK(c, hipEventElapsedTime(&v, t.start, t.stop));
+            if (ms) ms[k] = v;
+            if (ids) ids[k] = t.bucket;
+        }
+        ++k;
+    }
+    *n = k;
+    return DDP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,77 @@
+// Launch wrappers of the HIP kernels (gfx950).  Internal to the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace ddp {
+
+// Work is cut into tiles of TILE_BYTES of gradient data: one thread block of
+// BLOCK threads moves TILE_VECS 16-byte vectors per replica.
+constexpr int BLOCK = 256;
+constexpr int TILE_VECS = 1024;
+constexpr int TILE_BYTES = TILE_VECS * 16;
+
+// Tiles a segment of `bytes` bytes can need, whatever its pointer alignment:
+// vectors are cut at 16-byte boundaries of the destination, so up to
+// 16 - elem_size bytes of lead-in shift the grid.
+inline int64_t tiles_for(int64_t numel, int es) {
+    if (numel <= 0) return 0;
+    return (numel * es + (16 - es) + TILE_BYTES - 1) / TILE_BYTES;
+}
+
+// Device-resident tables over the G segments (parameters in bucket-major fill
+// order) of the model.
+struct SegTables {
+    const int64_t* numel;      // [G] elements
+    const int64_t* flat_byte;  // [G] byte offset of the segment inside a replica slab
+    const int64_t* tile0;      // [G+1] exclusive prefix sum of tiles_for()
+    const int32_t* param;      // [G] registration index
+    const int32_t* dtype;      // [G] element type
+    void* const* grad;         // [R*G] replica r's gradient of segment g at [r*G+g]
+    int32_t G;
+};
+
+struct Scale {       // y = use_mul ? s * mul : s / div
+    float div;
+    float mul;
+    int32_t use_mul;
+};
+
+// All segment launches cover the tiles [tile_base, tile_base + ntiles) of the
+// global tile numbering (tile0), which must lie inside segments
+// [seg_begin, seg_end).
+
+// K1: gradients -> flat replica slabs for all `nrep` replicas.  unused (may be
+// null): per-parameter flags, 1 = write zeros and do not read the gradient.
+hipError_t launch_pack(const SegTables& t, int seg_begin, int seg_end, int64_t tile_base,
+                       int64_t ntiles, char* slab0, int64_t slab_stride, int nrep,
+                       const uint8_t* unused, hipStream_t s);
+
+// K3: averaged slab -> gradient tensors of replicas [0, nrep).
+hipError_t launch_unpack(const SegTables& t, int seg_begin, int seg_end, int64_t tile_base,
+                         int64_t ntiles, const char* out_slab, int nrep, hipStream_t s);
+
+// K2 (staged): out[v] = scale(sum_r in_r[v]) over nvec 16-byte vectors;
+// in_r = in0 + r*stride.  max_blocks > 0 bounds the grid (blocks then loop).
+hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* out, int64_t nvec,
+                              int R, Scale sc, int max_blocks, bool nontemporal, hipStream_t s);
+
+// K2 (fused): gather R replicas through the segment table, reduce, scatter to
+// the gradient tensors of replicas [0, nwrite).
+hipError_t launch_fused_reduce(int dtype, const SegTables& t, int seg_begin, int seg_end,
+                               int64_t tile_base, int64_t ntiles, int R, int nwrite,
+                               const uint8_t* unused, Scale sc, bool nontemporal, hipStream_t s);
+
+// K4: grad[r][g] += micro[r*n + param[g]] for all segments and replicas
+// (null micro pointers are skipped).  ntiles = tile0[G].
+hipError_t launch_accumulate(const SegTables& t, int64_t ntiles, int R, int n, void* const* micro,
+                             hipStream_t s);
+
+// K6: busy-wait `ticks` of the device wall clock (bounded), then copy
+// src_r -> dst_r (nelem elements of es bytes) for r < R, where
+// ptrs = [dst_0..dst_{R-1}, src_0..src_{R-1}] is a device array (null = delay
+// only).
+hipError_t launch_emit(int64_t ticks, void* const* ptrs, int R, int64_t nelem, int es,
+                       hipStream_t s);
+
+}  // namespace ddp

@@ -1,0 +1,315 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Indexing (assignment, pack, unpack) must be
+bit-exact; reductions must stay within 1e-6 (fp32) / 1e-3 (fp16, bf16) of the
+oracle relative to max(|oracle|, mean_r |x_r|) -- and, because both sides add
+in the same order, are also expected to agree bit for bit, which is asserted
+separately so that a failure tells which bar was missed."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+FP32, FP16, BF16 = 0, 1, 2
+TOL = {FP32: 1e-6, FP16: 1e-3, BF16: 1e-3}
+STAGED, FUSED = 0, 1
+
+
+def lib():
+    import paper_2006_15704_amd as d
+    from paper_2006_15704_amd import harness
+    return d, harness
+
+
+def assert_close(got, want, reps_p, dtype, what):
+    """spec tolerance, then bit equality (NaN == NaN, -0 == +0)."""
+    g = oracle.to_f32(got, dtype).astype(np.float64)
+    w = oracle.to_f32(want, dtype).astype(np.float64)
+    scale = np.zeros_like(w)
+    for x in reps_p:
+        scale += np.abs(oracle.to_f32(x, dtype).astype(np.float64))
+    scale /= len(reps_p)
+    both_nan = np.isnan(g) & np.isnan(w)
+    with np.errstate(invalid="ignore"):
+        bad = ~both_nan & ~(np.abs(g - w) <= TOL[dtype] * np.maximum(np.abs(w), scale))
+        bad &= ~((g == w))          # covers equal infinities
+    assert not bad.any(), f"{what}: {int(bad.sum())} elements outside tolerance"
+    same = both_nan | (g == w)
+    assert same.all(), f"{what}: {int((~same).sum())} elements differ in bits"
+
+
+def run_sync(numel, dtypes, reps, cap, pipeline, order=None, skew=None, replica_skew=None,
+             write_all=False, one_by_one=False, same_stream=False, check_flat=True):
+    d, harness = lib()
+    R = len(reps)
+    grads = harness.DeviceGrads(numel, dtypes, R, skew=skew, replica_skew=replica_skew, fill=0xFF)
+    for r in range(R):
+        grads.upload_replica(r, reps[r])
+    want, asg, wlog = oracle.synchronize(numel, dtypes, cap, reps, order)
+    with harness.Session(grads, cap, pipeline, write_all, same_stream) as s:
+        assert s.n_buckets == len(asg.buckets)
+        bucket_of, offset = d.ddp_get_assignment(s.ctx, len(numel))
+        assert bucket_of.tolist() == asg.bucket_of.tolist()
+        assert offset.tolist() == asg.offset_of.tolist()
+        s.sync(order, one_by_one=one_by_one)
+        assert d.ddp_get_launch_log(s.ctx, 1) == wlog
+        if pipeline == STAGED and check_flat:
+            marked = set(range(len(numel))) if order is None else set(order)
+            unused = [i for i in range(len(numel)) if i not in marked]
+            for b in range(s.n_buckets):
+                for r in range(R):
+                    flat = s.bucket_bytes(b, r)
+                    assert flat.tobytes() == oracle.pack_bucket(asg, b, reps[r], unused).tobytes(), \
+                        f"flat bucket {b} replica {r}"
+        outs = [[grads.download(r, i) for i in range(len(numel))] for r in range(R if write_all else 1)]
+        others = [[grads.download(r, i) for i in range(len(numel))] for r in range(1, R)] if not write_all else []
+    for rr, out_r in enumerate(outs):
+        for i in range(len(numel)):
+            assert_close(out_r[i], want[i], [reps[r][i] for r in range(R)], dtypes[i],
+                         f"param {i} replica {rr}")
+    return outs, others, want
+
+
+def gaussian_reps(config_id, numel, R, sigma, dtype=FP32):
+    return [workloads.gaussian_replica(config_id, r, 0, numel, sigma, dtype) for r in range(R)]
+
+
+# ---- config 1: Tiny ----------------------------------------------------------------
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_tiny_config(pipeline):
+    numel = workloads.numel_of(workloads.tiny_shapes())
+    reps = gaussian_reps(1, numel, 2, 1.0)
+    outs, others, _ = run_sync(numel, [FP32] * 8, reps, 16384, pipeline, one_by_one=True)
+    if pipeline == FUSED:
+        return
+    # W = 1: the other replicas' gradients are inputs only and stay untouched
+    for r, row in enumerate(others, start=1):
+        for i in range(8):
+            assert row[i].tobytes() == reps[r][i].tobytes()
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_tiny_linear_regression_mean_gradient(pipeline):
+    X, w, b, y = workloads.linear_regression_problem(1)
+    full_w = 2.0 / 64 * (X.T @ (X @ w + b - y))
+    full_b = 2.0 / 64 * (X @ w + b - y).sum()
+    reps = []
+    for r in range(2):
+        sl = slice(r * 32, (r + 1) * 32)
+        res = X[sl] @ w + b - y[sl]
+        reps.append([(2.0 / 32 * (X[sl].T @ res)).astype(np.float32),
+                     np.array([2.0 / 32 * res.sum()], dtype=np.float32)])
+    outs, _, _ = run_sync([16, 1], [FP32, FP32], reps, 25 << 20, pipeline)
+    assert np.allclose(outs[0][0], full_w, rtol=1e-6, atol=1e-7)
+    assert np.allclose(outs[0][1], full_b, rtol=1e-6, atol=1e-7)
+
+
+# ---- indexing: tags, alignments, odd sizes ----------------------------------------------
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("dtype", [FP32, FP16, BF16])
+@pytest.mark.parametrize("cap", [0, 1000, 16384, oracle.CAP_WHOLE_MODEL])
+def test_single_replica_round_trip_is_identity(pipeline, dtype, cap):
+    numel = workloads.numel_of(workloads.tiny_shapes()) + [0, 1, 3, 4099, 7]
+    starts = np.concatenate([[0], np.cumsum(numel)[:-1]])
+    reps = [[workloads.tag_grad(0, int(s), int(n), dtype) for s, n in zip(starts, numel)]]
+    outs, _, _ = run_sync(numel, [dtype] * len(numel), reps, cap, pipeline)
+    for i in range(len(numel)):
+        assert outs[0][i].tobytes() == reps[0][i].tobytes()
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("dtype", [FP32, FP16])
+def test_unaligned_gradient_pointers(pipeline, dtype):
+    """Tensors that start at every element-aligned offset modulo 16 bytes,
+    different per replica, with lengths around the vector and tile sizes."""
+    es = 4 if dtype == FP32 else 2
+    numel = [1, 2, 3, 5, 8, 13, 4095, 4096, 4097, 8191, 8193, 20000, 33, 64, 1023, 9000]
+    skew = [(i * es) % 16 for i in range(len(numel))]
+    R = 3
+    replica_skew = [0, es, 3 * es]
+    reps = gaussian_reps(11, numel, R, 1e-2, dtype)
+    for write_all in (False, True):
+        run_sync(numel, [dtype] * len(numel), reps, 20000, pipeline, skew=skew,
+                 replica_skew=replica_skew, write_all=write_all)
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_mixed_element_types(pipeline):
+    numel = [100, 257, 4100, 33, 64, 9]
+    dtypes = [FP32, FP16, FP16, BF16, FP32, FP32]
+    R = 4
+    reps = [[workloads.gaussian_grad(12, r, 0, p, n, 1e-2, dt) for p, (n, dt) in enumerate(zip(numel, dtypes))]
+            for r in range(R)]
+    run_sync(numel, dtypes, reps, 1 << 20, pipeline)
+
+
+# ---- reductions -----------------------------------------------------------------------------
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("R", [1, 2, 3, 5, 7, 8, 12, 16, 31, 32, 64])
+def test_replica_counts_fp32(pipeline, R):
+    numel = [5000, 17, 4096, 1]
+    reps = gaussian_reps(20 + R, numel, R, 1e-2)
+    run_sync(numel, [FP32] * 4, reps, 8192, pipeline)
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("dtype", [FP16, BF16])
+@pytest.mark.parametrize("R", [2, 3, 16])
+def test_replica_counts_16bit(pipeline, dtype, R):
+    numel = [5000, 17, 8192, 1]
+    reps = gaussian_reps(40 + R, numel, R, 1e-2, dtype)
+    run_sync(numel, [dtype] * 4, reps, 8192, pipeline)
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("R", [3, 8])
+def test_integer_inputs_equal_exact_arithmetic(pipeline, R):
+    numel = [4097, 300]
+    reps = [[workloads.integer_grad(3, r, 0, p, n, 100_000) for p, n in enumerate(numel)] for r in range(R)]
+    outs, _, _ = run_sync(numel, [FP32] * 2, reps, 1 << 20, pipeline)
+    for p in range(2):
+        total = sum(reps[r][p].astype(np.int64) for r in range(R))
+        assert (outs[0][p] == (total / R).astype(np.float32)).all()
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_fp16_every_bit_pattern_with_partner(pipeline):
+    """All 65,536 fp16 patterns (subnormals, infinities, NaNs) averaged with a
+    fixed partner, and alone (R = 1 must hand finite values back unchanged)."""
+    bits = np.arange(65536, dtype=np.uint16).view(np.float16)
+    partner = np.full(65536, np.float16(0.3711), dtype=np.float16)
+    run_sync([65536], [FP16], [[bits], [partner]], 1 << 20, pipeline, check_flat=False)
+    outs, _, _ = run_sync([65536], [FP16], [[bits]], 1 << 20, pipeline, check_flat=False)
+    finite = np.isfinite(bits)
+    assert (outs[0][0].view(np.uint16)[finite] == bits.view(np.uint16)[finite]).all()
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_bf16_rounding_ties_and_specials(pipeline):
+    """Sums that land exactly on bf16 rounding ties: x = k + 0.5 ulp patterns
+    built from two bf16 addends, plus infinities and NaN."""
+    hi = np.arange(0, 65536, dtype=np.uint16)
+    a = hi                                   # every bf16 pattern
+    b = (hi & np.uint16(0xFF80))             # same exponent, zero mantissa: sum doubles/rounds
+    c = np.full(65536, 0x3B80, dtype=np.uint16)   # 2^-8
+    run_sync([65536], [BF16], [[a], [b], [c]], 1 << 20, pipeline, check_flat=False)
+    run_sync([65536], [BF16], [[a], [c]], 1 << 20, pipeline, check_flat=False)
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_nonfinite_and_signed_zero(pipeline):
+    x = np.array([np.inf, np.nan, 1.0, -np.inf, -0.0, -0.0, 1e-45, 3e38], dtype=np.float32)
+    y = np.array([1.0, 1.0, np.inf, np.inf, -0.0, 0.0, 1e-45, 3e38], dtype=np.float32)
+    outs, _, want = run_sync([8], [FP32], [[x], [y]], 1 << 20, pipeline)
+    assert np.signbit(outs[0][0][4]) == np.signbit(want[0][4])    # -0 + -0 stays -0
+    assert outs[0][0][6] == want[0][6] and want[0][6] > 0           # subnormals are not flushed
+
+
+# ---- ready order, launch order, absent gradients, iterations ----------------------------
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("seed", range(4))
+def test_random_ready_orders_with_unmarked_parameters(pipeline, seed):
+    rng = np.random.default_rng(seed)
+    n = 40
+    numel = [int(x) for x in rng.integers(1, 3000, size=n)]
+    R = 4
+    reps = gaussian_reps(60 + seed, numel, R, 1e-2)
+    order = [int(p) for p in rng.permutation(n)]
+    never = sorted(order[n - 6:]) if seed % 2 else []
+    order = order[: n - 6] if seed % 2 else order
+    for r in range(R):
+        for p in never:
+            reps[r][p][:] = np.nan          # must not be read
+    outs, _, _ = run_sync(numel, [FP32] * n, reps, 10000, pipeline, order=order,
+                          write_all=bool(seed & 2), one_by_one=True)
+    for row in outs:
+        for p in never:
+            assert row[p].tobytes() == np.zeros(numel[p], np.float32).tobytes()
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_two_iterations_replenish_pending_counts(pipeline):
+    d, harness = lib()
+    numel = workloads.numel_of(workloads.tiny_shapes())
+    R = 2
+    grads = harness.DeviceGrads(numel, [FP32] * 8, R)
+    with harness.Session(grads, 16384, pipeline) as s:
+        for it, order in enumerate([[7, 6, 5, 4, 3, 2, 1, 0], [0, 1, 2, 3, 4, 5, 6, 7], [7, 6, 5, 4]]):
+            reps = [workloads.gaussian_replica(70 + it, r, 0, numel, 1.0) for r in range(R)]
+            for r in range(R):
+                grads.upload_replica(r, reps[r])
+            want, asg, wlog = oracle.synchronize(numel, [FP32] * 8, 16384, reps, order)
+            s.sync(order, one_by_one=True)
+            assert d.ddp_get_launch_log(s.ctx, 1) == wlog
+            for i in range(8):
+                assert grads.download(0, i).tobytes() == want[i].tobytes()
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_mark_ready(s.ctx, 3)
+            d.ddp_mark_ready(s.ctx, 3)
+        assert e.value.code == d.DDP_ERR_ALREADY_READY
+        d.ddp_finalize_backward(s.ctx)
+        d.ddp_synchronize(s.ctx)
+
+
+# ---- no_sync -------------------------------------------------------------------------------
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("dtype", [FP32, FP16, BF16])
+def test_no_sync_accumulation_then_one_reduction(pipeline, dtype):
+    d, harness = lib()
+    numel = workloads.numel_of(workloads.tiny_shapes()) + [4099]
+    n, R, K = len(numel), 3, 4
+    dts = [dtype] * n
+    grads = harness.DeviceGrads(numel, dts, R, fill=0)
+    micro_dev = harness.DeviceGrads(numel, dts, R, skew=[(i * 2 * (2 if dtype else 4)) % 16 for i in range(n)])
+    acc = [[np.zeros(x, dtype=oracle.STORAGE[dtype]) for x in numel] for _ in range(R)]
+    skipped = {1: [2, 5]}          # micro-step 1 produces no gradient for parameters 2 and 5
+    with harness.Session(grads, 16384, pipeline) as s:
+        for k in range(K):
+            micro = [workloads.gaussian_replica(80, r, k, numel, 1e-2, dtype) for r in range(R)]
+            ptrs = []
+            for r in range(R):
+                row = list(micro[r])
+                for p in skipped.get(k, []):
+                    row[p] = None
+                oracle.accumulate(acc[r], row, dts)
+                for p in range(n):
+                    if row[p] is not None:
+                        micro_dev.upload(r, p, row[p])
+                ptrs += [None if row[p] is None else micro_dev.ptr(r, p) for p in range(n)]
+            d.ddp_no_sync_accumulate(s.ctx, ptrs)
+            d.ddp_synchronize(s.ctx)
+            assert d.ddp_get_launch_log(s.ctx, 0) == []         # no reduction was launched
+        for r in range(R):
+            for p in range(n):
+                assert grads.download(r, p).tobytes() == acc[r][p].tobytes(), f"accumulator r{r} p{p}"
+        want, _, _ = oracle.synchronize(numel, dts, 16384, acc)
+        s.sync()
+        assert d.ddp_get_used_map(s.ctx, n, 1).tolist() == [1] * n
+        for p in range(n):
+            assert grads.download(0, p).tobytes() == want[p].tobytes()
+
+
+# ---- overlap plumbing: the reduction must wait for the backward stream ------------------
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_reduction_waits_for_gradients_produced_on_the_backward_stream(pipeline):
+    """Gradient memory starts as NaN; the synthetic backward stream writes the
+    real gradients after a delay, parameter by parameter, and marks them ready.
+    Any reduction that ran ahead of its inputs would average NaNs."""
+    d, harness = lib()
+    numel = workloads.numel_of(workloads.tiny_shapes())
+    R = 2
+    reps = [workloads.gaussian_replica(90, r, 0, numel, 1.0) for r in range(R)]
+    grads = harness.DeviceGrads(numel, [FP32] * 8, R, fill=0xFF)
+    src = harness.DeviceGrads(numel, [FP32] * 8, R)
+    for r in range(R):
+        src.upload_replica(r, reps[r])
+    want, _, _ = oracle.synchronize(numel, [FP32] * 8, 16384, reps)
+    with harness.Session(grads, 16384, pipeline) as s:
+        order = list(range(7, -1, -1))
+        d.ddp_synth_backward(s.ctx, order, [200_000] * 8, src.ptrs(), True)
+        d.ddp_finalize_backward(s.ctx)
+        d.ddp_synchronize(s.ctx)
+        for i in range(8):
+            assert grads.download(0, i).tobytes() == want[i].tobytes()

@@ -1,0 +1,171 @@
+"""CPU-only tests of the library's host logic through the C ABI, on a
+plan-only context (no device, nothing computed): bucket assignment and the
+ready/launch state machine must agree with the oracle exactly; error paths
+return codes instead of hanging or aborting; the shared library exports every
+symbol the header declares."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def d():
+    import paper_2006_15704_amd as lib
+    return lib
+
+
+def plan(d, numel, dtype, cap, R=2):
+    ctx = d.ddp_create(R, d.DDP_DEVICE_NONE)
+    d.ddp_register_params(ctx, numel, dtype, None)
+    nb = d.ddp_build_buckets(ctx, cap)
+    return ctx, nb
+
+
+def test_library_exports_every_declared_symbol(d):
+    header = open(os.path.join(ROOT, "include", "ddp_gfx950.h")).read()
+    declared = set(re.findall(r"\b(ddp_[a-z_]+)\s*\(", header))
+    declared.discard("ddp_ctx")
+    assert declared, "no declarations found"
+    lib = ctypes.CDLL(d.binding.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} is declared but not exported"
+    assert declared == set(d.binding.EXPORTS)
+    for name in d.binding.EXPORTS:
+        assert callable(getattr(d, name)), f"binding lacks {name}"
+
+
+@pytest.mark.parametrize("name,dt,caps", [
+    ("tiny", 0, [0, 100, 16384, 1 << 20]),
+    ("resnet50", 0, [0, 1 << 20, 5 << 20, 10 << 20, 25 << 20, 50 << 20, 100 << 20]),
+    ("resnet50", 1, [0, 1 << 20, 5 << 20, 25 << 20]),
+    ("bert_large", 0, [0, 1 << 20, 25 << 20, 25 * 10**6, 100 << 20]),
+])
+def test_assignment_matches_oracle(d, name, dt, caps):
+    numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[name]())
+    n = len(numel)
+    for cap in caps + [d.DDP_CAP_WHOLE_MODEL]:
+        asg = oracle.assign_buckets(numel, [dt] * n, cap)
+        ctx, nb = plan(d, numel, [dt] * n, cap)
+        try:
+            assert nb == len(asg.buckets)
+            bucket_of, offset = d.ddp_get_assignment(ctx, n)
+            assert bucket_of.tolist() == asg.bucket_of.tolist()
+            assert offset.tolist() == asg.offset_of.tolist()
+            for b, bk in enumerate(asg.buckets):
+                assert d.ddp_get_bucket_info(ctx, b) == (bk.elems, len(bk.params), bk.dtype)
+        finally:
+            d.ddp_destroy(ctx)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_assignment_and_schedule_match_oracle(d, seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 120))
+    numel = [int(x) for x in rng.integers(0, 5000, size=n)]
+    dtype = [0] * n if seed % 2 else [int(x) for x in rng.integers(0, 3, size=n)]
+    cap = int(rng.choice([0, 64, 1000, 8192, 100000]))
+    asg = oracle.assign_buckets(numel, dtype, cap)
+    order = [int(p) for p in rng.permutation(n)]
+    if seed % 3 == 0:
+        order = order[: int(rng.integers(0, n + 1))]
+    ctx, nb = plan(d, numel, dtype, cap)
+    try:
+        bucket_of, offset = d.ddp_get_assignment(ctx, n)
+        assert bucket_of.tolist() == asg.bucket_of.tolist()
+        assert offset.tolist() == asg.offset_of.tolist()
+        for it in range(2):          # pending counts must be replenished
+            for p in order:
+                d.ddp_mark_ready(ctx, p)
+            running = d.ddp_get_launch_log(ctx, 0)
+            d.ddp_finalize_backward(ctx)
+            want = oracle.launch_schedule(asg, order)
+            assert d.ddp_get_launch_log(ctx, 1) == want
+            assert running == [x for x in want if x[1] < len(order)]
+            used = d.ddp_get_used_map(ctx, n, 1)
+            assert used.tolist() == [1 if p in set(order) else 0 for p in range(n)]
+    finally:
+        d.ddp_destroy(ctx)
+
+
+def test_cap_arithmetic_does_not_wrap(d):
+    # sizes close to 2^63 bytes: the running total must not overflow into "fits"
+    huge = (1 << 60)
+    ctx, nb = plan(d, [huge, huge, huge], [0, 0, 0], d.DDP_CAP_WHOLE_MODEL - 5)
+    try:
+        assert nb == len(oracle.assign_buckets([huge] * 3, [0] * 3, d.DDP_CAP_WHOLE_MODEL - 5).buckets)
+    finally:
+        d.ddp_destroy(ctx)
+
+
+def test_error_codes(d):
+    with pytest.raises(d.DdpError) as e:
+        d.ddp_create(0, d.DDP_DEVICE_NONE)
+    assert e.value.code == d.DDP_ERR_ARG
+    with pytest.raises(d.DdpError) as e:
+        d.ddp_create(d.DDP_MAX_REPLICAS + 1, d.DDP_DEVICE_NONE)
+    assert e.value.code == d.DDP_ERR_UNSUPPORTED
+
+    ctx = d.ddp_create(2, d.DDP_DEVICE_NONE)
+    try:
+        for call in (lambda: d.ddp_build_buckets(ctx, 100), lambda: d.ddp_mark_ready(ctx, 0),
+                     lambda: d.ddp_finalize_backward(ctx)):
+            with pytest.raises(d.DdpError) as e:
+                call()
+            assert e.value.code == d.DDP_ERR_STATE
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_register_params(ctx, [4, 4], [0, 7], None)
+        assert e.value.code == d.DDP_ERR_ARG
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_register_params(ctx, [4, -1], [0, 0], None)
+        assert e.value.code == d.DDP_ERR_ARG
+        d.ddp_register_params(ctx, [4, 4, 4], [0, 0, 0], None)
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_register_params(ctx, [4], [0], None)
+        assert e.value.code == d.DDP_ERR_STATE
+        assert d.ddp_build_buckets(ctx, 32) == 2
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_build_buckets(ctx, 32)
+        assert e.value.code == d.DDP_ERR_STATE
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_set_option(ctx, d.DDP_OPT_PIPELINE, d.DDP_PIPELINE_FUSED)
+        assert e.value.code == d.DDP_ERR_STATE
+        for bad in (-1, 3, 1000):
+            with pytest.raises(d.DdpError) as e:
+                d.ddp_mark_ready(ctx, bad)
+            assert e.value.code == d.DDP_ERR_ARG
+        d.ddp_mark_ready(ctx, 2)
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_mark_ready(ctx, 2)
+        assert e.value.code == d.DDP_ERR_ALREADY_READY
+        assert "already marked" in d.ddp_last_error(ctx)
+        # the failed call changed nothing: bucket 0 = {2, 1} still waits for parameter 1
+        assert d.ddp_get_launch_log(ctx, 0) == []
+        d.ddp_mark_ready(ctx, 1)
+        assert d.ddp_get_launch_log(ctx, 0) == [(0, 1)]
+        for call in (lambda: d.ddp_synchronize(ctx), lambda: d.ddp_no_sync_accumulate(ctx, [None] * 6),
+                     lambda: d.ddp_synth_backward(ctx, [0]), lambda: d.ddp_get_bucket_ptr(ctx, 0, 0),
+                     lambda: d.ddp_get_kernel_times(ctx, 1)):
+            with pytest.raises(d.DdpError) as e:
+                call()
+            assert e.value.code == d.DDP_ERR_NO_DEVICE
+        d.ddp_finalize_backward(ctx)      # parameter 0 never marked: no hang, launched by finalize
+        assert d.ddp_get_launch_log(ctx, 1) == [(0, 1), (1, 2)]
+    finally:
+        d.ddp_destroy(ctx)
+
+
+def test_compute_context_without_gpu_fails_loudly(d):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(d.DdpError) as e:
+        d.ddp_create(2, 0)
+    assert e.value.code == d.DDP_ERR_HIP
