@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of bucketed gradient synchronization on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic
+gradients: ready marks for every parameter in reverse registration order
+(launching each bucket's pack + reduce, or the fused one-pass kernel, as soon
+as it is complete and its predecessors have been launched), then the
+finalizing step (write-back of the averages), all through the C ABI.  Inputs
+are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is the algorithmic end-to-end rate
+(R + W) * B / ms_per_step (every replica gradient read once, the average
+written W = 1 times); `roofline` is the reduce kernel against the HBM peak;
+`cpu_baseline` is the CPU oracle on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
+
+WORKLOADS = {
+    # name: (shape list, config id, R, sigma, dtype code, cap bytes)
+    "resnet50": ("resnet50", 2, 8, 1e-2, 0, 25 << 20),
+    "bert_large": ("bert_large", 3, 8, 1e-3, 0, 25 << 20),
+    "tiny": ("tiny", 1, 2, 1.0, 0, 16384),
+}
+
+
+def generate_replicas(config_id, numel, R, sigma, dtype, threads=16):
+    import workloads
+    jobs = [(r, p) for r in range(R) for p in range(len(numel))]
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        flat = list(pool.map(
+            lambda rp: workloads.gaussian_grad(config_id, rp[0], 0, rp[1], numel[rp[1]], sigma, dtype), jobs))
+    n = len(numel)
+    return [flat[r * n:(r + 1) * n] for r in range(R)]
+
+
+def read_traffic(workload, pipeline):
+    """HBM bytes per reduce launch from the committed counter summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"reduce_traffic_{workload}_{pipeline}.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh).get("traffic_bytes_per_launch")
+    except Exception:
+        return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet50", choices=sorted(WORKLOADS))
+    ap.add_argument("--pipeline", default="staged", choices=["staged", "fused"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--reduce-blocks", type=int, default=None)
+    ap.add_argument("--plain-loads", action="store_true")
+    ap.add_argument("--unroll", type=int, default=None, choices=[1, 2, 4])
+    ap.add_argument("--same-stream", action="store_true",
+                    help="use one stream for backward and reduction (no event plumbing)")
+    ap.add_argument("--timing", default="launch", choices=["launch", "iteration"],
+                    help="HIP-event granularity in the timed region: one pair per kernel launch, "
+                         "or one pair around each iteration's bucket launches")
+    ap.add_argument("--cap-mib", type=float, default=None,
+                    help="override the bucket cap (MiB; negative = whole model)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the R replicas are R buffers in one GPU's "
+              "HBM); --gpus above 1 is not supported and nothing was measured", file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads
+    import paper_2006_15704_amd as lib
+    from paper_2006_15704_amd import harness
+
+    shape_name, config_id, R, sigma, dtype, cap = WORKLOADS[args.workload]
+    if args.cap_mib is not None:
+        cap = lib.DDP_CAP_WHOLE_MODEL if args.cap_mib < 0 else int(args.cap_mib * (1 << 20))
+    numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[shape_name]())
+    n = len(numel)
+    es = harness.ESIZE[dtype]
+    B = sum(numel) * es
+    W = 1
+    pipeline = lib.DDP_PIPELINE_STAGED if args.pipeline == "staged" else lib.DDP_PIPELINE_FUSED
+
+    reps = generate_replicas(config_id, numel, R, sigma, dtype)
+    grads = harness.DeviceGrads(numel, [dtype] * n, R)
+    for r in range(R):
+        grads.upload_replica(r, reps[r])
+    torch.cuda.synchronize()
+
+    order = list(range(n - 1, -1, -1))
+    with harness.Session(grads, cap, pipeline, same_stream=args.same_stream) as s:
+        ctx = s.ctx
+        if args.reduce_blocks is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_BLOCKS, args.reduce_blocks)
+        if args.plain_loads:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_NONTEMPORAL, 0)
+        if args.unroll is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_UNROLL, args.unroll)
+
+        def step():
+            lib.ddp_mark_ready_many(ctx, order)
+            lib.ddp_finalize_backward(ctx)
+
+        for _ in range(args.warmup):
+            step()
+        lib.ddp_synchronize(ctx)
+        torch.cuda.synchronize()
+
+        # timed region: K steps, HIP events around every kernel launch on the reduce stream
+        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 1 if args.timing == "launch" else 2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        lib.ddp_synchronize(ctx)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+        red_ms, red_ids = lib.ddp_get_kernel_times(ctx, lib.DDP_K_REDUCE)
+        pack_ms, _ = lib.ddp_get_kernel_times(ctx, lib.DDP_K_PACK)
+        unpack_ms, _ = lib.ddp_get_kernel_times(ctx, lib.DDP_K_UNPACK)
+        iter_ms, iter_launches = lib.ddp_get_kernel_times(ctx, lib.DDP_K_ITERATION)
+        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 0)
+
+        # the same K steps without the timing events, for comparison
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        lib.ddp_synchronize(ctx)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step_plain = (t1 - t0) * 1e3 / args.steps
+
+        bucket_elems = [lib.ddp_get_bucket_info(ctx, b)[0] for b in range(s.n_buckets)]
+        n_buckets = s.n_buckets
+
+    # reduce kernel: algorithmic bytes per launch = (R + 1) * bucket bytes
+    if args.timing == "launch":
+        launches = len(red_ms)
+        total_alg = float(sum((R + 1) * bucket_elems[b] * es for b in red_ids))
+        total_ms = float(red_ms.sum())
+    else:
+        # one interval per iteration holding all its bucket launches (meaningful
+        # for the fused pipeline, where they are the only kernels in it)
+        launches = int(iter_launches.sum())
+        total_alg = float((R + 1) * B * len(iter_ms))
+        total_ms = float(iter_ms.sum())
+    avg_launch_ms = total_ms / max(launches, 1)
+    achieved = total_alg / max(total_ms, 1e-12) / 1e6          # bytes / ms -> GB/s
+    per_bucket = {}
+    for b in range(n_buckets):
+        sel = red_ms[red_ids == b]
+        if len(sel):
+            per_bucket[str(b)] = round((R + 1) * bucket_elems[b] * es / float(np.median(sel)) / 1e6, 1)
+
+    value = (R + W) * B / ms_per_step / 1e6
+    out = {
+        "metric": "bucketed grad-sync throughput ((R+W)*B per synchronization)",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": {0: "f32", 1: "f16", 2: "bf16"}[dtype],
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {n} tensors, {sum(numel)} elements, R={R}, "
+                               f"cap={cap} B, {n_buckets} buckets, ready order = reverse registration",
+                   "pipeline": args.pipeline, "R": R, "W": W, "bucket_cap_bytes": cap},
+        "pct_hbm_peak_end_to_end": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "ms_per_step_without_timing_events": round(ms_per_step_plain, 4),
+        "kernel_ms_per_step": {
+            "pack": round(float(pack_ms.sum()) / args.steps, 4),
+            "reduce": round(total_ms / args.steps, 4),
+            "unpack": round(float(unpack_ms.sum()) / args.steps, 4),
+        },
+        "reduce_gbps_per_bucket": per_bucket,
+        "roofline": {
+            "kernel": "flat_reduce_kernel" if args.pipeline == "staged" else "fused_reduce_kernel",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "avg_launch_ms": round(avg_launch_ms, 5),
+            "launches": launches,
+            "timing": "HIP event pair per " + args.timing,
+            "algorithmic_bytes_per_launch": round(total_alg / max(launches, 1)),
+            "traffic": read_traffic(args.workload, args.pipeline),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        reps_cpu = args.steps and 1
+        t0 = time.perf_counter()
+        done = 0
+        while True:
+            oracle.synchronize(numel, [dtype] * n, cap, reps)
+            done += 1
+            if time.perf_counter() - t0 > 10.0 or done >= 20:
+                break
+        cpu_ms = (time.perf_counter() - t0) * 1e3 / done
+        out["cpu_baseline"] = {
+            "value": round((R + W) * B / cpu_ms / 1e6, 3),
+            "unit": "GB/s",
+            "cores": 1,
+            "kind": "oracle",
+            "ms_per_step": round(cpu_ms, 2),
+            "sample": f"{done} full synchronizations of the same {args.workload} workload "
+                      f"(all {n_buckets} buckets, R={R}) by the numpy oracle, single thread",
+            "host_cores_visible": os.cpu_count(),
+            "numpy": np.__version__,
+        }
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

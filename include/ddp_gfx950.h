@@ -67,12 +67,16 @@ typedef struct ddp_ctx ddp_ctx;
 #define DDP_OPT_PIPELINE       1  /* DDP_PIPELINE_STAGED (default) or DDP_PIPELINE_FUSED */
 #define DDP_OPT_WRITE_ALL      2  /* 0 (default): the average is written to replica 0's gradient
                                      tensors only (one rank's view); 1: to all R replicas' tensors */
-#define DDP_OPT_TIMING         3  /* 0/1, any time: bracket every kernel launch with HIP events
-                                     on its stream; read back with ddp_get_kernel_times */
+#define DDP_OPT_TIMING         3  /* any time.  1: bracket every kernel launch with a pair of HIP
+                                     events on its stream; 2: one pair per iteration, from just
+                                     before its first bucket launch to just after its last (kind
+                                     DDP_K_ITERATION); 0: off.  Read with ddp_get_kernel_times */
 #define DDP_OPT_REDUCE_BLOCKS  4  /* any time: upper bound on thread blocks per reduce launch
                                      (0 = one block per tile) */
-#define DDP_OPT_NONTEMPORAL    5  /* any time: 1 (default) = read-once inputs are loaded with the
-                                     non-temporal hint, 0 = plain loads */
+#define DDP_OPT_NONTEMPORAL    5  /* any time: 1 (default) = read-once inputs are loaded, and the
+                                     averages stored, with the non-temporal hint; 0 = plain */
+#define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
+                                     kernels: 1, 2 (default) or 4 */
 
 /* DDP_PIPELINE_STAGED follows the paper's data flow literally: gradients are
  * copied into flat per-replica bucket buffers (Algorithm 1, autograd_hook),
@@ -90,6 +94,7 @@ typedef struct ddp_ctx ddp_ctx;
 #define DDP_K_REDUCE     1   /* staged reduce, or the fused gather-reduce-scatter */
 #define DDP_K_UNPACK     2
 #define DDP_K_ACCUMULATE 3
+#define DDP_K_ITERATION  4   /* timing mode 2: all bucket launches of one iteration */
 
 /* Create a context for R >= 1 replicas on HIP device `device` (or
  * DDP_DEVICE_NONE).  `reduce_stream` is the dedicated stream the bucket
@@ -216,7 +221,8 @@ int32_t ddp_synth_backward(ddp_ctx* ctx, const int32_t* order, int32_t count,
  * since the option was last set, in launch order.  Call after
  * ddp_synchronize.  ms holds `cap` entries; *n receives the count available.
  * ids (may be NULL) receives the bucket index of each launch (-1 if the launch
- * covered several buckets). */
+ * covered several buckets; for DDP_K_ITERATION the number of bucket launches
+ * inside the interval). */
 int32_t ddp_get_kernel_times(ddp_ctx* ctx, int32_t kind, float* ms, int32_t* ids,
                              int32_t cap, int32_t* n);
 

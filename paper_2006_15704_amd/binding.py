@@ -34,9 +34,9 @@ DDP_MAX_REPLICAS = 64
 DDP_DEVICE_NONE = -1
 DDP_CAP_WHOLE_MODEL = (1 << 64) - 1
 DDP_OPT_PIPELINE, DDP_OPT_WRITE_ALL, DDP_OPT_TIMING = 1, 2, 3
-DDP_OPT_REDUCE_BLOCKS, DDP_OPT_NONTEMPORAL = 4, 5
+DDP_OPT_REDUCE_BLOCKS, DDP_OPT_NONTEMPORAL, DDP_OPT_REDUCE_UNROLL = 4, 5, 6
 DDP_PIPELINE_STAGED, DDP_PIPELINE_FUSED = 0, 1
-DDP_K_PACK, DDP_K_REDUCE, DDP_K_UNPACK, DDP_K_ACCUMULATE = 0, 1, 2, 3
+DDP_K_PACK, DDP_K_REDUCE, DDP_K_UNPACK, DDP_K_ACCUMULATE, DDP_K_ITERATION = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "ddp_version", "ddp_last_error", "ddp_create", "ddp_destroy", "ddp_set_option",

@@ -39,6 +39,7 @@ struct ddp_ctx {
     int32_t timing = 0;
     int32_t reduce_blocks = 0;
     int32_t nontemporal = 1;
+    int32_t unroll = 2;
 
     bool registered = false, built = false;
     ddp::BucketPlan plan;
@@ -52,6 +53,7 @@ struct ddp_ctx {
     std::vector<int64_t> bucket_vecs;        // 16-byte vectors per bucket (padded)
     std::vector<int64_t> h_tile0;            // [G+1]
     void* d_tables = nullptr;                // one allocation holding all segment tables
+    int32_t* d_tile_seg = nullptr;           // [tiles] segment index of every tile
     ddp::SegTables tables{};
     uint8_t* d_unused = nullptr;
     uint8_t* h_unused = nullptr;             // pinned
@@ -67,6 +69,8 @@ struct ddp_ctx {
     std::vector<std::pair<int32_t, int32_t>> log_running, log_closed;
     std::vector<uint8_t> used_running, used_closed;
     std::vector<TimedLaunch> timed;
+    size_t open_group = static_cast<size_t>(-1);   // timing mode 2: the running iteration's entry
+    bool ordered_in_call = false;   // reduce stream already ordered after backward in this API call
     std::string err;
 };
 
@@ -95,7 +99,7 @@ ddp::Scale make_scale(int R) {
 
 int32_t timed_begin(ddp_ctx* c, int32_t kind, int32_t bucket, hipStream_t s, size_t* slot) {
     *slot = static_cast<size_t>(-1);
-    if (!c->timing) return DDP_OK;
+    if (c->timing != 1) return DDP_OK;
     TimedLaunch t{kind, bucket, nullptr, nullptr};
     HIPCHK(c, hipEventCreate(&t.start));
     HIPCHK(c, hipEventCreate(&t.stop));
@@ -117,6 +121,7 @@ void drop_timed(ddp_ctx* c) {
         if (t.stop) (void)hipEventDestroy(t.stop);
     }
     c->timed.clear();
+    c->open_group = static_cast<size_t>(-1);
 }
 
 // Enqueue everything bucket b needs on the reduce stream.
@@ -129,28 +134,51 @@ int32_t launch_bucket(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t ca
     const int64_t tile_base = c->h_tile0[seg_begin];
     const int64_t ntiles = c->h_tile0[seg_end] - tile_base;
     if (c->backward != c->reduce) {
-        HIPCHK(c, hipEventRecord(c->ev_ready[b], c->backward));
-        HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_ready[b], 0));
+        // Order the bucket after the gradient-producing work enqueued so far.
+        // If the backward stream has already drained there is nothing to wait
+        // for, and the two queue packets are saved.
+        // Within one API call the caller cannot enqueue anything in between,
+        // so one ordering point serves every bucket the call launches.
+        if (!c->ordered_in_call) {
+            const hipError_t q = hipStreamQuery(c->backward);
+            if (q == hipErrorNotReady) {
+                HIPCHK(c, hipEventRecord(c->ev_ready[b], c->backward));
+                HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_ready[b], 0));
+            } else if (q != hipSuccess) {
+                return fail(c, DDP_ERR_HIP, std::string("hipStreamQuery: ") + hipGetErrorString(q));
+            }
+            c->ordered_in_call = true;
+        }
     }
     const ddp::Scale sc = make_scale(c->R);
     size_t slot;
     int32_t rc;
+    if (c->timing == 2 && c->open_group == static_cast<size_t>(-1)) {
+        // one event pair per iteration: opened by its first bucket launch
+        TimedLaunch t{DDP_K_ITERATION, 0, nullptr, nullptr};
+        HIPCHK(c, hipEventCreate(&t.start));
+        HIPCHK(c, hipEventCreate(&t.stop));
+        HIPCHK(c, hipEventRecord(t.start, c->reduce));
+        c->timed.push_back(t);
+        c->open_group = c->timed.size() - 1;
+    }
+    if (c->timing == 2) c->timed[c->open_group].bucket += 1;   // counts the launches
     if (c->pipeline == DDP_PIPELINE_STAGED) {
         char* in0 = c->slabs + c->bucket_slab_off[b];
         char* out = c->slabs + static_cast<int64_t>(c->R) * c->slab_stride + c->bucket_slab_off[b];
         if ((rc = timed_begin(c, DDP_K_PACK, b, c->reduce, &slot)) != DDP_OK) return rc;
-        HIPCHK(c, ddp::launch_pack(c->tables, seg_begin, seg_end, tile_base, ntiles, c->slabs,
-                                   c->slab_stride, c->R, d_unused, c->reduce));
+        HIPCHK(c, ddp::launch_pack(c->tables, tile_base, ntiles, c->slabs, c->slab_stride, c->R,
+                                   d_unused, c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
         if ((rc = timed_begin(c, DDP_K_REDUCE, b, c->reduce, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_flat_reduce(bk.dtype, in0, c->slab_stride, out, c->bucket_vecs[b],
-                                          c->R, sc, c->reduce_blocks, c->nontemporal != 0,
-                                          c->reduce));
+                                          c->R, sc, c->reduce_blocks, c->unroll,
+                                          c->nontemporal != 0, c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
     } else {
         if ((rc = timed_begin(c, DDP_K_REDUCE, b, c->reduce, &slot)) != DDP_OK) return rc;
-        HIPCHK(c, ddp::launch_fused_reduce(bk.dtype, c->tables, seg_begin, seg_end, tile_base,
-                                           ntiles, c->R, c->write_all ? c->R : 1, d_unused, sc,
+        HIPCHK(c, ddp::launch_fused_reduce(bk.dtype, c->tables, tile_base, ntiles, c->R,
+                                           c->write_all ? c->R : 1, d_unused, sc, c->unroll,
                                            c->nontemporal != 0, c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
     }
@@ -170,13 +198,14 @@ void release_device(ddp_ctx* c) {
         if (*e) { (void)hipEventDestroy(*e); *e = nullptr; }
     if (c->slabs) (void)hipFree(c->slabs);
     if (c->d_tables) (void)hipFree(c->d_tables);
+    if (c->d_tile_seg) (void)hipFree(c->d_tile_seg);
     if (c->d_unused) (void)hipFree(c->d_unused);
     if (c->d_micro) (void)hipFree(c->d_micro);
     if (c->d_emit) (void)hipFree(c->d_emit);
     if (c->h_unused) (void)hipHostFree(c->h_unused);
     if (c->h_micro) (void)hipHostFree(c->h_micro);
     if (c->h_emit) (void)hipHostFree(c->h_emit);
-    c->slabs = nullptr; c->d_tables = nullptr; c->d_unused = nullptr; c->d_micro = nullptr;
+    c->slabs = nullptr; c->d_tables = nullptr; c->d_tile_seg = nullptr; c->d_unused = nullptr; c->d_micro = nullptr;
     c->d_emit = nullptr; c->h_unused = nullptr; c->h_micro = nullptr; c->h_emit = nullptr;
 }
 
@@ -257,7 +286,12 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
                 (void)hipSetDevice(c->device);
                 drop_timed(c);
             }
-            c->timing = value != 0 && !c->plan_only;
+            if (value < 0 || value > 2) return fail(c, DDP_ERR_ARG, "timing mode must be 0, 1 or 2");
+            c->timing = c->plan_only ? 0 : static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_REDUCE_UNROLL:
+            if (value != 1 && value != 2 && value != 4) return fail(c, DDP_ERR_ARG, "unroll must be 1, 2 or 4");
+            c->unroll = static_cast<int32_t>(value);
             return DDP_OK;
         case DDP_OPT_REDUCE_BLOCKS:
             if (value < 0 || value > (1 << 30)) return fail(c, DDP_ERR_ARG, "bad block bound");
@@ -347,33 +381,45 @@ int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
             return fail(c, DDP_ERR_UNSUPPORTED, "model too large for one launch grid");
         }
         HIPCHK(c, hipSetDevice(c->device));
-        // one allocation for all tables: numel, flat_byte, tile0, grad pointers, param, dtype
+        // one allocation for the segment records and the pointer rows
         const int64_t R = c->R;
-        const size_t bytes = sizeof(int64_t) * (n + n + (n + 1)) + sizeof(void*) * R * n +
-                             sizeof(int32_t) * (n + n);
-        std::vector<char> host(bytes);
-        char* h = host.data();
-        size_t at = 0;
-        auto put = [&](const void* src, size_t len) { std::memcpy(h + at, src, len); size_t o = at; at += len; return o; };
-        const size_t o_numel = put(numel.data(), sizeof(int64_t) * n);
-        const size_t o_flat = put(flat_byte.data(), sizeof(int64_t) * n);
-        const size_t o_tile0 = put(c->h_tile0.data(), sizeof(int64_t) * (n + 1));
+        std::vector<ddp::SegInfo> seg(n);
         std::vector<void*> grad(static_cast<size_t>(R) * n);
-        for (int64_t r = 0; r < R; ++r)
-            for (int32_t g = 0; g < n; ++g) grad[r * n + g] = c->grad_ptrs[r * n + param[g]];
-        const size_t o_grad = put(grad.data(), sizeof(void*) * R * n);
-        const size_t o_param = put(param.data(), sizeof(int32_t) * n);
-        const size_t o_dtype = put(dtype.data(), sizeof(int32_t) * n);
+        for (int32_t g = 0; g < n; ++g) {
+            bool cong = true;
+            for (int64_t r = 0; r < R; ++r) {
+                void* ptr = c->grad_ptrs[r * n + param[g]];
+                grad[g * R + r] = ptr;
+                cong = cong && ((reinterpret_cast<uintptr_t>(ptr) ^ reinterpret_cast<uintptr_t>(c->grad_ptrs[param[g]])) & 15u) == 0;
+            }
+            seg[g].numel = numel[g];
+            seg[g].tile0 = c->h_tile0[g];
+            seg[g].flat_byte = flat_byte[g];
+            seg[g].param = param[g];
+            seg[g].flags = dtype[g] | (cong ? 0x100 : 0);
+        }
+        const size_t seg_bytes = sizeof(ddp::SegInfo) * n;
+        const size_t bytes = seg_bytes + sizeof(void*) * R * n;
+        std::vector<char> host(bytes);
+        std::memcpy(host.data(), seg.data(), seg_bytes);
+        std::memcpy(host.data() + seg_bytes, grad.data(), sizeof(void*) * R * n);
         HIPCHK(c, hipMalloc(&c->d_tables, bytes));
-        HIPCHK(c, hipMemcpy(c->d_tables, h, bytes, hipMemcpyHostToDevice));
+        HIPCHK(c, hipMemcpy(c->d_tables, host.data(), bytes, hipMemcpyHostToDevice));
         char* d = static_cast<char*>(c->d_tables);
-        c->tables.numel = reinterpret_cast<const int64_t*>(d + o_numel);
-        c->tables.flat_byte = reinterpret_cast<const int64_t*>(d + o_flat);
-        c->tables.tile0 = reinterpret_cast<const int64_t*>(d + o_tile0);
-        c->tables.grad = reinterpret_cast<void* const*>(d + o_grad);
-        c->tables.param = reinterpret_cast<const int32_t*>(d + o_param);
-        c->tables.dtype = reinterpret_cast<const int32_t*>(d + o_dtype);
+        c->tables.seg = reinterpret_cast<const ddp::SegInfo*>(d);
+        c->tables.grad = reinterpret_cast<void* const*>(d + seg_bytes);
         c->tables.G = n;
+        c->tables.R = c->R;
+        {
+            std::vector<int32_t> tile_seg(static_cast<size_t>(c->h_tile0[n]));
+            for (int32_t g = 0; g < n; ++g)
+                for (int64_t tl = c->h_tile0[g]; tl < c->h_tile0[g + 1]; ++tl) tile_seg[tl] = g;
+            const size_t tb = sizeof(int32_t) * (tile_seg.empty() ? 1 : tile_seg.size());
+            HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_tile_seg), tb));
+            if (!tile_seg.empty())
+                HIPCHK(c, hipMemcpy(c->d_tile_seg, tile_seg.data(), sizeof(int32_t) * tile_seg.size(), hipMemcpyHostToDevice));
+            c->tables.tile_seg = c->d_tile_seg;
+        }
 
         HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_unused), static_cast<size_t>(n)));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_unused), static_cast<size_t>(n), hipHostMallocDefault));
@@ -426,9 +472,7 @@ int32_t ddp_get_bucket_ptr(const ddp_ctx* c, int32_t b, int32_t r, void** ptr) {
     return DDP_OK;
 }
 
-int32_t ddp_mark_ready(ddp_ctx* c, int32_t param_id) {
-    if (!c) return DDP_ERR_ARG;
-    if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready before ddp_build_buckets");
+static int32_t mark_one(ddp_ctx* c, int32_t param_id) {
     std::vector<int32_t> launch;
     const int rc = c->tracker.mark(param_id, launch);
     if (rc == -1) return fail(c, DDP_ERR_ARG, "ddp_mark_ready: parameter id out of range");
@@ -442,10 +486,19 @@ int32_t ddp_mark_ready(ddp_ctx* c, int32_t param_id) {
     return DDP_OK;
 }
 
+int32_t ddp_mark_ready(ddp_ctx* c, int32_t param_id) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready before ddp_build_buckets");
+    c->ordered_in_call = false;
+    return mark_one(c, param_id);
+}
+
 int32_t ddp_mark_ready_many(ddp_ctx* c, const int32_t* ids, int32_t count) {
     if (!c || (count > 0 && !ids) || count < 0) return DDP_ERR_ARG;
+    if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready_many before ddp_build_buckets");
+    c->ordered_in_call = false;
     for (int32_t k = 0; k < count; ++k) {
-        const int32_t st = ddp_mark_ready(c, ids[k]);
+        const int32_t st = mark_one(c, ids[k]);
         if (st != DDP_OK) return st;
     }
     return DDP_OK;
@@ -456,6 +509,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_finalize_backward before ddp_build_buckets");
     const int32_t n = static_cast<int32_t>(c->plan.params.size());
     const int32_t marks = c->tracker.marks();
+    c->ordered_in_call = false;
     std::vector<int32_t> launch;
     c->tracker.drain(launch);
     const uint8_t* flags = nullptr;
@@ -479,11 +533,15 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
         if (st != DDP_OK) return st;
     }
     if (!c->plan_only) {
+        if (c->open_group != static_cast<size_t>(-1)) {      // closes this iteration's bucket launches
+            HIPCHK(c, hipEventRecord(c->timed[c->open_group].stop, c->reduce));
+            c->open_group = static_cast<size_t>(-1);
+        }
         if (c->pipeline == DDP_PIPELINE_STAGED) {
             size_t slot;
             int32_t rc;
             if ((rc = timed_begin(c, DDP_K_UNPACK, -1, c->reduce, &slot)) != DDP_OK) return rc;
-            HIPCHK(c, ddp::launch_unpack(c->tables, 0, n, 0, c->h_tile0[n],
+            HIPCHK(c, ddp::launch_unpack(c->tables, 0, c->h_tile0[n],
                                          c->slabs + static_cast<int64_t>(c->R) * c->slab_stride,
                                          c->write_all ? c->R : 1, c->reduce));
             if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
@@ -609,7 +667,8 @@ int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, cons
                                        c->backward));
         }
         if (mark) {
-            const int32_t st = ddp_mark_ready(c, p);
+            c->ordered_in_call = false;   // a kernel was just enqueued on the backward stream
+            const int32_t st = mark_one(c, p);
             if (st != DDP_OK) return st;
         }
     }

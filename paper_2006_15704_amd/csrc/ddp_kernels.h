@@ -21,14 +21,23 @@ inline int64_t tiles_for(int64_t numel, int es) {
 
 // Device-resident tables over the G segments (parameters in bucket-major fill
 // order) of the model.
+struct SegInfo {               // 32 bytes, read with one scalar load
+    int64_t numel;             // elements
+    int64_t tile0;             // first tile of the segment in the global tile numbering
+    int64_t flat_byte;         // byte offset of the segment inside a replica slab
+    int32_t param;             // registration index
+    int32_t flags;             // bits 0-7: element type; bit 8: all R gradient tensors share
+                               // replica 0's address modulo 16
+    __host__ __device__ int dtype() const { return flags & 0xFF; }
+    __host__ __device__ bool congruent() const { return (flags & 0x100) != 0; }
+};
+
 struct SegTables {
-    const int64_t* numel;      // [G] elements
-    const int64_t* flat_byte;  // [G] byte offset of the segment inside a replica slab
-    const int64_t* tile0;      // [G+1] exclusive prefix sum of tiles_for()
-    const int32_t* param;      // [G] registration index
-    const int32_t* dtype;      // [G] element type
-    void* const* grad;         // [R*G] replica r's gradient of segment g at [r*G+g]
+    const SegInfo* seg;        // [G]
+    const int32_t* tile_seg;   // [tiles] segment that each tile belongs to
+    void* const* grad;         // [G*R] replica r's gradient of segment g at [g*R+r]
     int32_t G;
+    int32_t R;
 };
 
 struct Scale {       // y = use_mul ? s * mul : s / div
@@ -38,29 +47,29 @@ struct Scale {       // y = use_mul ? s * mul : s / div
 };
 
 // All segment launches cover the tiles [tile_base, tile_base + ntiles) of the
-// global tile numbering (tile0), which must lie inside segments
-// [seg_begin, seg_end).
+// global tile numbering (tile0 / tile_seg).
 
 // K1: gradients -> flat replica slabs for all `nrep` replicas.  unused (may be
 // null): per-parameter flags, 1 = write zeros and do not read the gradient.
-hipError_t launch_pack(const SegTables& t, int seg_begin, int seg_end, int64_t tile_base,
-                       int64_t ntiles, char* slab0, int64_t slab_stride, int nrep,
-                       const uint8_t* unused, hipStream_t s);
+hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
+                       int64_t slab_stride, int nrep, const uint8_t* unused, hipStream_t s);
 
 // K3: averaged slab -> gradient tensors of replicas [0, nrep).
-hipError_t launch_unpack(const SegTables& t, int seg_begin, int seg_end, int64_t tile_base,
-                         int64_t ntiles, const char* out_slab, int nrep, hipStream_t s);
+hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
+                         const char* out_slab, int nrep, hipStream_t s);
 
 // K2 (staged): out[v] = scale(sum_r in_r[v]) over nvec 16-byte vectors;
-// in_r = in0 + r*stride.  max_blocks > 0 bounds the grid (blocks then loop).
+// in_r = in0 + r*stride.  unroll = vectors per thread (1, 2 or 4);
+// max_blocks > 0 bounds the grid (blocks then loop).
 hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* out, int64_t nvec,
-                              int R, Scale sc, int max_blocks, bool nontemporal, hipStream_t s);
+                              int R, Scale sc, int max_blocks, int unroll, bool nontemporal,
+                              hipStream_t s);
 
 // K2 (fused): gather R replicas through the segment table, reduce, scatter to
 // the gradient tensors of replicas [0, nwrite).
-hipError_t launch_fused_reduce(int dtype, const SegTables& t, int seg_begin, int seg_end,
-                               int64_t tile_base, int64_t ntiles, int R, int nwrite,
-                               const uint8_t* unused, Scale sc, bool nontemporal, hipStream_t s);
+hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
+                               int R, int nwrite, const uint8_t* unused, Scale sc, int unroll,
+                               bool nontemporal, hipStream_t s);
 
 // K4: grad[r][g] += micro[r*n + param[g]] for all segments and replicas
 // (null micro pointers are skipped).  ntiles = tile0[G].

@@ -16,14 +16,37 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Every gradient, slab and table lives in global memory.  Pointers that are
+// read from tables carry no address space, and the compiler would fall back to
+// generic (flat) accesses for them; the casts below keep all traffic on the
+// global path.
+#define DDP_GLOBAL __attribute__((address_space(1)))
+typedef DDP_GLOBAL const u32x4* gc_u32x4;
+typedef DDP_GLOBAL u32x4* g_u32x4;
+
+template <typename T>
+__device__ __forceinline__ T gload(const char* p) {
+    return *(DDP_GLOBAL const T*)(p);
+}
+template <typename T>
+__device__ __forceinline__ void gstore(char* p, T v) {
+    *(DDP_GLOBAL T*)(p) = v;
+}
+
 template <bool NT>
 __device__ __forceinline__ u32x4 load16(const char* p) {
-    const u32x4* q = reinterpret_cast<const u32x4*>(p);
+    gc_u32x4 q = (gc_u32x4)(p);
     if (NT) return __builtin_nontemporal_load(q);
     return *q;
 }
 __device__ __forceinline__ void store16(char* p, u32x4 v) {
-    *reinterpret_cast<u32x4*>(p) = v;
+    *(g_u32x4)(p) = v;
+}
+// Results that are not read again soon are stored with the non-temporal hint.
+template <bool NT>
+__device__ __forceinline__ void store16s(char* p, u32x4 v) {
+    if (NT) __builtin_nontemporal_store(v, (g_u32x4)(p));
+    else *(g_u32x4)(p) = v;
 }
 __device__ __forceinline__ u32x4 zero16() {
     u32x4 z = {0u, 0u, 0u, 0u};
@@ -46,10 +69,10 @@ template <> struct Fmt<0> {   // binary32
         return v;
     }
     static __device__ __forceinline__ float load1(const char* p) {
-        return *reinterpret_cast<const float*>(p);
+        return gload<float>(p);
     }
     static __device__ __forceinline__ void store1(char* p, float y) {
-        *reinterpret_cast<float*>(p) = y;
+        gstore<float>(p, y);
     }
 };
 
@@ -75,10 +98,10 @@ template <> struct Fmt<1> {   // binary16: exact widening, round-to-nearest-even
         return v;
     }
     static __device__ __forceinline__ float load1(const char* p) {
-        return up(*reinterpret_cast<const uint16_t*>(p));
+        return up(gload<uint16_t>(p));
     }
     static __device__ __forceinline__ void store1(char* p, float y) {
-        *reinterpret_cast<uint16_t*>(p) = static_cast<uint16_t>(down(y));
+        gstore<uint16_t>(p, static_cast<uint16_t>(down(y)));
     }
 };
 
@@ -104,28 +127,15 @@ template <> struct Fmt<2> {   // bfloat16 = upper half of binary32
         return v;
     }
     static __device__ __forceinline__ float load1(const char* p) {
-        return __uint_as_float(static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(p)) << 16);
+        return __uint_as_float(static_cast<uint32_t>(gload<uint16_t>(p)) << 16);
     }
     static __device__ __forceinline__ void store1(char* p, float y) {
-        *reinterpret_cast<uint16_t*>(p) = static_cast<uint16_t>(down(y));
+        gstore<uint16_t>(p, static_cast<uint16_t>(down(y)));
     }
 };
 
 __device__ __forceinline__ float apply_scale(const Scale& sc, float s) {
     return sc.use_mul ? s * sc.mul : s / sc.div;
-}
-
-// Block-uniform lookup: the segment whose tile range contains `tile`, i.e. the
-// largest g in [seg_begin, seg_end) with tile0[g] <= tile (segments without
-// tiles are skipped over by construction).
-__device__ __forceinline__ int find_segment(const int64_t* __restrict__ tile0, int seg_begin,
-                                            int seg_end, int64_t tile) {
-    int lo = seg_begin, hi = seg_end - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (tile0[mid] <= tile) lo = mid; else hi = mid - 1;
-    }
-    return lo;
 }
 
 // Vectors are cut at 16-byte boundaries of the destination.  `sh` elements
@@ -150,12 +160,12 @@ __device__ __forceinline__ u32x4 gather16(const char* p) {
     u32x4 v;
     if (ES == 4) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const uint32_t*>(p + 4 * i);
+        for (int i = 0; i < 4; ++i) v[i] = gload<uint32_t>(p + 4 * i);
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t lo = *reinterpret_cast<const uint16_t*>(p + 4 * i);
-            const uint32_t hi = *reinterpret_cast<const uint16_t*>(p + 4 * i + 2);
+            const uint32_t lo = gload<uint16_t>(p + 4 * i);
+            const uint32_t hi = gload<uint16_t>(p + 4 * i + 2);
             v[i] = lo | (hi << 16);
         }
     }
@@ -191,11 +201,9 @@ __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __
                 const int64_t idx = e[k] + i;
                 if (idx < 0 || idx >= numel) continue;
                 if (ES == 4) {
-                    *reinterpret_cast<uint32_t*>(dst + idx * 4) =
-                        zero ? 0u : *reinterpret_cast<const uint32_t*>(src + idx * 4);
+                    gstore<uint32_t>(dst + idx * 4, zero ? 0u : gload<uint32_t>(src + idx * 4));
                 } else {
-                    *reinterpret_cast<uint16_t*>(dst + idx * 2) =
-                        zero ? uint16_t(0) : *reinterpret_cast<const uint16_t*>(src + idx * 2);
+                    gstore<uint16_t>(dst + idx * 2, zero ? uint16_t(0) : gload<uint16_t>(src + idx * 2));
                 }
             }
         }
@@ -204,27 +212,27 @@ __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __
 
 // PACK: grad[r][g] -> slab_r + flat_byte[g];  UNPACK: out slab -> grad[r][g].
 template <bool PACK>
-__global__ __launch_bounds__(BLOCK) void seg_copy_kernel(SegTables t, int seg_begin, int seg_end,
-                                                         int64_t tile_base, char* slab0,
-                                                         int64_t slab_stride,
+__global__ __launch_bounds__(BLOCK) void seg_copy_kernel(SegTables t, int64_t tile_base,
+                                                         char* slab0, int64_t slab_stride,
                                                          const uint8_t* __restrict__ unused) {
     const int64_t tile = tile_base + blockIdx.x;
     const int r = blockIdx.y;
-    const int g = find_segment(t.tile0, seg_begin, seg_end, tile);
-    const int64_t numel = t.numel[g];
-    const int64_t ltile = tile - t.tile0[g];
-    char* grad = static_cast<char*>(t.grad[static_cast<int64_t>(r) * t.G + g]);
-    const bool zero = PACK && unused != nullptr && unused[t.param[g]] != 0;
+    const int g = t.tile_seg[tile];
+    const SegInfo si = t.seg[g];
+    const int64_t numel = si.numel;
+    const int64_t ltile = tile - si.tile0;
+    char* grad = static_cast<char*>(t.grad[static_cast<int64_t>(g) * t.R + r]);
+    const bool zero = PACK && unused != nullptr && unused[si.param] != 0;
     const char* src;
     char* dst;
     if (PACK) {
         src = grad;
-        dst = slab0 + r * slab_stride + t.flat_byte[g];
+        dst = slab0 + r * slab_stride + si.flat_byte;
     } else {
-        src = slab0 + t.flat_byte[g];
+        src = slab0 + si.flat_byte;
         dst = grad;
     }
-    if (t.dtype[g] == 0) copy_tile<4>(src, dst, numel, ltile, zero);
+    if (si.dtype() == 0) copy_tile<4>(src, dst, numel, ltile, zero);
     else copy_tile<2>(src, dst, numel, ltile, zero);
 }
 
@@ -236,6 +244,50 @@ __device__ __forceinline__ void add_into(float (&acc)[Fmt<DT>::VEC], u32x4 x) {
     Fmt<DT>::widen(x, f);
 #pragma unroll
     for (int i = 0; i < Fmt<DT>::VEC; ++i) acc[i] += f[i];
+}
+
+// Interior work (every vector of the block lies inside the data): no lane is
+// predicated.  base_of(r) returns replica r's block-uniform base address; the
+// per-thread part of the address is a 32-bit byte offset, so the loads take the
+// scalar-base + vector-offset form.  All C*U loads are issued before the adds,
+// which run in ascending r.
+template <int DT, bool NT, int C, int U, typename BaseFn>
+__device__ __forceinline__ void chunk_interior(BaseFn base_of, int r, const uint32_t (&lane_off)[U],
+                                               float (&acc)[U][Fmt<DT>::VEC]) {
+    const char* base[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) base[i] = base_of(r + i);
+    u32x4 x[C][U];
+#pragma unroll
+    for (int i = 0; i < C; ++i)
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[i][u] = load16<NT>(base[i] + lane_off[u]);
+#pragma unroll
+    for (int i = 0; i < C; ++i)
+#pragma unroll
+        for (int u = 0; u < U; ++u) add_into<DT>(acc[u], x[i][u]);
+}
+
+template <int DT, bool NT, int U, typename BaseFn>
+__device__ __forceinline__ void sum_interior(BaseFn base_of, int R, const uint32_t (&lane_off)[U],
+                                             float (&acc)[U][Fmt<DT>::VEC]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < Fmt<DT>::VEC; ++i) acc[u][i] = -0.0f;   // -0 + x == x for every x
+    int r = 0;
+    for (; r + 8 <= R; r += 8) chunk_interior<DT, NT, 8, U>(base_of, r, lane_off, acc);
+    if (r + 4 <= R) { chunk_interior<DT, NT, 4, U>(base_of, r, lane_off, acc); r += 4; }
+    if (r + 2 <= R) { chunk_interior<DT, NT, 2, U>(base_of, r, lane_off, acc); r += 2; }
+    if (r < R) { chunk_interior<DT, NT, 1, U>(base_of, r, lane_off, acc); }
+}
+
+template <int DT>
+__device__ __forceinline__ u32x4 scaled(const Scale& sc, const float (&acc)[Fmt<DT>::VEC]) {
+    float y[Fmt<DT>::VEC];
+#pragma unroll
+    for (int i = 0; i < Fmt<DT>::VEC; ++i) y[i] = apply_scale(sc, acc[i]);
+    return Fmt<DT>::narrow(y);
 }
 
 // C replicas starting at r, U vectors per thread: issue all C*U loads, then
@@ -257,53 +309,64 @@ __device__ __forceinline__ void chunk_flat(const char* __restrict__ in0, int64_t
         for (int u = 0; u < U; ++u) add_into<DT>(acc[u], x[i][u]);
 }
 
-template <int DT, bool NT>
+// One block iteration handles a row of BLOCK*U consecutive vectors; with the
+// default grid every block handles exactly one row, so blocks stream through
+// memory in launch order.
+template <int DT, bool NT, int U>
 __global__ __launch_bounds__(BLOCK) void flat_reduce_kernel(const char* __restrict__ in0,
                                                             int64_t stride, char* __restrict__ out,
                                                             int64_t nvec, int R, Scale sc) {
     constexpr int VEC = Fmt<DT>::VEC;
-    constexpr int U = 2;
-    const int64_t ntiles = (nvec + TILE_VECS - 1) / TILE_VECS;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-#pragma unroll 1
-        for (int step = 0; step < TILE_VECS / (BLOCK * U); ++step) {
-            int64_t off[U];
-            bool ok[U];
-            float acc[U][VEC];
+    const int64_t nrows = (nvec + BLOCK * U - 1) / (BLOCK * U);
+    for (int64_t row = blockIdx.x; row < nrows; row += gridDim.x) {
+        float acc[U][VEC];
+        if ((row + 1) * (BLOCK * U) <= nvec) {
+            const int64_t row_byte = row * (BLOCK * U * 16);
+            uint32_t lane_off[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t v = tile * TILE_VECS + (step * U + u) * BLOCK + threadIdx.x;
-                ok[u] = v < nvec;
-                off[u] = v * 16;
+            for (int u = 0; u < U; ++u) lane_off[u] = (u * BLOCK + threadIdx.x) * 16u;
+            sum_interior<DT, NT, U>(
+                [&](int r) { return in0 + static_cast<int64_t>(r) * stride + row_byte; }, R, lane_off, acc);
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[u][i] = -0.0f;   // -0 + x == x for every x
-            }
-            int r = 0;
-            for (; r + 8 <= R; r += 8) chunk_flat<DT, NT, 8, U>(in0, stride, r, off, ok, acc);
-            if (r + 4 <= R) { chunk_flat<DT, NT, 4, U>(in0, stride, r, off, ok, acc); r += 4; }
-            if (r + 2 <= R) { chunk_flat<DT, NT, 2, U>(in0, stride, r, off, ok, acc); r += 2; }
-            if (r < R) { chunk_flat<DT, NT, 1, U>(in0, stride, r, off, ok, acc); }
+            for (int u = 0; u < U; ++u)
+                store16s<NT>(out + row_byte + lane_off[u], scaled<DT>(sc, acc[u]));
+            continue;
+        }
+        int64_t off[U];
+        bool ok[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (!ok[u]) continue;
-                float y[VEC];
+        for (int u = 0; u < U; ++u) {
+            const int64_t v = row * (BLOCK * U) + u * BLOCK + threadIdx.x;
+            ok[u] = v < nvec;
+            off[u] = v * 16;
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) y[i] = apply_scale(sc, acc[u][i]);
-                store16(out + off[u], Fmt<DT>::narrow(y));
-            }
+            for (int i = 0; i < VEC; ++i) acc[u][i] = -0.0f;   // -0 + x == x for every x
+        }
+        int r = 0;
+        for (; r + 8 <= R; r += 8) chunk_flat<DT, NT, 8, U>(in0, stride, r, off, ok, acc);
+        if (r + 4 <= R) { chunk_flat<DT, NT, 4, U>(in0, stride, r, off, ok, acc); r += 4; }
+        if (r + 2 <= R) { chunk_flat<DT, NT, 2, U>(in0, stride, r, off, ok, acc); r += 2; }
+        if (r < R) { chunk_flat<DT, NT, 1, U>(in0, stride, r, off, ok, acc); }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!ok[u]) continue;
+            float y[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) y[i] = apply_scale(sc, acc[u][i]);
+            store16s<NT>(out + off[u], Fmt<DT>::narrow(y));
         }
     }
 }
 
 // Fused variant: replica pointers come from the segment table.
 template <int DT, bool NT, int C, int U>
-__device__ __forceinline__ void chunk_seg(void* const* __restrict__ grad, int64_t G, int g, int r,
+__device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r,
                                           const int64_t (&off)[U], const bool (&ok)[U],
                                           float (&acc)[U][Fmt<DT>::VEC]) {
     u32x4 x[C][U];
 #pragma unroll
     for (int i = 0; i < C; ++i) {
-        const char* p = static_cast<const char*>(grad[static_cast<int64_t>(r + i) * G + g]);
+        const char* p = static_cast<const char*>(row[r + i]);
 #pragma unroll
         for (int u = 0; u < U; ++u) x[i][u] = ok[u] ? load16<NT>(p + off[u]) : zero16();
     }
@@ -321,33 +384,52 @@ __device__ __forceinline__ void reduce_element(const SegTables& t, int g, int R,
     if (!zero) {
         float s = -0.0f;
         for (int r = 0; r < R; ++r)
-            s += Fmt<DT>::load1(static_cast<const char*>(t.grad[static_cast<int64_t>(r) * t.G + g]) + idx * ES);
+            s += Fmt<DT>::load1(static_cast<const char*>(t.grad[static_cast<int64_t>(g) * t.R + r]) + idx * ES);
         y = apply_scale(sc, s);
     }
     for (int w = 0; w < nwrite; ++w)
-        Fmt<DT>::store1(static_cast<char*>(t.grad[static_cast<int64_t>(w) * t.G + g]) + idx * ES, y);
+        Fmt<DT>::store1(static_cast<char*>(t.grad[static_cast<int64_t>(g) * t.R + w]) + idx * ES, y);
 }
 
-template <int DT, bool NT>
-__global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int seg_begin,
-                                                             int seg_end, int64_t tile_base, int R,
+template <int DT, bool NT, int U>
+__global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int64_t tile_base, int R,
                                                              int nwrite,
                                                              const uint8_t* __restrict__ unused,
                                                              Scale sc) {
     constexpr int ES = Fmt<DT>::ES;
     constexpr int VEC = Fmt<DT>::VEC;
-    constexpr int U = 2;
     const int64_t tile = tile_base + blockIdx.x;
-    const int g = find_segment(t.tile0, seg_begin, seg_end, tile);
-    const int64_t numel = t.numel[g];
-    const int64_t ltile = tile - t.tile0[g];
-    const bool zero = unused != nullptr && unused[t.param[g]] != 0;
-    const char* dst0 = static_cast<const char*>(t.grad[g]);
+    const int g = t.tile_seg[tile];
+    const SegInfo si = t.seg[g];
+    const int64_t numel = si.numel;
+    const int64_t ltile = tile - si.tile0;
+    const bool zero = unused != nullptr && unused[si.param] != 0;
+    void* const* __restrict__ row = t.grad + static_cast<int64_t>(g) * t.R;   // this segment's R pointers
+    const char* dst0 = static_cast<const char*>(row[0]);
     const int sh = lead_in(dst0, ES);
-    bool fast = true;   // every replica's tensor sits at the same offset modulo 16
-    for (int r = 1; r < R; ++r)
-        fast = fast && congruent16(t.grad[static_cast<int64_t>(r) * t.G + g], dst0);
+    const bool fast = si.congruent();   // every replica's tensor sits at the same offset modulo 16
     const int64_t e_tile = ltile * (TILE_BYTES / ES) - sh;
+
+    if (fast && !zero && e_tile >= 0 && e_tile + TILE_BYTES / ES <= numel) {
+        // the whole tile is inside the segment and every replica is aligned alike
+        const int64_t tile_byte = e_tile * ES;
+#pragma unroll 1
+        for (int step = 0; step < TILE_VECS / (BLOCK * U); ++step) {
+            uint32_t lane_off[U];
+            float acc[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) lane_off[u] = ((step * U + u) * BLOCK + threadIdx.x) * 16u;
+            sum_interior<DT, NT, U>(
+                [&](int r) { return static_cast<const char*>(row[r]) + tile_byte; }, R, lane_off, acc);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const u32x4 out = scaled<DT>(sc, acc[u]);
+                for (int w = 0; w < nwrite; ++w)
+                    store16s<NT>(static_cast<char*>(row[w]) + tile_byte + lane_off[u], out);
+            }
+        }
+        return;
+    }
 
 #pragma unroll 1
     for (int step = 0; step < TILE_VECS / (BLOCK * U); ++step) {
@@ -366,10 +448,10 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int se
         }
         if (!zero && fast) {
             int r = 0;
-            for (; r + 8 <= R; r += 8) chunk_seg<DT, NT, 8, U>(t.grad, t.G, g, r, off, ok, acc);
-            if (r + 4 <= R) { chunk_seg<DT, NT, 4, U>(t.grad, t.G, g, r, off, ok, acc); r += 4; }
-            if (r + 2 <= R) { chunk_seg<DT, NT, 2, U>(t.grad, t.G, g, r, off, ok, acc); r += 2; }
-            if (r < R) { chunk_seg<DT, NT, 1, U>(t.grad, t.G, g, r, off, ok, acc); }
+            for (; r + 8 <= R; r += 8) chunk_seg<DT, NT, 8, U>(row, r, off, ok, acc);
+            if (r + 4 <= R) { chunk_seg<DT, NT, 4, U>(row, r, off, ok, acc); r += 4; }
+            if (r + 2 <= R) { chunk_seg<DT, NT, 2, U>(row, r, off, ok, acc); r += 2; }
+            if (r < R) { chunk_seg<DT, NT, 1, U>(row, r, off, ok, acc); }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -385,11 +467,11 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int se
                 // replica w's tensor is congruent with replica 0's when fast; for
                 // unused parameters only replica 0's alignment is known to be
                 // right, so the others go element by element below.
-                store16(static_cast<char*>(t.grad[g]) + off[u], out);
+                store16s<NT>(static_cast<char*>(row[0]) + off[u], out);
                 for (int w = 1; w < nwrite; ++w) {
-                    char* d = static_cast<char*>(t.grad[static_cast<int64_t>(w) * t.G + g]);
+                    char* d = static_cast<char*>(t.grad[static_cast<int64_t>(g) * t.R + w]);
                     if (fast) {
-                        store16(d + off[u], out);
+                        store16s<NT>(d + off[u], out);
                     } else {
                         for (int i = 0; i < VEC; ++i) Fmt<DT>::store1(d + (e[u] + i) * ES, 0.0f);
                     }
@@ -455,13 +537,14 @@ __global__ __launch_bounds__(BLOCK) void accumulate_kernel(SegTables t, int n,
                                                            void* const* __restrict__ micro) {
     const int64_t tile = blockIdx.x;
     const int r = blockIdx.y;
-    const int g = find_segment(t.tile0, 0, t.G, tile);
-    const char* src = static_cast<const char*>(micro[static_cast<int64_t>(r) * n + t.param[g]]);
+    const int g = t.tile_seg[tile];
+    const SegInfo si = t.seg[g];
+    const char* src = static_cast<const char*>(micro[static_cast<int64_t>(r) * n + si.param]);
     if (src == nullptr) return;
-    char* dst = static_cast<char*>(t.grad[static_cast<int64_t>(r) * t.G + g]);
-    const int64_t numel = t.numel[g];
-    const int64_t ltile = tile - t.tile0[g];
-    switch (t.dtype[g]) {
+    char* dst = static_cast<char*>(t.grad[static_cast<int64_t>(g) * t.R + r]);
+    const int64_t numel = si.numel;
+    const int64_t ltile = tile - si.tile0;
+    switch (si.dtype()) {
         case 0: accumulate_tile<0>(src, dst, numel, ltile); break;
         case 1: accumulate_tile<1>(src, dst, numel, ltile); break;
         default: accumulate_tile<2>(src, dst, numel, ltile); break;
@@ -489,8 +572,8 @@ __global__ __launch_bounds__(BLOCK) void emit_kernel(int64_t ticks, void* const*
     const char* src = static_cast<const char*>(ptrs[R + r]);
     const int64_t stride = static_cast<int64_t>(gridDim.x) * BLOCK;
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * BLOCK + threadIdx.x; i < nelem; i += stride) {
-        if (es == 4) reinterpret_cast<uint32_t*>(dst)[i] = reinterpret_cast<const uint32_t*>(src)[i];
-        else reinterpret_cast<uint16_t*>(dst)[i] = reinterpret_cast<const uint16_t*>(src)[i];
+        if (es == 4) gstore<uint32_t>(dst + i * 4, gload<uint32_t>(src + i * 4));
+        else gstore<uint16_t>(dst + i * 2, gload<uint16_t>(src + i * 2));
     }
 }
 
@@ -499,65 +582,80 @@ inline hipError_t after_launch() { return hipGetLastError(); }
 }  // namespace
 
 // ---- launch wrappers ---------------------------------------------------------
-hipError_t launch_pack(const SegTables& t, int seg_begin, int seg_end, int64_t tile_base,
-                       int64_t ntiles, char* slab0, int64_t slab_stride, int nrep,
-                       const uint8_t* unused, hipStream_t s) {
+hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
+                       int64_t slab_stride, int nrep, const uint8_t* unused, hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
-    hipLaunchKernelGGL(seg_copy_kernel<true>, grid, dim3(BLOCK), 0, s, t, seg_begin, seg_end,
-                       tile_base, slab0, slab_stride, unused);
+    hipLaunchKernelGGL(seg_copy_kernel<true>, grid, dim3(BLOCK), 0, s, t, tile_base, slab0,
+                       slab_stride, unused);
     return after_launch();
 }
 
-hipError_t launch_unpack(const SegTables& t, int seg_begin, int seg_end, int64_t tile_base,
-                         int64_t ntiles, const char* out_slab, int nrep, hipStream_t s) {
+hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
+                         const char* out_slab, int nrep, hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
-    hipLaunchKernelGGL(seg_copy_kernel<false>, grid, dim3(BLOCK), 0, s, t, seg_begin, seg_end,
-                       tile_base, const_cast<char*>(out_slab), int64_t(0),
-                       static_cast<const uint8_t*>(nullptr));
+    hipLaunchKernelGGL(seg_copy_kernel<false>, grid, dim3(BLOCK), 0, s, t, tile_base,
+                       const_cast<char*>(out_slab), int64_t(0), static_cast<const uint8_t*>(nullptr));
     return after_launch();
+}
+
+template <int DT, int U>
+static void flat_reduce_dispatch(bool nt, int64_t nrows, int max_blocks, hipStream_t s,
+                                 const char* in0, int64_t stride, char* out, int64_t nvec, int R,
+                                 Scale sc) {
+    int64_t blocks = nrows;
+    if (max_blocks > 0 && blocks > max_blocks) blocks = max_blocks;
+    dim3 grid(static_cast<unsigned>(blocks));
+    if (nt) hipLaunchKernelGGL((flat_reduce_kernel<DT, true, U>), grid, dim3(BLOCK), 0, s, in0, stride, out, nvec, R, sc);
+    else hipLaunchKernelGGL((flat_reduce_kernel<DT, false, U>), grid, dim3(BLOCK), 0, s, in0, stride, out, nvec, R, sc);
 }
 
 template <int DT>
-static void flat_reduce_dispatch(bool nt, dim3 grid, hipStream_t s, const char* in0, int64_t stride,
-                                 char* out, int64_t nvec, int R, Scale sc) {
-    if (nt) hipLaunchKernelGGL((flat_reduce_kernel<DT, true>), grid, dim3(BLOCK), 0, s, in0, stride, out, nvec, R, sc);
-    else hipLaunchKernelGGL((flat_reduce_kernel<DT, false>), grid, dim3(BLOCK), 0, s, in0, stride, out, nvec, R, sc);
+static void flat_reduce_unroll(int unroll, bool nt, int max_blocks, hipStream_t s, const char* in0,
+                               int64_t stride, char* out, int64_t nvec, int R, Scale sc) {
+    if (unroll >= 4) flat_reduce_dispatch<DT, 4>(nt, (nvec + BLOCK * 4 - 1) / (BLOCK * 4), max_blocks, s, in0, stride, out, nvec, R, sc);
+    else if (unroll >= 2) flat_reduce_dispatch<DT, 2>(nt, (nvec + BLOCK * 2 - 1) / (BLOCK * 2), max_blocks, s, in0, stride, out, nvec, R, sc);
+    else flat_reduce_dispatch<DT, 1>(nt, (nvec + BLOCK - 1) / BLOCK, max_blocks, s, in0, stride, out, nvec, R, sc);
 }
 
 hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* out, int64_t nvec,
-                              int R, Scale sc, int max_blocks, bool nontemporal, hipStream_t s) {
+                              int R, Scale sc, int max_blocks, int unroll, bool nontemporal,
+                              hipStream_t s) {
     if (nvec <= 0) return hipSuccess;
-    int64_t blocks = (nvec + TILE_VECS - 1) / TILE_VECS;
-    if (max_blocks > 0 && blocks > max_blocks) blocks = max_blocks;
-    dim3 grid(static_cast<unsigned>(blocks));
     switch (dtype) {
-        case 0: flat_reduce_dispatch<0>(nontemporal, grid, s, in0, stride, out, nvec, R, sc); break;
-        case 1: flat_reduce_dispatch<1>(nontemporal, grid, s, in0, stride, out, nvec, R, sc); break;
-        case 2: flat_reduce_dispatch<2>(nontemporal, grid, s, in0, stride, out, nvec, R, sc); break;
+        case 0: flat_reduce_unroll<0>(unroll, nontemporal, max_blocks, s, in0, stride, out, nvec, R, sc); break;
+        case 1: flat_reduce_unroll<1>(unroll, nontemporal, max_blocks, s, in0, stride, out, nvec, R, sc); break;
+        case 2: flat_reduce_unroll<2>(unroll, nontemporal, max_blocks, s, in0, stride, out, nvec, R, sc); break;
         default: return hipErrorInvalidValue;
     }
     return after_launch();
 }
 
-template <int DT>
-static void fused_dispatch(bool nt, dim3 grid, hipStream_t s, const SegTables& t, int seg_begin,
-                           int seg_end, int64_t tile_base, int R, int nwrite, const uint8_t* unused,
-                           Scale sc) {
-    if (nt) hipLaunchKernelGGL((fused_reduce_kernel<DT, true>), grid, dim3(BLOCK), 0, s, t, seg_begin, seg_end, tile_base, R, nwrite, unused, sc);
-    else hipLaunchKernelGGL((fused_reduce_kernel<DT, false>), grid, dim3(BLOCK), 0, s, t, seg_begin, seg_end, tile_base, R, nwrite, unused, sc);
+template <int DT, int U>
+static void fused_dispatch(bool nt, dim3 grid, hipStream_t s, const SegTables& t, int64_t tile_base,
+                           int R, int nwrite, const uint8_t* unused, Scale sc) {
+    if (nt) hipLaunchKernelGGL((fused_reduce_kernel<DT, true, U>), grid, dim3(BLOCK), 0, s, t, tile_base, R, nwrite, unused, sc);
+    else hipLaunchKernelGGL((fused_reduce_kernel<DT, false, U>), grid, dim3(BLOCK), 0, s, t, tile_base, R, nwrite, unused, sc);
 }
 
-hipError_t launch_fused_reduce(int dtype, const SegTables& t, int seg_begin, int seg_end,
-                               int64_t tile_base, int64_t ntiles, int R, int nwrite,
-                               const uint8_t* unused, Scale sc, bool nontemporal, hipStream_t s) {
+template <int DT>
+static void fused_unroll(int unroll, bool nt, dim3 grid, hipStream_t s, const SegTables& t,
+                         int64_t tile_base, int R, int nwrite, const uint8_t* unused, Scale sc) {
+    if (unroll >= 4) fused_dispatch<DT, 4>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
+    else if (unroll >= 2) fused_dispatch<DT, 2>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
+    else fused_dispatch<DT, 1>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
+}
+
+hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
+                               int R, int nwrite, const uint8_t* unused, Scale sc, int unroll,
+                               bool nontemporal, hipStream_t s) {
     if (ntiles <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles));
     switch (dtype) {
-        case 0: fused_dispatch<0>(nontemporal, grid, s, t, seg_begin, seg_end, tile_base, R, nwrite, unused, sc); break;
-        case 1: fused_dispatch<1>(nontemporal, grid, s, t, seg_begin, seg_end, tile_base, R, nwrite, unused, sc); break;
-        case 2: fused_dispatch<2>(nontemporal, grid, s, t, seg_begin, seg_end, tile_base, R, nwrite, unused, sc); break;
+        case 0: fused_unroll<0>(unroll, nontemporal, grid, s, t, tile_base, R, nwrite, unused, sc); break;
+        case 1: fused_unroll<1>(unroll, nontemporal, grid, s, t, tile_base, R, nwrite, unused, sc); break;
+        case 2: fused_unroll<2>(unroll, nontemporal, grid, s, t, tile_base, R, nwrite, unused, sc); break;
         default: return hipErrorInvalidValue;
     }
     return after_launch();

@@ -42,3 +42,23 @@ def read_golden(name):
             key, val = line.split(":", 1)
             out[key.strip()] = val.strip()
     return out
+
+
+def progress(msg: str) -> None:
+    """A progress line for long GPU tests: goes to the real stderr (not
+    captured by pytest) and, when the folder exists, to
+    gpurun_out/test_progress.log, so that a long test is not mistaken for a
+    hung one."""
+    line = f"[progress] {msg}\n"
+    try:
+        sys.__stderr__.write(line)
+        sys.__stderr__.flush()
+    except Exception:
+        pass
+    folder = os.path.join(ROOT, "gpurun_out")
+    if os.path.isdir(folder):
+        try:
+            with open(os.path.join(folder, "test_progress.log"), "a") as fh:
+                fh.write(line)
+        except Exception:
+            pass
