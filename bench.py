@@ -2,16 +2,23 @@
 """Benchmark of bucketed gradient synchronization on one MI355X.
 
 One "step" is one pass of the whole hot path over one batch of synthetic
-gradients: ready marks for every parameter in reverse registration order
-(launching each bucket's pack + reduce, or the fused one-pass kernel, as soon
-as it is complete and its predecessors have been launched), then the
-finalizing step (write-back of the averages), all through the C ABI.  Inputs
-are resident in HBM before the timed region starts.
+gradients, through the C ABI: ready marks for every parameter in reverse
+registration order (each bucket is launched as soon as it is complete and its
+predecessors have been launched), then the finalizing step.  Inputs are
+resident in HBM before the timed region starts.  The default pipeline is the
+one-pass (fused) one; `--pipeline staged` times the literal pack / reduce /
+unpack pipeline instead, and the default run also reports the staged
+pipeline's per-kernel rates in a `staged` sub-object.
 
-Prints ONE JSON line.  `value` is the algorithmic end-to-end rate
-(R + W) * B / ms_per_step (every replica gradient read once, the average
-written W = 1 times); `roofline` is the reduce kernel against the HBM peak;
-`cpu_baseline` is the CPU oracle on the same workload.
+Prints ONE JSON line.
+  value     (R + W) * B / ms_per_step: every replica gradient read once, the
+            average written W = 1 times -- the algorithmic end-to-end bytes of
+            one synchronization divided by the measured step time.
+  roofline  the reduce kernel (the dominant one) against the 8 TB/s HBM peak:
+            algorithmic bytes per launch (R + 1) * bucket_bytes divided by the
+            average launch duration, measured with HIP events on the reduction
+            stream inside the timed region.
+  cpu_baseline  the CPU oracle on the same workload.
 """
 from __future__ import annotations
 
@@ -35,6 +42,7 @@ WORKLOADS = {
     "resnet50": ("resnet50", 2, 8, 1e-2, 0, 25 << 20),
     "bert_large": ("bert_large", 3, 8, 1e-3, 0, 25 << 20),
     "tiny": ("tiny", 1, 2, 1.0, 0, 16384),
+    "uniform": ("uniform", 9, 8, 1e-2, 0, 25 << 20),     # diagnostic: 40 single-tensor 25 MiB buckets
 }
 
 
@@ -58,24 +66,69 @@ def read_traffic(workload, pipeline):
         return None
 
 
+def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup, timing_mode, args):
+    """Runs warmup + `steps` timed steps on a fresh context; returns a dict."""
+    with harness.Session(grads, cap, pipeline_code, same_stream=args.same_stream) as s:
+        ctx = s.ctx
+        if args.reduce_blocks is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_BLOCKS, args.reduce_blocks)
+        if args.plain_loads:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_NONTEMPORAL, 0)
+        if args.unroll is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_UNROLL, args.unroll)
+
+        def step():
+            lib.ddp_mark_ready_many(ctx, order)
+            lib.ddp_finalize_backward(ctx)
+
+        for _ in range(warmup):
+            step()
+        lib.ddp_synchronize(ctx)
+        torch.cuda.synchronize()
+
+        # timed region: `steps` steps with HIP events on the reduction stream
+        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 1 if timing_mode == "launch" else 2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        lib.ddp_synchronize(ctx)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        res = {"ms_per_step": (t1 - t0) * 1e3 / steps}
+        res["reduce"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_REDUCE)
+        res["pack"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_PACK)
+        res["unpack"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_UNPACK)
+        res["iteration"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_ITERATION)
+        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 0)
+        res["bucket_elems"] = [lib.ddp_get_bucket_info(ctx, b)[0] for b in range(s.n_buckets)]
+        res["n_buckets"] = s.n_buckets
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet50", choices=sorted(WORKLOADS))
-    ap.add_argument("--pipeline", default="staged", choices=["staged", "fused"])
+    ap.add_argument("--pipeline", default="fused", choices=["staged", "fused"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-staged-leg", action="store_true",
+                    help="skip the extra measurement of the staged pipeline's kernels")
     ap.add_argument("--reduce-blocks", type=int, default=None)
     ap.add_argument("--plain-loads", action="store_true")
     ap.add_argument("--unroll", type=int, default=None, choices=[1, 2, 4])
     ap.add_argument("--same-stream", action="store_true",
                     help="use one stream for backward and reduction (no event plumbing)")
-    ap.add_argument("--timing", default="launch", choices=["launch", "iteration"],
-                    help="HIP-event granularity in the timed region: one pair per kernel launch, "
-                         "or one pair around each iteration's bucket launches")
+    ap.add_argument("--timing", default=None, choices=["launch", "iteration"],
+                    help="HIP-event granularity in the timed region: one pair per kernel launch "
+                         "(default for staged), or one pair around each iteration's bucket "
+                         "launches (default for fused, where they are the only kernels)")
     ap.add_argument("--cap-mib", type=float, default=None,
                     help="override the bucket cap (MiB; negative = whole model)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling profiler counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the R replicas are R buffers in one GPU's "
@@ -95,7 +148,8 @@ def main() -> int:
     es = harness.ESIZE[dtype]
     B = sum(numel) * es
     W = 1
-    pipeline = lib.DDP_PIPELINE_STAGED if args.pipeline == "staged" else lib.DDP_PIPELINE_FUSED
+    codes = {"staged": lib.DDP_PIPELINE_STAGED, "fused": lib.DDP_PIPELINE_FUSED}
+    timing = args.timing or ("iteration" if args.pipeline == "fused" else "launch")
 
     reps = generate_replicas(config_id, numel, R, sigma, dtype)
     grads = harness.DeviceGrads(numel, [dtype] * n, R)
@@ -103,73 +157,40 @@ def main() -> int:
         grads.upload_replica(r, reps[r])
     torch.cuda.synchronize()
 
+    if args.calibration_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     order = list(range(n - 1, -1, -1))
-    with harness.Session(grads, cap, pipeline, same_stream=args.same_stream) as s:
-        ctx = s.ctx
-        if args.reduce_blocks is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_BLOCKS, args.reduce_blocks)
-        if args.plain_loads:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_NONTEMPORAL, 0)
-        if args.unroll is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_UNROLL, args.unroll)
-
-        def step():
-            lib.ddp_mark_ready_many(ctx, order)
-            lib.ddp_finalize_backward(ctx)
-
-        for _ in range(args.warmup):
-            step()
-        lib.ddp_synchronize(ctx)
-        torch.cuda.synchronize()
-
-        # timed region: K steps, HIP events around every kernel launch on the reduce stream
-        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 1 if args.timing == "launch" else 2)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        lib.ddp_synchronize(ctx)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-        red_ms, red_ids = lib.ddp_get_kernel_times(ctx, lib.DDP_K_REDUCE)
-        pack_ms, _ = lib.ddp_get_kernel_times(ctx, lib.DDP_K_PACK)
-        unpack_ms, _ = lib.ddp_get_kernel_times(ctx, lib.DDP_K_UNPACK)
-        iter_ms, iter_launches = lib.ddp_get_kernel_times(ctx, lib.DDP_K_ITERATION)
-        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 0)
-
-        # the same K steps without the timing events, for comparison
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        lib.ddp_synchronize(ctx)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ms_per_step_plain = (t1 - t0) * 1e3 / args.steps
-
-        bucket_elems = [lib.ddp_get_bucket_info(ctx, b)[0] for b in range(s.n_buckets)]
-        n_buckets = s.n_buckets
+    m = measure(lib, harness, torch, grads, cap, codes[args.pipeline], order, args.steps, args.warmup,
+                timing, args)
+    ms_per_step = m["ms_per_step"]
+    bucket_elems, n_buckets = m["bucket_elems"], m["n_buckets"]
+    red_ms, red_ids = m["reduce"]
+    iter_ms, iter_launches = m["iteration"]
 
     # reduce kernel: algorithmic bytes per launch = (R + 1) * bucket bytes
-    if args.timing == "launch":
+    per_bucket = {}
+    if timing == "launch":
         launches = len(red_ms)
         total_alg = float(sum((R + 1) * bucket_elems[b] * es for b in red_ids))
         total_ms = float(red_ms.sum())
+        for b in range(n_buckets):
+            sel = red_ms[red_ids == b]
+            if len(sel):
+                per_bucket[str(b)] = round((R + 1) * bucket_elems[b] * es / float(np.median(sel)) / 1e6, 1)
     else:
-        # one interval per iteration holding all its bucket launches (meaningful
-        # for the fused pipeline, where they are the only kernels in it)
+        # one interval per iteration holding all its bucket launches; in the
+        # fused pipeline they are the only kernels inside it
         launches = int(iter_launches.sum())
         total_alg = float((R + 1) * B * len(iter_ms))
         total_ms = float(iter_ms.sum())
     avg_launch_ms = total_ms / max(launches, 1)
     achieved = total_alg / max(total_ms, 1e-12) / 1e6          # bytes / ms -> GB/s
-    per_bucket = {}
-    for b in range(n_buckets):
-        sel = red_ms[red_ids == b]
-        if len(sel):
-            per_bucket[str(b)] = round((R + 1) * bucket_elems[b] * es / float(np.median(sel)) / 1e6, 1)
 
     value = (R + W) * B / ms_per_step / 1e6
     out = {
@@ -189,13 +210,11 @@ def main() -> int:
                                f"cap={cap} B, {n_buckets} buckets, ready order = reverse registration",
                    "pipeline": args.pipeline, "R": R, "W": W, "bucket_cap_bytes": cap},
         "pct_hbm_peak_end_to_end": round(100.0 * value / HBM_PEAK_GBPS, 2),
-        "ms_per_step_without_timing_events": round(ms_per_step_plain, 4),
         "kernel_ms_per_step": {
-            "pack": round(float(pack_ms.sum()) / args.steps, 4),
+            "pack": round(float(m["pack"][0].sum()) / args.steps, 4),
             "reduce": round(total_ms / args.steps, 4),
-            "unpack": round(float(unpack_ms.sum()) / args.steps, 4),
+            "unpack": round(float(m["unpack"][0].sum()) / args.steps, 4),
         },
-        "reduce_gbps_per_bucket": per_bucket,
         "roofline": {
             "kernel": "flat_reduce_kernel" if args.pipeline == "staged" else "fused_reduce_kernel",
             "bound": "hbm",
@@ -205,15 +224,32 @@ def main() -> int:
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "avg_launch_ms": round(avg_launch_ms, 5),
             "launches": launches,
-            "timing": "HIP event pair per " + args.timing,
+            "timing": "HIP event pair per " + timing,
             "algorithmic_bytes_per_launch": round(total_alg / max(launches, 1)),
             "traffic": read_traffic(args.workload, args.pipeline),
         },
     }
+    if per_bucket:
+        out["reduce_gbps_per_bucket"] = per_bucket
+
+    if args.pipeline == "fused" and not args.no_staged_leg:
+        # the literal three-kernel pipeline on the same data, one event pair per launch
+        steps2 = max(5, args.steps // 2)
+        st = measure(lib, harness, torch, grads, cap, codes["staged"], order, steps2, 2, "launch", args)
+        s_red_ms, s_red_ids = st["reduce"]
+        red_alg = float(sum((R + 1) * bucket_elems[b] * es for b in s_red_ids))
+        out["staged"] = {
+            "ms_per_step": round(st["ms_per_step"], 4),
+            "value_gbps": round((R + W) * B / st["ms_per_step"] / 1e6, 1),
+            "pack_gbps": round(2.0 * R * B * steps2 / float(st["pack"][0].sum()) / 1e6, 1),
+            "reduce_gbps": round(red_alg / float(s_red_ms.sum()) / 1e6, 1),
+            "unpack_gbps": round((1.0 + W) * B * steps2 / float(st["unpack"][0].sum()) / 1e6, 1),
+            "bytes": "pack 2RB, reduce (R+1)B, unpack (1+W)B per step",
+            "steps": steps2,
+        }
 
     if not args.no_cpu_baseline:
         import oracle
-        reps_cpu = args.steps and 1
         t0 = time.perf_counter()
         done = 0
         while True:

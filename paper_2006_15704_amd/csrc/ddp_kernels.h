@@ -6,9 +6,16 @@
 namespace ddp {
 
 // Work is cut into tiles of TILE_BYTES of gradient data: one thread block of
-// BLOCK threads moves TILE_VECS 16-byte vectors per replica.
+// BLOCK threads moves TILE_VECS 16-byte vectors per replica.  8 KiB tiles (two
+// vectors per thread and replica) measured best on the ResNet-50-shaped list,
+// whose buckets are small enough for block granularity to show; 16 KiB tiles
+// with four vectors per thread are about 1.5 % faster on BERT-large and 8 %
+// slower on ResNet-50.
 constexpr int BLOCK = 256;
-constexpr int TILE_VECS = 1024;
+#ifndef DDP_TILE_VECS
+#define DDP_TILE_VECS 512
+#endif
+constexpr int TILE_VECS = DDP_TILE_VECS;
 constexpr int TILE_BYTES = TILE_VECS * 16;
 
 // Tiles a segment of `bytes` bytes can need, whatever its pointer alignment:

@@ -642,8 +642,9 @@ static void fused_dispatch(bool nt, dim3 grid, hipStream_t s, const SegTables& t
 template <int DT>
 static void fused_unroll(int unroll, bool nt, dim3 grid, hipStream_t s, const SegTables& t,
                          int64_t tile_base, int R, int nwrite, const uint8_t* unused, Scale sc) {
-    if (unroll >= 4) fused_dispatch<DT, 4>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
-    else if (unroll >= 2) fused_dispatch<DT, 2>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
+    constexpr int UMAX = TILE_VECS / BLOCK;      // a tile holds at most this many vectors per thread
+    if (unroll >= 4 && UMAX >= 4) fused_dispatch<DT, (UMAX >= 4 ? 4 : 1)>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
+    else if (unroll >= 2 && UMAX >= 2) fused_dispatch<DT, (UMAX >= 2 ? 2 : 1)>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
     else fused_dispatch<DT, 1>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
 }
 

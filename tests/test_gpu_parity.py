@@ -125,7 +125,7 @@ def test_unaligned_gradient_pointers(pipeline, dtype):
     """Tensors that start at every element-aligned offset modulo 16 bytes,
     different per replica, with lengths around the vector and tile sizes."""
     es = 4 if dtype == FP32 else 2
-    numel = [1, 2, 3, 5, 8, 13, 4095, 4096, 4097, 8191, 8193, 20000, 33, 64, 1023, 9000]
+    numel = [1, 2, 3, 5, 8, 13, 2047, 2048, 2049, 4095, 4096, 4097, 8191, 8193, 20000, 33, 64, 1023, 9000]
     skew = [(i * es) % 16 for i in range(len(numel))]
     R = 3
     replica_skew = [0, es, 3 * es]

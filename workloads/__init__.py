@@ -10,7 +10,7 @@ BERT, Section 5, with random synthetic inputs): only the *parameter-list
 shapes* matter to gradient synchronization, so the gradients themselves are
 seeded Gaussians.
 """
-from .shapes import (tiny_shapes, resnet50_shapes, bert_large_shapes,
+from .shapes import (tiny_shapes, resnet50_shapes, bert_large_shapes, uniform_shapes,
                      numel_of, WORKLOAD_SHAPES)
 from .grads import (DT_FP32, DT_FP16, DT_BF16, ESIZE, NP_STORAGE,
                     gaussian_grad, gaussian_replica, tag_grad, integer_grad,
@@ -18,7 +18,7 @@ from .grads import (DT_FP32, DT_FP16, DT_BF16, ESIZE, NP_STORAGE,
                     f32_to_storage_trunc)
 
 __all__ = [
-    "tiny_shapes", "resnet50_shapes", "bert_large_shapes", "numel_of",
+    "tiny_shapes", "resnet50_shapes", "bert_large_shapes", "uniform_shapes", "numel_of",
     "WORKLOAD_SHAPES", "DT_FP32", "DT_FP16", "DT_BF16", "ESIZE", "NP_STORAGE",
     "gaussian_grad", "gaussian_replica", "tag_grad", "integer_grad",
     "linear_regression_problem", "unused_param_set", "f32_to_storage_trunc",

@@ -71,6 +71,12 @@ def bert_large_shapes() -> List[Shape]:
     return out
 
 
+def uniform_shapes(count: int = 40, elems: int = 25 * (1 << 20) // 4) -> List[Shape]:
+    """Diagnostic list: `count` equal tensors of `elems` elements (25 MiB of
+    fp32 each by default), so that every bucket is one plain contiguous run."""
+    return [(f"u{i}", (elems,)) for i in range(count)]
+
+
 def numel_of(shapes: List[Shape]) -> List[int]:
     return [int(prod(d)) for _, d in shapes]
 
@@ -79,4 +85,5 @@ WORKLOAD_SHAPES = {
     "tiny": tiny_shapes,
     "resnet50": resnet50_shapes,
     "bert_large": bert_large_shapes,
+    "uniform": uniform_shapes,
 }
