@@ -127,6 +127,8 @@ def main() -> int:
                          "launches (default for fused, where they are the only kernels)")
     ap.add_argument("--cap-mib", type=float, default=None,
                     help="override the bucket cap (MiB; negative = whole model)")
+    ap.add_argument("--uniform", default=None,
+                    help="diagnostic workload 'count,elems': that many equal tensors (with --workload uniform)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling profiler counters)")
     args = ap.parse_args()
@@ -143,7 +145,11 @@ def main() -> int:
     shape_name, config_id, R, sigma, dtype, cap = WORKLOADS[args.workload]
     if args.cap_mib is not None:
         cap = lib.DDP_CAP_WHOLE_MODEL if args.cap_mib < 0 else int(args.cap_mib * (1 << 20))
-    numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[shape_name]())
+    if args.workload == "uniform" and args.uniform:
+        count, elems = (int(x) for x in args.uniform.split(","))
+        numel = workloads.numel_of(workloads.uniform_shapes(count, elems))
+    else:
+        numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[shape_name]())
     n = len(numel)
     es = harness.ESIZE[dtype]
     B = sum(numel) * es

@@ -373,7 +373,14 @@ int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
                 flat_byte[g] = c->bucket_slab_off[b] + p.offset * ddp::elem_size(p.dtype);
                 param[g] = i;
                 dtype[g] = p.dtype;
-                c->h_tile0[g + 1] = c->h_tile0[g] + ddp::tiles_for(p.numel, ddp::elem_size(p.dtype));
+                // largest lead-in over every destination this segment can have:
+                // its slot in the flat slab and each replica's gradient tensor
+                int lead = static_cast<int>(flat_byte[g] & 15);
+                for (int64_t r = 0; r < c->R; ++r) {
+                    const int a = static_cast<int>(reinterpret_cast<uintptr_t>(c->grad_ptrs[r * n + i]) & 15u);
+                    if (a > lead) lead = a;
+                }
+                c->h_tile0[g + 1] = c->h_tile0[g] + ddp::tiles_for(p.numel, ddp::elem_size(p.dtype), lead);
             }
         }
         if (c->h_tile0[n] >= (int64_t(1) << 31)) {

@@ -18,12 +18,13 @@ constexpr int BLOCK = 256;
 constexpr int TILE_VECS = DDP_TILE_VECS;
 constexpr int TILE_BYTES = TILE_VECS * 16;
 
-// Tiles a segment of `bytes` bytes can need, whatever its pointer alignment:
-// vectors are cut at 16-byte boundaries of the destination, so up to
-// 16 - elem_size bytes of lead-in shift the grid.
-inline int64_t tiles_for(int64_t numel, int es) {
+// Tiles of a segment.  Vectors are cut at 16-byte boundaries of the
+// destination, so a destination that starts `lead_bytes` (< 16) past such a
+// boundary shifts the grid by that much; the caller passes the largest lead-in
+// over all destinations the segment can have.
+inline int64_t tiles_for(int64_t numel, int es, int lead_bytes) {
     if (numel <= 0) return 0;
-    return (numel * es + (16 - es) + TILE_BYTES - 1) / TILE_BYTES;
+    return (numel * es + lead_bytes + TILE_BYTES - 1) / TILE_BYTES;
 }
 
 // Device-resident tables over the G segments (parameters in bucket-major fill

@@ -358,18 +358,21 @@ __global__ __launch_bounds__(BLOCK) void flat_reduce_kernel(const char* __restri
     }
 }
 
-// Fused variant: replica pointers come from the segment table.
+// Fused variant, boundary tiles: replica pointers come from the segment table
+// and lanes are predicated.  The C pointers are fetched first (one scalar
+// load), then all C*U vector loads are issued, then the adds run in order.
 template <int DT, bool NT, int C, int U>
 __device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r,
                                           const int64_t (&off)[U], const bool (&ok)[U],
                                           float (&acc)[U][Fmt<DT>::VEC]) {
+    const char* base[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) base[i] = static_cast<const char*>(row[r + i]);
     u32x4 x[C][U];
 #pragma unroll
-    for (int i = 0; i < C; ++i) {
-        const char* p = static_cast<const char*>(row[r + i]);
+    for (int i = 0; i < C; ++i)
 #pragma unroll
-        for (int u = 0; u < U; ++u) x[i][u] = ok[u] ? load16<NT>(p + off[u]) : zero16();
-    }
+        for (int u = 0; u < U; ++u) x[i][u] = ok[u] ? load16<NT>(base[i] + off[u]) : zero16();
 #pragma unroll
     for (int i = 0; i < C; ++i)
 #pragma unroll
