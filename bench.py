@@ -76,6 +76,8 @@ def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup
             lib.ddp_set_option(ctx, lib.DDP_OPT_NONTEMPORAL, 0)
         if args.unroll is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_UNROLL, args.unroll)
+        if args.pair_min_mib is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_PAIR_MIN_BYTES, int(args.pair_min_mib * (1 << 20)))
 
         def step():
             lib.ddp_mark_ready_many(ctx, order)
@@ -92,10 +94,12 @@ def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup
         t0 = time.perf_counter()
         for _ in range(steps):
             step()
+        t_enq = time.perf_counter()
         lib.ddp_synchronize(ctx)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        res = {"ms_per_step": (t1 - t0) * 1e3 / steps}
+        res = {"ms_per_step": (t1 - t0) * 1e3 / steps,
+               "host_enqueue_ms_per_step": (t_enq - t0) * 1e3 / steps}
         res["reduce"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_REDUCE)
         res["pack"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_PACK)
         res["unpack"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_UNPACK)
@@ -116,9 +120,13 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staged-leg", action="store_true",
                     help="skip the extra measurement of the staged pipeline's kernels")
+    ap.add_argument("--no-accumulate-leg", action="store_true",
+                    help="skip the extra measurement of the no_sync accumulation kernel")
     ap.add_argument("--reduce-blocks", type=int, default=None)
     ap.add_argument("--plain-loads", action="store_true")
     ap.add_argument("--unroll", type=int, default=None, choices=[1, 2, 4])
+    ap.add_argument("--pair-min-mib", type=float, default=None,
+                    help="fused pipeline: bucket size from which blocks take two tiles")
     ap.add_argument("--same-stream", action="store_true",
                     help="use one stream for backward and reduction (no event plumbing)")
     ap.add_argument("--timing", default=None, choices=["launch", "iteration"],
@@ -216,6 +224,7 @@ def main() -> int:
                                f"cap={cap} B, {n_buckets} buckets, ready order = reverse registration",
                    "pipeline": args.pipeline, "R": R, "W": W, "bucket_cap_bytes": cap},
         "pct_hbm_peak_end_to_end": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "host_enqueue_ms_per_step": round(m["host_enqueue_ms_per_step"], 4),
         "kernel_ms_per_step": {
             "pack": round(float(m["pack"][0].sum()) / args.steps, 4),
             "reduce": round(total_ms / args.steps, 4),
@@ -253,6 +262,27 @@ def main() -> int:
             "bytes": "pack 2RB, reduce (R+1)B, unpack (1+W)B per step",
             "steps": steps2,
         }
+
+    if not args.no_accumulate_leg:
+        # no_sync micro-step: grad[r][i] += micro[r][i] for all replicas, 3*R*B bytes
+        micro = harness.DeviceGrads(numel, [dtype] * n, R, fill=0)
+        ptrs = micro.ptrs()
+        with harness.Session(grads, cap, codes[args.pipeline]) as s:
+            for _ in range(2):
+                lib.ddp_no_sync_accumulate(s.ctx, ptrs)
+            lib.ddp_synchronize(s.ctx)
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 1)
+            reps_acc = 10
+            for _ in range(reps_acc):
+                lib.ddp_no_sync_accumulate(s.ctx, ptrs)
+            lib.ddp_synchronize(s.ctx)
+            acc_ms, _ = lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_ACCUMULATE)
+        out["no_sync_accumulate"] = {
+            "ms_per_micro_step": round(float(acc_ms.mean()), 4),
+            "gbps": round(3.0 * R * B / float(acc_ms.mean()) / 1e6, 1),
+            "bytes": "3*R*B per micro-step (read gradient and micro-gradient, write gradient)",
+        }
+        del micro
 
     if not args.no_cpu_baseline:
         import oracle

@@ -75,6 +75,13 @@ typedef struct ddp_ctx ddp_ctx;
                                      (0 = one block per tile) */
 #define DDP_OPT_NONTEMPORAL    5  /* any time: 1 (default) = read-once inputs are loaded, and the
                                      averages stored, with the non-temporal hint; 0 = plain */
+#define DDP_OPT_PAIR_MIN_BYTES 7  /* any time: fused pipeline, buckets of at least this many bytes
+                                     are reduced with two tiles per thread block (more loads in
+                                     flight per thread; pays off on large launches).  Default 48 MiB */
+#define DDP_OPT_EMIT_BUSY_BLOCKS 8 /* any time: ddp_synth_backward's delay kernel.  0 (default): one
+                                     thread block that sleeps between clock polls; n > 0: n blocks
+                                     that do arithmetic between polls, so that the delay loads the
+                                     GPU the way backward compute does */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 

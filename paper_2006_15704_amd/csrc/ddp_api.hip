@@ -16,6 +16,15 @@
 
 namespace {
 
+// Cross-stream ordering events: no timestamps, and a device-scope release --
+// producer and consumer kernels run on the same GPU, so the default
+// system-scope release (a cache write-back at every record) is not needed.
+// Host-visible completion always goes through hipStreamSynchronize.
+constexpr unsigned kOrderEvent = hipEventDisableTiming | hipEventReleaseToDevice;
+// Timing events: device-scope release as well, so that the record itself does
+// not add cache maintenance to the interval it measures.
+constexpr unsigned kTimingEvent = hipEventReleaseToDevice;
+
 thread_local std::string g_create_error;
 
 struct TimedLaunch {
@@ -40,6 +49,8 @@ struct ddp_ctx {
     int32_t reduce_blocks = 0;
     int32_t nontemporal = 1;
     int32_t unroll = 2;
+    int64_t pair_min_bytes = int64_t(48) << 20;   // buckets at least this large use paired tiles
+    int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
 
     bool registered = false, built = false;
     ddp::BucketPlan plan;
@@ -101,8 +112,8 @@ int32_t timed_begin(ddp_ctx* c, int32_t kind, int32_t bucket, hipStream_t s, siz
     *slot = static_cast<size_t>(-1);
     if (c->timing != 1) return DDP_OK;
     TimedLaunch t{kind, bucket, nullptr, nullptr};
-    HIPCHK(c, hipEventCreate(&t.start));
-    HIPCHK(c, hipEventCreate(&t.stop));
+    HIPCHK(c, hipEventCreateWithFlags(&t.start, kTimingEvent));
+    HIPCHK(c, hipEventCreateWithFlags(&t.stop, kTimingEvent));
     HIPCHK(c, hipEventRecord(t.start, s));
     c->timed.push_back(t);
     *slot = c->timed.size() - 1;
@@ -156,8 +167,8 @@ int32_t launch_bucket(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t ca
     if (c->timing == 2 && c->open_group == static_cast<size_t>(-1)) {
         // one event pair per iteration: opened by its first bucket launch
         TimedLaunch t{DDP_K_ITERATION, 0, nullptr, nullptr};
-        HIPCHK(c, hipEventCreate(&t.start));
-        HIPCHK(c, hipEventCreate(&t.stop));
+        HIPCHK(c, hipEventCreateWithFlags(&t.start, kTimingEvent));
+        HIPCHK(c, hipEventCreateWithFlags(&t.stop, kTimingEvent));
         HIPCHK(c, hipEventRecord(t.start, c->reduce));
         c->timed.push_back(t);
         c->open_group = c->timed.size() - 1;
@@ -179,6 +190,7 @@ int32_t launch_bucket(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t ca
         if ((rc = timed_begin(c, DDP_K_REDUCE, b, c->reduce, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_fused_reduce(bk.dtype, c->tables, tile_base, ntiles, c->R,
                                            c->write_all ? c->R : 1, d_unused, sc, c->unroll,
+                                           static_cast<int64_t>(bk.bytes()) >= c->pair_min_bytes,
                                            c->nontemporal != 0, c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
     }
@@ -246,7 +258,7 @@ int32_t ddp_create(ddp_ctx** out, int32_t R, int32_t device, void* reduce_stream
         int khz = 0;
         if (e == hipSuccess) e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device);
         if (e == hipSuccess && khz > 0) c->wall_clock_khz = khz;
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_done, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_done, kOrderEvent);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_flags, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_micro, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_emit, hipEventDisableTiming);
@@ -288,6 +300,14 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             }
             if (value < 0 || value > 2) return fail(c, DDP_ERR_ARG, "timing mode must be 0, 1 or 2");
             c->timing = c->plan_only ? 0 : static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_EMIT_BUSY_BLOCKS:
+            if (value < 0 || value > 4096) return fail(c, DDP_ERR_ARG, "busy blocks outside [0, 4096]");
+            c->emit_busy_blocks = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_PAIR_MIN_BYTES:
+            if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
+            c->pair_min_bytes = value;
             return DDP_OK;
         case DDP_OPT_REDUCE_UNROLL:
             if (value != 1 && value != 2 && value != 4) return fail(c, DDP_ERR_ARG, "unroll must be 1, 2 or 4");
@@ -428,13 +448,13 @@ int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
             c->tables.tile_seg = c->d_tile_seg;
         }
 
-        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_unused), static_cast<size_t>(n)));
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_unused), static_cast<size_t>(n) + 16));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_unused), static_cast<size_t>(n), hipHostMallocDefault));
         HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_micro), sizeof(void*) * R * n));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_micro), sizeof(void*) * R * n, hipHostMallocDefault));
         c->ev_ready.resize(nb, nullptr);
         for (int32_t b = 0; b < nb; ++b)
-            HIPCHK(c, hipEventCreateWithFlags(&c->ev_ready[b], hipEventDisableTiming));
+            HIPCHK(c, hipEventCreateWithFlags(&c->ev_ready[b], kOrderEvent));
         if (c->pipeline == DDP_PIPELINE_STAGED) {
             const size_t total = static_cast<size_t>(c->slab_stride) * static_cast<size_t>(R + 1);
             HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->slabs), total));
@@ -671,6 +691,7 @@ int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, cons
         if (ticks > 0 || d_rows) {
             HIPCHK(c, ddp::launch_emit(ticks, d_rows ? d_rows + 2 * R * k : nullptr, c->R,
                                        c->plan.params[p].numel, ddp::elem_size(c->plan.params[p].dtype),
+                                       c->emit_busy_blocks, reinterpret_cast<float*>(c->d_unused),
                                        c->backward));
         }
         if (mark) {

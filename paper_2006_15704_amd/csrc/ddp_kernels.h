@@ -74,21 +74,23 @@ hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* 
                               hipStream_t s);
 
 // K2 (fused): gather R replicas through the segment table, reduce, scatter to
-// the gradient tensors of replicas [0, nwrite).
+// the gradient tensors of replicas [0, nwrite).  pair = blocks take two tiles
+// each (for large launches).
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* unused, Scale sc, int unroll,
-                               bool nontemporal, hipStream_t s);
+                               bool pair, bool nontemporal, hipStream_t s);
 
 // K4: grad[r][g] += micro[r*n + param[g]] for all segments and replicas
 // (null micro pointers are skipped).  ntiles = tile0[G].
 hipError_t launch_accumulate(const SegTables& t, int64_t ntiles, int R, int n, void* const* micro,
                              hipStream_t s);
 
-// K6: busy-wait `ticks` of the device wall clock (bounded), then copy
+// K6: wait `ticks` of the device wall clock (bounded), then copy
 // src_r -> dst_r (nelem elements of es bytes) for r < R, where
 // ptrs = [dst_0..dst_{R-1}, src_0..src_{R-1}] is a device array (null = delay
-// only).
+// only).  busy_blocks = 0: one block that sleeps between polls; > 0: that many
+// blocks (delay-only launches) doing arithmetic between polls.
 hipError_t launch_emit(int64_t ticks, void* const* ptrs, int R, int64_t nelem, int es,
-                       hipStream_t s);
+                       int busy_blocks, float* sink, hipStream_t s);
 
 }  // namespace ddp

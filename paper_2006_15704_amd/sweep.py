@@ -1,0 +1,141 @@
+"""Bucket-size sweep with a synthetic backward pass (one GPU).
+
+The one-GPU analogue of the paper's bucket-size experiment (Section 5.2) and of
+its overlap measurement (Section 5.1): ResNet-50-shaped fp16 gradients, R = 16
+replica copies, bucket caps from 0 (every gradient alone) to the whole model.
+A synthetic backward stream stands in for autograd: for every parameter, in
+reverse registration order, it runs a kernel that waits a fixed delay and then
+the parameter is marked ready, so buckets are reduced on the reduction stream
+while "backward" is still running.
+
+For every cap and delay the script reports
+    t_backward   the backward pass alone (no ready marks)
+    t_sync       the synchronization alone (ready marks without delay)
+    t_total      backward with ready marks + finalize, until the averaged
+                 gradients are complete
+(all three are GPU times between two events on the backward stream)
+    exposed      t_total - t_backward: synchronization time not hidden
+    overlap      1 - exposed / t_sync
+one JSON object per line.  Run:  python -m paper_2006_15704_amd.sweep
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MIB = 1 << 20
+
+
+def timed(fn, sync, reps, torch, stream):
+    """Median GPU time of fn(): the work is bracketed by two events recorded on
+    the backward stream.  ddp_finalize_backward makes that stream wait for the
+    reductions, so the closing event marks the completion of everything."""
+    out = []
+    for _ in range(reps):
+        sync()
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        fn()
+        b.record(stream)
+        sync()
+        b.synchronize()
+        out.append(a.elapsed_time(b))
+    return statistics.median(out)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "bert_large"])
+    ap.add_argument("--dtype", default="f16", choices=["f32", "f16", "bf16"])
+    ap.add_argument("--replicas", type=int, default=16)
+    ap.add_argument("--caps-mib", default="0,1,5,10,25,50,100,-1",
+                    help="comma list of caps in MiB; -1 = whole model")
+    ap.add_argument("--delays-us", default="0,10,50")
+    ap.add_argument("--pipelines", default="fused,staged")
+    ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--busy-blocks", type=int, default=0,
+                    help="delay kernels use this many thread blocks doing arithmetic instead of "
+                         "one sleeping block")
+    ap.add_argument("--produce", action="store_true",
+                    help="the synthetic backward also writes every gradient (copies it from a "
+                         "source buffer after the delay), which keeps the memory system busy "
+                         "the way a real backward pass does")
+    args = ap.parse_args()
+
+    import torch
+    import workloads
+    import paper_2006_15704_amd as lib
+    from paper_2006_15704_amd import harness
+
+    dtype = {"f32": 0, "f16": 1, "bf16": 2}[args.dtype]
+    numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[args.workload]())
+    n, R = len(numel), args.replicas
+    es = harness.ESIZE[dtype]
+    B = sum(numel) * es
+    grads = harness.DeviceGrads(numel, [dtype] * n, R)
+    for r in range(R):
+        grads.upload_replica(r, workloads.gaussian_replica(4, r, 0, numel, 1e-2, dtype))
+    src_ptrs = None
+    if args.produce:
+        src = harness.DeviceGrads(numel, [dtype] * n, R, fill=0)
+        src_ptrs = src.ptrs()
+    torch.cuda.synchronize()
+    order = list(range(n - 1, -1, -1))
+    caps = [int(x) for x in args.caps_mib.split(",")]
+    delays = [int(x) for x in args.delays_us.split(",")]
+
+    for pipe in args.pipelines.split(","):
+        code = lib.DDP_PIPELINE_FUSED if pipe == "fused" else lib.DDP_PIPELINE_STAGED
+        for cap_mib in caps:
+            cap = lib.DDP_CAP_WHOLE_MODEL if cap_mib < 0 else cap_mib * MIB
+            with harness.Session(grads, cap, code) as s:
+                ctx = s.ctx
+                lib.ddp_set_option(ctx, lib.DDP_OPT_EMIT_BUSY_BLOCKS, args.busy_blocks)
+
+                def sync():
+                    lib.ddp_synchronize(ctx)
+
+                def sync_alone():
+                    lib.ddp_synth_backward(ctx, order, None, None, True)
+                    lib.ddp_finalize_backward(ctx)
+
+                for _ in range(3):
+                    sync_alone()
+                t_sync = timed(sync_alone, sync, args.reps, torch, s.backward_stream)
+                for d_us in delays:
+                    dl = [d_us * 1000] * n
+
+                    def backward_alone():
+                        lib.ddp_synth_backward(ctx, order, dl, src_ptrs, False)
+
+                    def backward_and_sync():
+                        lib.ddp_synth_backward(ctx, order, dl, src_ptrs, True)
+                        lib.ddp_finalize_backward(ctx)
+
+                    t_bwd = timed(backward_alone, sync, args.reps, torch, s.backward_stream) if (d_us > 0 or src_ptrs) else 0.0
+                    t_tot = timed(backward_and_sync, sync, args.reps, torch, s.backward_stream)
+                    exposed = t_tot - t_bwd
+                    print(json.dumps({
+                        "workload": args.workload, "dtype": args.dtype, "R": R, "pipeline": pipe,
+                        "cap_mib": cap_mib, "n_buckets": s.n_buckets, "delay_us_per_param": d_us,
+                        "backward_writes_gradients": bool(src_ptrs), "busy_blocks": args.busy_blocks,
+                        "t_backward_ms": round(t_bwd, 4), "t_sync_ms": round(t_sync, 4),
+                        "t_total_ms": round(t_tot, 4), "exposed_ms": round(exposed, 4),
+                        "overlap": round(1.0 - exposed / t_sync, 3) if t_sync > 0 else None,
+                        "sync_gbps_alg": round((R + 1) * B / t_sync / 1e6, 1),
+                    }), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -41,7 +41,7 @@ def assert_close(got, want, reps_p, dtype, what):
 
 
 def run_sync(numel, dtypes, reps, cap, pipeline, order=None, skew=None, replica_skew=None,
-             write_all=False, one_by_one=False, same_stream=False, check_flat=True):
+             write_all=False, one_by_one=False, same_stream=False, check_flat=True, options=()):
     d, harness = lib()
     R = len(reps)
     grads = harness.DeviceGrads(numel, dtypes, R, skew=skew, replica_skew=replica_skew, fill=0xFF)
@@ -49,6 +49,8 @@ def run_sync(numel, dtypes, reps, cap, pipeline, order=None, skew=None, replica_
         grads.upload_replica(r, reps[r])
     want, asg, wlog = oracle.synchronize(numel, dtypes, cap, reps, order)
     with harness.Session(grads, cap, pipeline, write_all, same_stream) as s:
+        for opt, val in options:
+            d.ddp_set_option(s.ctx, opt, val)
         assert s.n_buckets == len(asg.buckets)
         bucket_of, offset = d.ddp_get_assignment(s.ctx, len(numel))
         assert bucket_of.tolist() == asg.bucket_of.tolist()
@@ -143,6 +145,27 @@ def test_mixed_element_types(pipeline):
     reps = [[workloads.gaussian_grad(12, r, 0, p, n, 1e-2, dt) for p, (n, dt) in enumerate(zip(numel, dtypes))]
             for r in range(R)]
     run_sync(numel, dtypes, reps, 1 << 20, pipeline)
+
+
+@pytest.mark.parametrize("dtype", [FP32, FP16, BF16])
+@pytest.mark.parametrize("unroll", [1, 2, 4])
+def test_kernel_variants_give_the_same_bits(dtype, unroll):
+    """Every unroll setting, with and without two-tile blocks and with plain
+    loads, on a list that mixes large, tiny, unaligned and unmarked tensors."""
+    d, _ = lib()
+    es = 4 if dtype == FP32 else 2
+    numel = [70000, 3, 2048, 4096, 12289, 1, 40000, 64, 9999]
+    skew = [0, es, 0, 0, 2 * es, 0, 0, 3 * es, 0]
+    R = 5
+    reps = gaussian_reps(13, numel, R, 1e-2, dtype)
+    order = [8, 7, 6, 4, 3, 2, 0]          # parameters 5 and 1 never marked
+    for pair_min in (0, 1 << 40):
+        for nt in (1, 0):
+            opts = [(d.DDP_OPT_REDUCE_UNROLL, unroll), (d.DDP_OPT_PAIR_MIN_BYTES, pair_min),
+                    (d.DDP_OPT_NONTEMPORAL, nt)]
+            for pipeline in (STAGED, FUSED):
+                run_sync(numel, [dtype] * len(numel), reps, 1 << 22, pipeline, order=order, skew=skew,
+                         options=opts, write_all=(nt == 0))
 
 
 # ---- reductions -----------------------------------------------------------------------------
