@@ -170,7 +170,10 @@ int32_t ddp_get_bucket_ptr(const ddp_ctx* ctx, int32_t b, int32_t r, void** ptr)
 int32_t ddp_mark_ready(ddp_ctx* ctx, int32_t param_id);
 
 /* Same as calling ddp_mark_ready for ids[0..count) in order; stops at the
- * first error and returns it.  Saves per-call binding overhead. */
+ * first error and returns it.  Buckets that complete during the call are
+ * launched one after the other in index order; because the caller cannot
+ * enqueue anything on backward_stream in the middle of the call, a single
+ * stream-ordering point serves all of them. */
 int32_t ddp_mark_ready_many(ddp_ctx* ctx, const int32_t* ids, int32_t count);
 
 /* The finalizing step described after Algorithm 1 (wait for the reductions and
