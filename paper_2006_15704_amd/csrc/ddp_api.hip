@@ -197,6 +197,23 @@ int32_t launch_bucket(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t ca
     return DDP_OK;
 }
 
+// Frees what ddp_build_buckets allocates (also after a build that failed half
+// way, so that a retry does not leak).
+void release_build(ddp_ctx* c) {
+    for (hipEvent_t e : c->ev_ready)
+        if (e) (void)hipEventDestroy(e);
+    c->ev_ready.clear();
+    if (c->slabs) (void)hipFree(c->slabs);
+    if (c->d_tables) (void)hipFree(c->d_tables);
+    if (c->d_tile_seg) (void)hipFree(c->d_tile_seg);
+    if (c->d_unused) (void)hipFree(c->d_unused);
+    if (c->d_micro) (void)hipFree(c->d_micro);
+    if (c->h_unused) (void)hipHostFree(c->h_unused);
+    if (c->h_micro) (void)hipHostFree(c->h_micro);
+    c->slabs = nullptr; c->d_tables = nullptr; c->d_tile_seg = nullptr; c->d_unused = nullptr;
+    c->d_micro = nullptr; c->h_unused = nullptr; c->h_micro = nullptr;
+}
+
 void release_device(ddp_ctx* c) {
     if (c->plan_only) return;
     (void)hipSetDevice(c->device);
@@ -204,21 +221,12 @@ void release_device(ddp_ctx* c) {
     if (c->backward) (void)hipStreamSynchronize(c->backward);
     if (!c->reduce || !c->backward) (void)hipStreamSynchronize(nullptr);
     drop_timed(c);
-    for (hipEvent_t e : c->ev_ready) (void)hipEventDestroy(e);
-    c->ev_ready.clear();
+    release_build(c);
     for (hipEvent_t* e : {&c->ev_done, &c->ev_flags, &c->ev_micro, &c->ev_emit})
         if (*e) { (void)hipEventDestroy(*e); *e = nullptr; }
-    if (c->slabs) (void)hipFree(c->slabs);
-    if (c->d_tables) (void)hipFree(c->d_tables);
-    if (c->d_tile_seg) (void)hipFree(c->d_tile_seg);
-    if (c->d_unused) (void)hipFree(c->d_unused);
-    if (c->d_micro) (void)hipFree(c->d_micro);
     if (c->d_emit) (void)hipFree(c->d_emit);
-    if (c->h_unused) (void)hipHostFree(c->h_unused);
-    if (c->h_micro) (void)hipHostFree(c->h_micro);
     if (c->h_emit) (void)hipHostFree(c->h_emit);
-    c->slabs = nullptr; c->d_tables = nullptr; c->d_tile_seg = nullptr; c->d_unused = nullptr; c->d_micro = nullptr;
-    c->d_emit = nullptr; c->h_unused = nullptr; c->h_micro = nullptr; c->h_emit = nullptr;
+    c->d_emit = nullptr; c->h_emit = nullptr;
 }
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -408,6 +416,7 @@ int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
             return fail(c, DDP_ERR_UNSUPPORTED, "model too large for one launch grid");
         }
         HIPCHK(c, hipSetDevice(c->device));
+        release_build(c);   // leftovers of an earlier attempt that failed
         // one allocation for the segment records and the pointer rows
         const int64_t R = c->R;
         std::vector<ddp::SegInfo> seg(n);

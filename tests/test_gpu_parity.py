@@ -336,3 +336,26 @@ def test_reduction_waits_for_gradients_produced_on_the_backward_stream(pipeline)
         d.ddp_synchronize(s.ctx)
         for i in range(8):
             assert grads.download(0, i).tobytes() == want[i].tobytes()
+
+
+# ---- degenerate and extreme shapes ------------------------------------------------------------
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("numel", [[0, 0, 0], [1], [0, 5, 0], [0], [16, 0, 0, 16]])
+def test_empty_and_single_element_tensors(pipeline, numel):
+    R = 3
+    reps = gaussian_reps(14, numel, R, 1.0)
+    for cap in (0, 64, oracle.CAP_WHOLE_MODEL):
+        run_sync(numel, [FP32] * len(numel), reps, cap, pipeline, one_by_one=True)
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_many_small_parameters_with_the_largest_replica_count(pipeline):
+    """3000 tensors of 0..700 elements, R = 64 (the library's maximum), a cap
+    that gives hundreds of buckets, a random ready order and 5 % of the
+    parameters never marked."""
+    rng = np.random.default_rng(15)
+    n, R = 3000, 64
+    numel = [int(x) for x in rng.integers(0, 700, size=n)]
+    reps = gaussian_reps(15, numel, R, 1e-2)
+    order = [int(p) for p in rng.permutation(n)][: n - 150]
+    run_sync(numel, [FP32] * n, reps, 16384, pipeline, order=order, check_flat=False)
