@@ -420,7 +420,7 @@ int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
         // one allocation for the segment records and the pointer rows
         const int64_t R = c->R;
         std::vector<ddp::SegInfo> seg(n);
-        std::vector<void*> grad(static_cast<size_t>(R) * n);
+        std::vector<void*> grad(static_cast<size_t>(R) * n + 8, nullptr);   // + 8: see SegTables::grad
         for (int32_t g = 0; g < n; ++g) {
             bool cong = true;
             for (int64_t r = 0; r < R; ++r) {
@@ -432,13 +432,14 @@ int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
             seg[g].tile0 = c->h_tile0[g];
             seg[g].flat_byte = flat_byte[g];
             seg[g].param = param[g];
-            seg[g].flags = dtype[g] | (cong ? 0x100 : 0);
+            const int lead0 = static_cast<int>(reinterpret_cast<uintptr_t>(c->grad_ptrs[param[g]]) & 15u);
+            seg[g].flags = dtype[g] | (cong ? 0x100 : 0) | (lead0 << 16);
         }
         const size_t seg_bytes = sizeof(ddp::SegInfo) * n;
-        const size_t bytes = seg_bytes + sizeof(void*) * R * n;
+        const size_t bytes = seg_bytes + sizeof(void*) * grad.size();
         std::vector<char> host(bytes);
         std::memcpy(host.data(), seg.data(), seg_bytes);
-        std::memcpy(host.data() + seg_bytes, grad.data(), sizeof(void*) * R * n);
+        std::memcpy(host.data() + seg_bytes, grad.data(), sizeof(void*) * grad.size());
         HIPCHK(c, hipMalloc(&c->d_tables, bytes));
         HIPCHK(c, hipMemcpy(c->d_tables, host.data(), bytes, hipMemcpyHostToDevice));
         char* d = static_cast<char*>(c->d_tables);

@@ -35,15 +35,18 @@ struct SegInfo {               // 32 bytes, read with one scalar load
     int64_t flat_byte;         // byte offset of the segment inside a replica slab
     int32_t param;             // registration index
     int32_t flags;             // bits 0-7: element type; bit 8: all R gradient tensors share
-                               // replica 0's address modulo 16
+                               // replica 0's address modulo 16; bits 16-19: that address
+                               // modulo 16 (replica 0)
     __host__ __device__ int dtype() const { return flags & 0xFF; }
     __host__ __device__ bool congruent() const { return (flags & 0x100) != 0; }
+    __host__ __device__ int lead_bytes() const { return (flags >> 16) & 0xF; }
 };
 
 struct SegTables {
     const SegInfo* seg;        // [G]
     const int32_t* tile_seg;   // [tiles] segment that each tile belongs to
-    void* const* grad;         // [G*R] replica r's gradient of segment g at [g*R+r]
+    void* const* grad;         // [G*R + 8] replica r's gradient of segment g at [g*R+r]; eight
+                               // null entries of padding so that any row can be read 8 wide
     int32_t G;
     int32_t R;
 };

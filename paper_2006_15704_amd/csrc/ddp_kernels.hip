@@ -282,6 +282,29 @@ __device__ __forceinline__ void sum_interior(BaseFn base_of, int R, const uint32
     if (r < R) { chunk_interior<DT, NT, 1, U>(base_of, r, lane_off, acc); }
 }
 
+// The same with the first eight replica pointers already in registers (they are
+// fetched together with the segment record, one dependent memory access
+// earlier than a fetch inside the loop would be).
+template <int DT, bool NT, int U, typename BaseFn>
+__device__ __forceinline__ void sum_interior_pre(const char* const (&pre)[8], int64_t byte0,
+                                                 BaseFn base_of, int R,
+                                                 const uint32_t (&lane_off)[U],
+                                                 float (&acc)[U][Fmt<DT>::VEC]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < Fmt<DT>::VEC; ++i) acc[u][i] = -0.0f;
+    int r = 0;
+    if (R >= 8) {
+        chunk_interior<DT, NT, 8, U>([&](int k) { return pre[k] + byte0; }, 0, lane_off, acc);
+        r = 8;
+    }
+    for (; r + 8 <= R; r += 8) chunk_interior<DT, NT, 8, U>(base_of, r, lane_off, acc);
+    if (r + 4 <= R) { chunk_interior<DT, NT, 4, U>(base_of, r, lane_off, acc); r += 4; }
+    if (r + 2 <= R) { chunk_interior<DT, NT, 2, U>(base_of, r, lane_off, acc); r += 2; }
+    if (r < R) { chunk_interior<DT, NT, 1, U>(base_of, r, lane_off, acc); }
+}
+
 template <int DT>
 __device__ __forceinline__ u32x4 scaled(const Scale& sc, const float (&acc)[Fmt<DT>::VEC]) {
     float y[Fmt<DT>::VEC];
@@ -401,14 +424,19 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
     constexpr int ES = Fmt<DT>::ES;
     constexpr int VEC = Fmt<DT>::VEC;
     const int g = t.tile_seg[tile];
+    // Everything that depends on g alone is fetched together: the segment
+    // record and the first eight replica pointers (the pointer table is padded
+    // so that eight entries can always be read).
+    void* const* __restrict__ row = t.grad + static_cast<int64_t>(g) * t.R;   // this segment's R pointers
     const SegInfo si = t.seg[g];
+    const char* pre[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pre[i] = static_cast<const char*>(row[i]);
     const int64_t numel = si.numel;
     const int64_t ltile = tile - si.tile0;
     const bool zero = unused != nullptr && unused[si.param] != 0;
-    void* const* __restrict__ row = t.grad + static_cast<int64_t>(g) * t.R;   // this segment's R pointers
-    const char* dst0 = static_cast<const char*>(row[0]);
-    const int sh = lead_in(dst0, ES);
-    const bool fast = si.congruent();   // every replica's tensor sits at the same offset modulo 16
+    const int sh = si.lead_bytes() / ES;    // replica 0's tensor starts this many elements past a 16-byte boundary
+    const bool fast = si.congruent();       // every replica's tensor sits at the same offset modulo 16
     const int64_t e_tile = ltile * (TILE_BYTES / ES) - sh;
 
     if (fast && !zero && e_tile >= 0 && e_tile + TILE_BYTES / ES <= numel) {
@@ -420,12 +448,14 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
             float acc[U][VEC];
 #pragma unroll
             for (int u = 0; u < U; ++u) lane_off[u] = ((step * U + u) * BLOCK + threadIdx.x) * 16u;
-            sum_interior<DT, NT, U>(
-                [&](int r) { return static_cast<const char*>(row[r]) + tile_byte; }, R, lane_off, acc);
+            sum_interior_pre<DT, NT, U>(
+                pre, tile_byte, [&](int r) { return static_cast<const char*>(row[r]) + tile_byte; }, R,
+                lane_off, acc);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const u32x4 out = scaled<DT>(sc, acc[u]);
-                for (int w = 0; w < nwrite; ++w)
+                store16s<NT>(const_cast<char*>(pre[0]) + tile_byte + lane_off[u], out);
+                for (int w = 1; w < nwrite; ++w)
                     store16s<NT>(static_cast<char*>(row[w]) + tile_byte + lane_off[u], out);
             }
         }
@@ -512,9 +542,12 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_pair_kernel(SegTables t, i
     if (tile_b < tile_end) {
         const int g = t.tile_seg[tile_a];
         if (g == t.tile_seg[tile_b]) {
-            const SegInfo si = t.seg[g];
             void* const* __restrict__ row = t.grad + static_cast<int64_t>(g) * t.R;
-            const int sh = lead_in(row[0], ES);
+            const SegInfo si = t.seg[g];
+            const char* pre[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pre[i] = static_cast<const char*>(row[i]);
+            const int sh = si.lead_bytes() / ES;
             const int64_t e_tile = (tile_a - si.tile0) * (TILE_BYTES / ES) - sh;
             const bool zero = unused != nullptr && unused[si.param] != 0;
             if (si.congruent() && !zero && e_tile >= 0 && e_tile + 2 * (TILE_BYTES / ES) <= si.numel) {
@@ -523,12 +556,14 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_pair_kernel(SegTables t, i
                 float acc[U2][VEC];
 #pragma unroll
                 for (int u = 0; u < U2; ++u) lane_off[u] = (u * BLOCK + threadIdx.x) * 16u;
-                sum_interior<DT, NT, U2>(
-                    [&](int r) { return static_cast<const char*>(row[r]) + tile_byte; }, R, lane_off, acc);
+                sum_interior_pre<DT, NT, U2>(
+                    pre, tile_byte, [&](int r) { return static_cast<const char*>(row[r]) + tile_byte; }, R,
+                    lane_off, acc);
 #pragma unroll
                 for (int u = 0; u < U2; ++u) {
                     const u32x4 out = scaled<DT>(sc, acc[u]);
-                    for (int w = 0; w < nwrite; ++w)
+                    store16s<NT>(const_cast<char*>(pre[0]) + tile_byte + lane_off[u], out);
+                    for (int w = 1; w < nwrite; ++w)
                         store16s<NT>(static_cast<char*>(row[w]) + tile_byte + lane_off[u], out);
                 }
                 return;
