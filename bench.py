@@ -76,6 +76,8 @@ def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup
             lib.ddp_set_option(ctx, lib.DDP_OPT_NONTEMPORAL, 0)
         if args.unroll is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_UNROLL, args.unroll)
+        if args.copy_nt_store:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_COPY_NT_STORE, 1)
         if args.pair_min_mib is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_PAIR_MIN_BYTES, int(args.pair_min_mib * (1 << 20)))
 
@@ -127,6 +129,8 @@ def main() -> int:
     ap.add_argument("--unroll", type=int, default=None, choices=[1, 2, 4])
     ap.add_argument("--pair-min-mib", type=float, default=None,
                     help="fused pipeline: bucket size from which blocks take two tiles")
+    ap.add_argument("--copy-nt-store", action="store_true",
+                    help="staged pipeline: pack/unpack store with the non-temporal hint")
     ap.add_argument("--same-stream", action="store_true",
                     help="use one stream for backward and reduction (no event plumbing)")
     ap.add_argument("--timing", default=None, choices=["launch", "iteration"],

@@ -82,6 +82,8 @@ typedef struct ddp_ctx ddp_ctx;
                                      thread block that sleeps between clock polls; n > 0: n blocks
                                      that do arithmetic between polls, so that the delay loads the
                                      GPU the way backward compute does */
+#define DDP_OPT_COPY_NT_STORE  9  /* any time: staged pipeline, pack and unpack store with the
+                                     non-temporal hint (1) or plainly (0, default) */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 

@@ -49,6 +49,7 @@ struct ddp_ctx {
     int32_t reduce_blocks = 0;
     int32_t nontemporal = 1;
     int32_t unroll = 2;
+    int32_t copy_nt_store = 0;
     int64_t pair_min_bytes = int64_t(48) << 20;   // buckets at least this large use paired tiles
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
 
@@ -179,7 +180,7 @@ int32_t launch_bucket(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t ca
         char* out = c->slabs + static_cast<int64_t>(c->R) * c->slab_stride + c->bucket_slab_off[b];
         if ((rc = timed_begin(c, DDP_K_PACK, b, c->reduce, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_pack(c->tables, tile_base, ntiles, c->slabs, c->slab_stride, c->R,
-                                   d_unused, c->reduce));
+                                   d_unused, c->copy_nt_store != 0, c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
         if ((rc = timed_begin(c, DDP_K_REDUCE, b, c->reduce, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_flat_reduce(bk.dtype, in0, c->slab_stride, out, c->bucket_vecs[b],
@@ -312,6 +313,9 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
         case DDP_OPT_EMIT_BUSY_BLOCKS:
             if (value < 0 || value > 4096) return fail(c, DDP_ERR_ARG, "busy blocks outside [0, 4096]");
             c->emit_busy_blocks = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_COPY_NT_STORE:
+            c->copy_nt_store = value != 0;
             return DDP_OK;
         case DDP_OPT_PAIR_MIN_BYTES:
             if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
@@ -580,7 +584,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             if ((rc = timed_begin(c, DDP_K_UNPACK, -1, c->reduce, &slot)) != DDP_OK) return rc;
             HIPCHK(c, ddp::launch_unpack(c->tables, 0, c->h_tile0[n],
                                          c->slabs + static_cast<int64_t>(c->R) * c->slab_stride,
-                                         c->write_all ? c->R : 1, c->reduce));
+                                         c->write_all ? c->R : 1, c->copy_nt_store != 0, c->reduce));
             if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
         }
         if (c->backward != c->reduce) {

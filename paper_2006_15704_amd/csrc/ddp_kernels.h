@@ -63,11 +63,12 @@ struct Scale {       // y = use_mul ? s * mul : s / div
 // K1: gradients -> flat replica slabs for all `nrep` replicas.  unused (may be
 // null): per-parameter flags, 1 = write zeros and do not read the gradient.
 hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
-                       int64_t slab_stride, int nrep, const uint8_t* unused, hipStream_t s);
+                       int64_t slab_stride, int nrep, const uint8_t* unused, bool nt_store,
+                       hipStream_t s);
 
 // K3: averaged slab -> gradient tensors of replicas [0, nrep).
 hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
-                         const char* out_slab, int nrep, hipStream_t s);
+                         const char* out_slab, int nrep, bool nt_store, hipStream_t s);
 
 // K2 (staged): out[v] = scale(sum_r in_r[v]) over nvec 16-byte vectors;
 // in_r = in0 + r*stride.  unroll = vectors per thread (1, 2 or 4);

@@ -173,7 +173,7 @@ __device__ __forceinline__ u32x4 gather16(const char* p) {
 }
 
 // ---- K1 / K3: segment copies ---------------------------------------------
-template <int ES>
+template <int ES, bool NTS>
 __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __restrict__ dst,
                                           int64_t numel, int64_t ltile, bool zero) {
     constexpr int VEC = 16 / ES;
@@ -195,7 +195,7 @@ __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         if (kind[k] == V_FULL) {
-            store16(dst + e[k] * ES, v[k]);
+            store16s<NTS>(dst + e[k] * ES, v[k]);
         } else if (kind[k] == V_EDGE) {
             for (int i = 0; i < VEC; ++i) {
                 const int64_t idx = e[k] + i;
@@ -211,7 +211,7 @@ __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __
 }
 
 // PACK: grad[r][g] -> slab_r + flat_byte[g];  UNPACK: out slab -> grad[r][g].
-template <bool PACK>
+template <bool PACK, bool NTS>
 __global__ __launch_bounds__(BLOCK) void seg_copy_kernel(SegTables t, int64_t tile_base,
                                                          char* slab0, int64_t slab_stride,
                                                          const uint8_t* __restrict__ unused) {
@@ -232,8 +232,8 @@ __global__ __launch_bounds__(BLOCK) void seg_copy_kernel(SegTables t, int64_t ti
         src = slab0 + si.flat_byte;
         dst = grad;
     }
-    if (si.dtype() == 0) copy_tile<4>(src, dst, numel, ltile, zero);
-    else copy_tile<2>(src, dst, numel, ltile, zero);
+    if (si.dtype() == 0) copy_tile<4, NTS>(src, dst, numel, ltile, zero);
+    else copy_tile<2, NTS>(src, dst, numel, ltile, zero);
 }
 
 // ---- K2: reduce and average ------------------------------------------------
@@ -684,20 +684,21 @@ inline hipError_t after_launch() { return hipGetLastError(); }
 
 // ---- launch wrappers ---------------------------------------------------------
 hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
-                       int64_t slab_stride, int nrep, const uint8_t* unused, hipStream_t s) {
+                       int64_t slab_stride, int nrep, const uint8_t* unused, bool nt_store,
+                       hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
-    hipLaunchKernelGGL(seg_copy_kernel<true>, grid, dim3(BLOCK), 0, s, t, tile_base, slab0,
-                       slab_stride, unused);
+    if (nt_store) hipLaunchKernelGGL((seg_copy_kernel<true, true>), grid, dim3(BLOCK), 0, s, t, tile_base, slab0, slab_stride, unused);
+    else hipLaunchKernelGGL((seg_copy_kernel<true, false>), grid, dim3(BLOCK), 0, s, t, tile_base, slab0, slab_stride, unused);
     return after_launch();
 }
 
 hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
-                         const char* out_slab, int nrep, hipStream_t s) {
+                         const char* out_slab, int nrep, bool nt_store, hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
-    hipLaunchKernelGGL(seg_copy_kernel<false>, grid, dim3(BLOCK), 0, s, t, tile_base,
-                       const_cast<char*>(out_slab), int64_t(0), static_cast<const uint8_t*>(nullptr));
+    if (nt_store) hipLaunchKernelGGL((seg_copy_kernel<false, true>), grid, dim3(BLOCK), 0, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), static_cast<const uint8_t*>(nullptr));
+    else hipLaunchKernelGGL((seg_copy_kernel<false, false>), grid, dim3(BLOCK), 0, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), static_cast<const uint8_t*>(nullptr));
     return after_launch();
 }
 
