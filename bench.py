@@ -78,6 +78,9 @@ def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup
             lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_UNROLL, args.unroll)
         if args.copy_nt_store:
             lib.ddp_set_option(ctx, lib.DDP_OPT_COPY_NT_STORE, 1)
+        if args.coalesce_mib is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE,
+                               (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * (1 << 20)))
         if args.pair_min_mib is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_PAIR_MIN_BYTES, int(args.pair_min_mib * (1 << 20)))
 
@@ -122,6 +125,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-staged-leg", action="store_true",
                     help="skip the extra measurement of the staged pipeline's kernels")
+    ap.add_argument("--no-coalesce-leg", action="store_true",
+                    help="skip the extra measurement with coalesced launches")
     ap.add_argument("--no-accumulate-leg", action="store_true",
                     help="skip the extra measurement of the no_sync accumulation kernel")
     ap.add_argument("--reduce-blocks", type=int, default=None)
@@ -129,6 +134,9 @@ def main() -> int:
     ap.add_argument("--unroll", type=int, default=None, choices=[1, 2, 4])
     ap.add_argument("--pair-min-mib", type=float, default=None,
                     help="fused pipeline: bucket size from which blocks take two tiles")
+    ap.add_argument("--coalesce-mib", type=float, default=None,
+                    help="buckets completed by one call share a launch up to this many MiB "
+                         "(DDP_OPT_COALESCE; negative = no limit)")
     ap.add_argument("--copy-nt-store", action="store_true",
                     help="staged pipeline: pack/unpack store with the non-temporal hint")
     ap.add_argument("--same-stream", action="store_true",
@@ -191,11 +199,16 @@ def main() -> int:
     red_ms, red_ids = m["reduce"]
     iter_ms, iter_launches = m["iteration"]
 
+    def launch_elems(ident):
+        """elements covered by a launch id (first bucket + 65536 * further buckets)"""
+        first, extra = int(ident) % 65536, int(ident) // 65536
+        return sum(bucket_elems[first:first + extra + 1])
+
     # reduce kernel: algorithmic bytes per launch = (R + 1) * bucket bytes
     per_bucket = {}
     if timing == "launch":
         launches = len(red_ms)
-        total_alg = float(sum((R + 1) * bucket_elems[b] * es for b in red_ids))
+        total_alg = float(sum((R + 1) * launch_elems(b) * es for b in red_ids))
         total_ms = float(red_ms.sum())
         for b in range(n_buckets):
             sel = red_ms[red_ids == b]
@@ -256,7 +269,7 @@ def main() -> int:
         steps2 = max(5, args.steps // 2)
         st = measure(lib, harness, torch, grads, cap, codes["staged"], order, steps2, 2, "launch", args)
         s_red_ms, s_red_ids = st["reduce"]
-        red_alg = float(sum((R + 1) * bucket_elems[b] * es for b in s_red_ids))
+        red_alg = float(sum((R + 1) * launch_elems(b) * es for b in s_red_ids))
         out["staged"] = {
             "ms_per_step": round(st["ms_per_step"], 4),
             "value_gbps": round((R + W) * B / st["ms_per_step"] / 1e6, 1),
@@ -265,6 +278,20 @@ def main() -> int:
             "unpack_gbps": round((1.0 + W) * B * steps2 / float(st["unpack"][0].sum()) / 1e6, 1),
             "bytes": "pack 2RB, reduce (R+1)B, unpack (1+W)B per step",
             "steps": steps2,
+        }
+
+    if args.pipeline == "fused" and args.coalesce_mib is None and not args.no_coalesce_leg:
+        # the same steps with DDP_OPT_COALESCE: buckets completed by one call share a launch
+        args.coalesce_mib = 100.0
+        co = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
+        args.coalesce_mib = None
+        co_ms, co_launches = co["iteration"]
+        out["coalesced_100mib"] = {
+            "ms_per_step": round(co["ms_per_step"], 4),
+            "value_gbps": round((R + W) * B / co["ms_per_step"] / 1e6, 1),
+            "launches_per_step": int(co_launches.sum()) // args.steps,
+            "reduce_gbps": round((R + 1) * B * len(co_ms) / float(co_ms.sum()) / 1e6, 1),
+            "frac_of_hbm_peak": round((R + 1) * B * len(co_ms) / float(co_ms.sum()) / 1e6 / HBM_PEAK_GBPS, 4),
         }
 
     if not args.no_accumulate_leg:

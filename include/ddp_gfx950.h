@@ -84,6 +84,13 @@ typedef struct ddp_ctx ddp_ctx;
                                      GPU the way backward compute does */
 #define DDP_OPT_COPY_NT_STORE  9  /* any time: staged pipeline, pack and unpack store with the
                                      non-temporal hint (1) or plainly (0, default) */
+#define DDP_OPT_COALESCE      10  /* any time: value > 0 = buckets that one API call makes launchable
+                                     (ddp_mark_ready_many, ddp_finalize_backward, ddp_synth_backward
+                                     between two of its kernels) and that are consecutive and of one
+                                     element type share ONE launch per kernel as long as the launch
+                                     stays within `value` bytes of bucket data (INT64_MAX: no
+                                     limit); order and results are unchanged.  Default 0 = one
+                                     launch per bucket */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 
@@ -232,9 +239,10 @@ int32_t ddp_synth_backward(ddp_ctx* ctx, const int32_t* order, int32_t count,
 /* With DDP_OPT_TIMING on: durations in milliseconds of the launches of `kind`
  * since the option was last set, in launch order.  Call after
  * ddp_synchronize.  ms holds `cap` entries; *n receives the count available.
- * ids (may be NULL) receives the bucket index of each launch (-1 if the launch
- * covered several buckets; for DDP_K_ITERATION the number of bucket launches
- * inside the interval). */
+ * ids (may be NULL) receives, per launch: for pack and reduce the first bucket
+ * of the launch plus 65536 times the number of further buckets coalesced into
+ * it; -1 for unpack and accumulate (whole model); for DDP_K_ITERATION the
+ * number of bucket launches inside the interval. */
 int32_t ddp_get_kernel_times(ddp_ctx* ctx, int32_t kind, float* ms, int32_t* ids,
                              int32_t cap, int32_t* n);
 

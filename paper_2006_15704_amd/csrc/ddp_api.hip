@@ -50,6 +50,8 @@ struct ddp_ctx {
     int32_t nontemporal = 1;
     int32_t unroll = 2;
     int32_t copy_nt_store = 0;
+    int64_t coalesce = 0;                         // > 0: consecutive buckets of one API call share a
+                                                  // launch while it stays within this many bytes
     int64_t pair_min_bytes = int64_t(48) << 20;   // buckets at least this large use paired tiles
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
 
@@ -83,6 +85,8 @@ struct ddp_ctx {
     std::vector<TimedLaunch> timed;
     size_t open_group = static_cast<size_t>(-1);   // timing mode 2: the running iteration's entry
     bool ordered_in_call = false;   // reduce stream already ordered after backward in this API call
+    std::vector<int32_t> deferred;  // buckets made launchable by the running API call, not yet enqueued
+    const uint8_t* deferred_flags = nullptr;
     std::string err;
 };
 
@@ -136,26 +140,30 @@ void drop_timed(ddp_ctx* c) {
     c->open_group = static_cast<size_t>(-1);
 }
 
-// Enqueue everything bucket b needs on the reduce stream.
-int32_t launch_bucket(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t call_index) {
-    c->log_running.emplace_back(b, call_index);
-    if (c->plan_only) return DDP_OK;
-    const ddp::BucketInfo& bk = c->plan.buckets[b];
-    const int seg_begin = bk.seg_begin;
-    const int seg_end = seg_begin + static_cast<int>(bk.params.size());
+// Enqueue on the reduce stream everything buckets [first, last] need, as one
+// launch per kernel.  The buckets are consecutive, hold one element type, and
+// their tiles and slab ranges are contiguous.
+int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, const uint8_t* d_unused) {
+    const ddp::BucketInfo& bf = c->plan.buckets[first];
+    const ddp::BucketInfo& bl = c->plan.buckets[last];
+    const int seg_begin = bf.seg_begin;
+    const int seg_end = bl.seg_begin + static_cast<int>(bl.params.size());
     const int64_t tile_base = c->h_tile0[seg_begin];
     const int64_t ntiles = c->h_tile0[seg_end] - tile_base;
+    int64_t bytes = 0;
+    for (int32_t b = first; b <= last; ++b) bytes += static_cast<int64_t>(c->plan.buckets[b].bytes());
+    const int32_t id = first + 65536 * (last - first);
     if (c->backward != c->reduce) {
-        // Order the bucket after the gradient-producing work enqueued so far.
+        // Order the buckets after the gradient-producing work enqueued so far.
         // If the backward stream has already drained there is nothing to wait
-        // for, and the two queue packets are saved.
-        // Within one API call the caller cannot enqueue anything in between,
-        // so one ordering point serves every bucket the call launches.
+        // for, and the two queue packets are saved.  Within one API call the
+        // caller cannot enqueue anything in between, so one ordering point
+        // serves every bucket the call launches.
         if (!c->ordered_in_call) {
             const hipError_t q = hipStreamQuery(c->backward);
             if (q == hipErrorNotReady) {
-                HIPCHK(c, hipEventRecord(c->ev_ready[b], c->backward));
-                HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_ready[b], 0));
+                HIPCHK(c, hipEventRecord(c->ev_ready[first], c->backward));
+                HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_ready[first], 0));
             } else if (q != hipSuccess) {
                 return fail(c, DDP_ERR_HIP, std::string("hipStreamQuery: ") + hipGetErrorString(q));
             }
@@ -176,26 +184,63 @@ int32_t launch_bucket(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t ca
     }
     if (c->timing == 2) c->timed[c->open_group].bucket += 1;   // counts the launches
     if (c->pipeline == DDP_PIPELINE_STAGED) {
-        char* in0 = c->slabs + c->bucket_slab_off[b];
-        char* out = c->slabs + static_cast<int64_t>(c->R) * c->slab_stride + c->bucket_slab_off[b];
-        if ((rc = timed_begin(c, DDP_K_PACK, b, c->reduce, &slot)) != DDP_OK) return rc;
+        char* in0 = c->slabs + c->bucket_slab_off[first];
+        char* out = c->slabs + static_cast<int64_t>(c->R) * c->slab_stride + c->bucket_slab_off[first];
+        // the range of the slab from the first bucket's base to the last one's padded end
+        const int64_t nvec = (c->bucket_slab_off[last] - c->bucket_slab_off[first]) / 16 + c->bucket_vecs[last];
+        if ((rc = timed_begin(c, DDP_K_PACK, id, c->reduce, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_pack(c->tables, tile_base, ntiles, c->slabs, c->slab_stride, c->R,
                                    d_unused, c->copy_nt_store != 0, c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
-        if ((rc = timed_begin(c, DDP_K_REDUCE, b, c->reduce, &slot)) != DDP_OK) return rc;
-        HIPCHK(c, ddp::launch_flat_reduce(bk.dtype, in0, c->slab_stride, out, c->bucket_vecs[b],
-                                          c->R, sc, c->reduce_blocks, c->unroll,
-                                          c->nontemporal != 0, c->reduce));
+        if ((rc = timed_begin(c, DDP_K_REDUCE, id, c->reduce, &slot)) != DDP_OK) return rc;
+        HIPCHK(c, ddp::launch_flat_reduce(bf.dtype, in0, c->slab_stride, out, nvec, c->R, sc,
+                                          c->reduce_blocks, c->unroll, c->nontemporal != 0, c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
     } else {
-        if ((rc = timed_begin(c, DDP_K_REDUCE, b, c->reduce, &slot)) != DDP_OK) return rc;
-        HIPCHK(c, ddp::launch_fused_reduce(bk.dtype, c->tables, tile_base, ntiles, c->R,
+        if ((rc = timed_begin(c, DDP_K_REDUCE, id, c->reduce, &slot)) != DDP_OK) return rc;
+        HIPCHK(c, ddp::launch_fused_reduce(bf.dtype, c->tables, tile_base, ntiles, c->R,
                                            c->write_all ? c->R : 1, d_unused, sc, c->unroll,
-                                           static_cast<int64_t>(bk.bytes()) >= c->pair_min_bytes,
-                                           c->nontemporal != 0, c->reduce));
+                                           bytes >= c->pair_min_bytes, c->nontemporal != 0, c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
     }
     return DDP_OK;
+}
+
+// Enqueue the buckets the running API call has made launchable: one launch per
+// bucket, or (DDP_OPT_COALESCE) one per run of consecutive buckets of equal
+// element type.
+int32_t flush_deferred(ddp_ctx* c) {
+    if (c->deferred.empty()) return DDP_OK;
+    std::vector<int32_t> todo;
+    todo.swap(c->deferred);
+    const uint8_t* flags = c->deferred_flags;
+    c->deferred_flags = nullptr;
+    if (c->plan_only) return DDP_OK;
+    HIPCHK(c, hipSetDevice(c->device));
+    size_t i = 0;
+    while (i < todo.size()) {
+        size_t j = i;
+        if (c->coalesce > 0) {
+            uint64_t bytes = c->plan.buckets[todo[i]].bytes();
+            while (j + 1 < todo.size() && todo[j + 1] == todo[j] + 1 &&
+                   c->plan.buckets[todo[j + 1]].dtype == c->plan.buckets[todo[i]].dtype &&
+                   bytes + c->plan.buckets[todo[j + 1]].bytes() <= static_cast<uint64_t>(c->coalesce)) {
+                bytes += c->plan.buckets[todo[j + 1]].bytes();
+                ++j;
+            }
+        }
+        const int32_t st = launch_range(c, todo[i], todo[j], flags);
+        if (st != DDP_OK) return st;
+        i = j + 1;
+    }
+    return DDP_OK;
+}
+
+// Bucket b has become launchable: log it and queue it for flush_deferred.
+void note_launch(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t call_index) {
+    c->log_running.emplace_back(b, call_index);
+    c->deferred.push_back(b);
+    c->deferred_flags = d_unused;
 }
 
 // Frees what ddp_build_buckets allocates (also after a build that failed half
@@ -313,6 +358,10 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
         case DDP_OPT_EMIT_BUSY_BLOCKS:
             if (value < 0 || value > 4096) return fail(c, DDP_ERR_ARG, "busy blocks outside [0, 4096]");
             c->emit_busy_blocks = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_COALESCE:
+            if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
+            c->coalesce = value;
             return DDP_OK;
         case DDP_OPT_COPY_NT_STORE:
             c->copy_nt_store = value != 0;
@@ -519,11 +568,8 @@ static int32_t mark_one(ddp_ctx* c, int32_t param_id) {
     if (rc == -1) return fail(c, DDP_ERR_ARG, "ddp_mark_ready: parameter id out of range");
     if (rc == -2) return fail(c, DDP_ERR_ALREADY_READY, "ddp_mark_ready: parameter already marked in this iteration");
     c->used_running[param_id] = 1;
-    if (!launch.empty() && !c->plan_only) HIPCHK(c, hipSetDevice(c->device));
-    for (int32_t b : launch) {
-        const int32_t st = launch_bucket(c, b, nullptr, c->tracker.marks() - 1);
-        if (st != DDP_OK) return st;
-    }
+    for (int32_t b : launch) note_launch(c, b, nullptr, c->tracker.marks() - 1);
+    if (c->coalesce <= 0) return flush_deferred(c);
     return DDP_OK;
 }
 
@@ -531,7 +577,9 @@ int32_t ddp_mark_ready(ddp_ctx* c, int32_t param_id) {
     if (!c) return DDP_ERR_ARG;
     if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready before ddp_build_buckets");
     c->ordered_in_call = false;
-    return mark_one(c, param_id);
+    const int32_t st = mark_one(c, param_id);
+    if (st != DDP_OK) return st;
+    return flush_deferred(c);
 }
 
 int32_t ddp_mark_ready_many(ddp_ctx* c, const int32_t* ids, int32_t count) {
@@ -540,9 +588,12 @@ int32_t ddp_mark_ready_many(ddp_ctx* c, const int32_t* ids, int32_t count) {
     c->ordered_in_call = false;
     for (int32_t k = 0; k < count; ++k) {
         const int32_t st = mark_one(c, ids[k]);
-        if (st != DDP_OK) return st;
+        if (st != DDP_OK) {
+            (void)flush_deferred(c);   // what the earlier marks completed is still launched
+            return st;
+        }
     }
-    return DDP_OK;
+    return flush_deferred(c);
 }
 
 int32_t ddp_finalize_backward(ddp_ctx* c) {
@@ -569,8 +620,9 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             flags = c->d_unused;
         }
     }
-    for (int32_t b : launch) {
-        const int32_t st = launch_bucket(c, b, flags, marks);
+    for (int32_t b : launch) note_launch(c, b, flags, marks);
+    {
+        const int32_t st = flush_deferred(c);
         if (st != DDP_OK) return st;
     }
     if (!c->plan_only) {
@@ -673,6 +725,7 @@ int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, cons
             return fail(c, DDP_ERR_ARG, "ddp_synth_backward: delay outside [0, 100 ms]");
     }
     HIPCHK(c, hipSetDevice(c->device));
+    c->ordered_in_call = false;
     void** d_rows = nullptr;
     if (src_ptrs && count > 0) {
         const int64_t need = 2 * R * count;
@@ -703,18 +756,24 @@ int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, cons
         const int32_t p = order[k];
         const int64_t ticks = delay_ns ? delay_ns[k] * c->wall_clock_khz / 1000000 : 0;
         if (ticks > 0 || d_rows) {
+            // buckets completed so far go out before more backward work is enqueued
+            const int32_t stf = flush_deferred(c);
+            if (stf != DDP_OK) return stf;
+            c->ordered_in_call = false;
             HIPCHK(c, ddp::launch_emit(ticks, d_rows ? d_rows + 2 * R * k : nullptr, c->R,
                                        c->plan.params[p].numel, ddp::elem_size(c->plan.params[p].dtype),
                                        c->emit_busy_blocks, reinterpret_cast<float*>(c->d_unused),
                                        c->backward));
         }
         if (mark) {
-            c->ordered_in_call = false;   // a kernel was just enqueued on the backward stream
             const int32_t st = mark_one(c, p);
-            if (st != DDP_OK) return st;
+            if (st != DDP_OK) {
+                (void)flush_deferred(c);
+                return st;
+            }
         }
     }
-    return DDP_OK;
+    return flush_deferred(c);
 }
 
 int32_t ddp_get_kernel_times(ddp_ctx* c, int32_t kind, float* ms, int32_t* ids, int32_t cap,

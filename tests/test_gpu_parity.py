@@ -162,7 +162,8 @@ def test_kernel_variants_give_the_same_bits(dtype, unroll):
     for pair_min in (0, 1 << 40):
         for nt in (1, 0):
             opts = [(d.DDP_OPT_REDUCE_UNROLL, unroll), (d.DDP_OPT_PAIR_MIN_BYTES, pair_min),
-                    (d.DDP_OPT_NONTEMPORAL, nt)]
+                    (d.DDP_OPT_NONTEMPORAL, nt), (d.DDP_OPT_COPY_NT_STORE, nt),
+                    (d.DDP_OPT_COALESCE, (1 << 62) if pair_min == 0 else 0)]
             for pipeline in (STAGED, FUSED):
                 run_sync(numel, [dtype] * len(numel), reps, 1 << 22, pipeline, order=order, skew=skew,
                          options=opts, write_all=(nt == 0))
@@ -359,3 +360,39 @@ def test_many_small_parameters_with_the_largest_replica_count(pipeline):
     reps = gaussian_reps(15, numel, R, 1e-2)
     order = [int(p) for p in rng.permutation(n)][: n - 150]
     run_sync(numel, [FP32] * n, reps, 16384, pipeline, order=order, check_flat=False)
+
+
+# ---- coalesced launches --------------------------------------------------------------------------
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_coalesced_launches_keep_order_results_and_cover_every_bucket(pipeline):
+    """DDP_OPT_COALESCE: buckets completed inside one call go out as one launch
+    per run of equal element type.  Same launch log, same bits; the launch ids
+    of the timed kernels decode to a partition of the buckets."""
+    d, harness = lib()
+    numel = [300, 5000, 64, 4096, 9000, 33, 2048, 100, 7000, 12]
+    dtypes = [FP32, FP32, FP32, FP16, FP16, FP16, FP32, FP32, BF16, BF16]
+    n, R, cap = len(numel), 4, 8192
+    reps = [[workloads.gaussian_grad(16, r, 0, p, numel[p], 1e-2, dtypes[p]) for p in range(n)] for r in range(R)]
+    order = [9, 8, 7, 6, 4, 3, 2, 1, 0]           # parameter 5 is never marked
+    want, asg, wlog = oracle.synchronize(numel, dtypes, cap, reps, order)
+    grads = harness.DeviceGrads(numel, dtypes, R)
+    for r in range(R):
+        grads.upload_replica(r, reps[r])
+    with harness.Session(grads, cap, pipeline) as s:
+        d.ddp_set_option(s.ctx, d.DDP_OPT_COALESCE, 1 << 62)
+        d.ddp_set_option(s.ctx, d.DDP_OPT_TIMING, 1)
+        d.ddp_mark_ready_many(s.ctx, order[:5])
+        d.ddp_mark_ready_many(s.ctx, order[5:])
+        d.ddp_finalize_backward(s.ctx)
+        d.ddp_synchronize(s.ctx)
+        assert d.ddp_get_launch_log(s.ctx, 1) == wlog
+        _, ids = d.ddp_get_kernel_times(s.ctx, d.DDP_K_REDUCE)
+        covered = []
+        for ident in ids:
+            first, extra = int(ident) % 65536, int(ident) // 65536
+            covered += list(range(first, first + extra + 1))
+            assert len({asg.buckets[b].dtype for b in range(first, first + extra + 1)}) == 1
+        assert covered == list(range(len(asg.buckets)))
+        assert len(ids) < len(asg.buckets)          # something was in fact coalesced
+    for p in range(n):
+        assert grads.download(0, p).tobytes() == want[p].tobytes(), f"parameter {p}"
