@@ -21,7 +21,10 @@ Data Parallel Training", arXiv 2006.15704):
     the gradient tensors (the finalizing step described after Algorithm 1).
   * Section 3.2.3, second caveat: parameters that take no part in an
     iteration must not keep their bucket from becoming ready.  Here they
-    contribute zeros and receive zeros.
+    contribute zeros and receive zeros; with per-replica participation
+    (`synchronize_local`) a replica that did not use a parameter contributes
+    zeros, and Section 4.2's global bitmap (an OR over the ranks) decides
+    whether a parameter's gradients are written at all.
   * Section 3.2.4: under no_sync, gradients of several backward passes
     accumulate into the same tensor and are synchronized once afterwards.
 
@@ -275,6 +278,61 @@ def synchronize(numel: Sequence[int], dtype: Sequence[int], cap_bytes: int,
         avg = reduce_average(flats, asg.buckets[b].dtype)
         unpack_bucket(asg, b, avg, outs)
     return outs, asg, log
+
+
+# --------------------------------------------------------------------------
+# per-replica participation and the global bitmap  (Sections 3.2.3, 4.2)
+# --------------------------------------------------------------------------
+def global_used_bitmap(local_used: np.ndarray) -> np.ndarray:
+    """local_used[r][i] = 1 if replica r's backward pass produced a gradient
+    for parameter i.  The extra AllReduce on the bitmap tells every rank which
+    parameters were used by at least one rank: an OR over the replicas."""
+    local_used = np.asarray(local_used, dtype=np.uint8)
+    out = np.zeros(local_used.shape[1], dtype=np.uint8)
+    for r in range(local_used.shape[0]):
+        out = out | (local_used[r] != 0).astype(np.uint8)
+    return out
+
+
+def synchronize_local(numel: Sequence[int], dtype: Sequence[int], cap_bytes: int,
+                      replica_grads: Sequence[Sequence[np.ndarray]],
+                      marks: Sequence[Tuple[int, Sequence[int]]],
+                      find_unused: bool = True,
+                      prior_used: Optional[np.ndarray] = None):
+    """One synchronization in which every replica has its own set of used
+    parameters.  `marks` is the sequence of ready marks, each (parameter,
+    used[R]); `prior_used[r][i]` (optional) carries participation recorded by
+    earlier no_sync iterations, which the paper lets accumulate in the bitmap
+    until the next communication.  A replica that did not use a parameter
+    contributes zeros for it and its tensor is not read; the sum is still
+    divided by R (DDP always averages over all processes).  A parameter that
+    no replica used is globally unused: with find_unused its gradients stay as
+    they are, otherwise they become zeros.
+    Returns (outs[R][n] -- every replica's view of its gradient tensors after
+    the synchronization --, assignment, launch_log, global_used)."""
+    n, R = len(numel), len(replica_grads)
+    asg = assign_buckets(numel, dtype, cap_bytes)
+    local = np.zeros((R, n), dtype=np.uint8) if prior_used is None else (np.asarray(prior_used) != 0).astype(np.uint8)
+    order = []
+    for p, used in marks:
+        order.append(int(p))
+        for r in range(R):
+            if used[r]:
+                local[r, int(p)] = 1
+    log = launch_schedule(asg, order)
+    glob = global_used_bitmap(local)
+    outs = [[np.array(replica_grads[r][i], copy=True) for i in range(n)] for r in range(R)]
+    for b, _ in log:
+        flats = [pack_bucket(asg, b, replica_grads[r], [i for i in asg.buckets[b].params if not local[r, i]])
+                 for r in range(R)]
+        avg = reduce_average(flats, asg.buckets[b].dtype)
+        res: List[Optional[np.ndarray]] = [None] * n
+        unpack_bucket(asg, b, avg, res)
+        for i in asg.buckets[b].params:
+            if glob[i] or not find_unused:
+                for r in range(R):
+                    outs[r][i] = res[i].copy()
+    return outs, asg, log, glob
 
 
 def mean_definition_f64(replica_grads: Sequence[Sequence[np.ndarray]],
