@@ -91,6 +91,10 @@ typedef struct ddp_ctx ddp_ctx;
                                      stays within `value` bytes of bucket data (INT64_MAX: no
                                      limit); order and results are unchanged.  Default 0 = one
                                      launch per bucket */
+#define DDP_OPT_FIND_UNUSED   11  /* any time between iterations: the paper's find_unused_parameters
+                                     knob.  1 = gradients of parameters that no replica used in the
+                                     iteration (the global bitmap of Section 4.2 says so) are left
+                                     exactly as they are; 0 (default) = they are written as zeros */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 
@@ -178,6 +182,25 @@ int32_t ddp_get_bucket_ptr(const ddp_ctx* ctx, int32_t b, int32_t r, void** ptr)
  * marked twice in one iteration -> DDP_ERR_ALREADY_READY (no state change). */
 int32_t ddp_mark_ready(ddp_ctx* ctx, int32_t param_id);
 
+/* Ready mark with per-replica participation (Section 3.2.3, last paragraph;
+ * Section 4.2 "Globally Unused Parameters"): used[r] != 0 (host array of R
+ * bytes) says that replica r's backward pass produced a gradient for the
+ * parameter.  A replica that did not contributes zeros to the sum (which is
+ * still divided by R) and its tensor is not read.  Participation recorded by
+ * ddp_no_sync_accumulate since the last finalize is OR-ed in (Section 3.2.4).
+ * ddp_mark_ready(p) is the same call with every used[r] = 1.  At finalize the
+ * per-replica flags are copied to the device and reduced with an OR over the
+ * replicas (the extra AllReduce on the bitmap); parameters whose global bit is
+ * 0 keep their gradients with DDP_OPT_FIND_UNUSED, else receive zeros.
+ * Errors as for ddp_mark_ready; used == NULL -> DDP_ERR_ARG. */
+int32_t ddp_mark_ready_local(ddp_ctx* ctx, int32_t param_id, const uint8_t* used);
+
+/* used[n] (host): the global bitmap of the synchronization closed by the latest
+ * ddp_finalize_backward, 1 = at least one replica used the parameter.  When any
+ * flag of that iteration was 0 this is the device-computed result (the call
+ * waits for the copy that finalize enqueued); otherwise it is all ones. */
+int32_t ddp_get_global_used(ddp_ctx* ctx, uint8_t* used);
+
 /* Same as calling ddp_mark_ready for ids[0..count) in order; stops at the
  * first error and returns it.  Buckets that complete during the call are
  * launched one after the other in index order; because the caller cannot
@@ -188,7 +211,10 @@ int32_t ddp_mark_ready_many(ddp_ctx* ctx, const int32_t* ids, int32_t count);
 /* The finalizing step described after Algorithm 1 (wait for the reductions and
  * write the averages back to the gradients), plus Section 3.2.3's handling of
  * absent gradients: parameters not marked in this iteration are treated as
- * ready with all-zero gradients (their memory is not read) and receive zeros;
+ * ready; replicas for which ddp_no_sync_accumulate recorded no gradient since
+ * the last finalize contribute zeros (their memory is not read); a parameter
+ * that nobody used receives zeros, or is left untouched with
+ * DDP_OPT_FIND_UNUSED;
  * remaining buckets are launched in order; the averaged buckets are copied
  * into the gradient tensors; backward_stream is made to wait for all of it, so
  * work enqueued on backward_stream afterwards sees the averaged gradients;

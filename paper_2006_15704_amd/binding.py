@@ -36,14 +36,15 @@ DDP_CAP_WHOLE_MODEL = (1 << 64) - 1
 DDP_OPT_PIPELINE, DDP_OPT_WRITE_ALL, DDP_OPT_TIMING = 1, 2, 3
 DDP_OPT_REDUCE_BLOCKS, DDP_OPT_NONTEMPORAL, DDP_OPT_REDUCE_UNROLL = 4, 5, 6
 DDP_OPT_PAIR_MIN_BYTES, DDP_OPT_EMIT_BUSY_BLOCKS, DDP_OPT_COPY_NT_STORE = 7, 8, 9
-DDP_OPT_COALESCE = 10
+DDP_OPT_COALESCE, DDP_OPT_FIND_UNUSED = 10, 11
 DDP_PIPELINE_STAGED, DDP_PIPELINE_FUSED = 0, 1
 DDP_K_PACK, DDP_K_REDUCE, DDP_K_UNPACK, DDP_K_ACCUMULATE, DDP_K_ITERATION = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "ddp_version", "ddp_last_error", "ddp_create", "ddp_destroy", "ddp_set_option",
     "ddp_register_params", "ddp_build_buckets", "ddp_get_assignment",
-    "ddp_get_bucket_info", "ddp_get_bucket_ptr", "ddp_mark_ready",
+    "ddp_get_bucket_info", "ddp_get_bucket_ptr", "ddp_mark_ready", "ddp_mark_ready_local",
+    "ddp_get_global_used",
     "ddp_mark_ready_many", "ddp_finalize_backward", "ddp_synchronize",
     "ddp_get_launch_log", "ddp_no_sync_accumulate", "ddp_get_used_map",
     "ddp_synth_backward", "ddp_get_kernel_times",
@@ -76,6 +77,8 @@ _lib.ddp_get_assignment.argtypes = [_vp, C.POINTER(_i32), C.POINTER(_i64)]
 _lib.ddp_get_bucket_info.argtypes = [_vp, _i32, C.POINTER(_i64), C.POINTER(_i32), C.POINTER(_i32)]
 _lib.ddp_get_bucket_ptr.argtypes = [_vp, _i32, _i32, C.POINTER(_vp)]
 _lib.ddp_mark_ready.argtypes = [_vp, _i32]
+_lib.ddp_mark_ready_local.argtypes = [_vp, _i32, C.POINTER(C.c_uint8)]
+_lib.ddp_get_global_used.argtypes = [_vp, C.POINTER(C.c_uint8)]
 _lib.ddp_mark_ready_many.argtypes = [_vp, C.POINTER(_i32), _i32]
 _lib.ddp_finalize_backward.argtypes = [_vp]
 _lib.ddp_synchronize.argtypes = [_vp]
@@ -122,16 +125,21 @@ def ddp_last_error(ctx) -> str:
     return msg.decode() if msg else ""
 
 
+_replicas = {}      # context address -> R, for checking array lengths before they cross the C ABI
+
+
 def ddp_create(R: int, device: int, reduce_stream: int = 0, backward_stream: int = 0):
     """Returns the opaque context handle.  Streams are raw hipStream_t values
     (torch.cuda.Stream.cuda_stream)."""
     handle = _vp()
     _check(None, _lib.ddp_create(C.byref(handle), R, device, _vp(reduce_stream or None),
                                  _vp(backward_stream or None)))
+    _replicas[handle.value] = int(R)
     return handle
 
 
 def ddp_destroy(ctx) -> None:
+    _replicas.pop(ctx.value, None)
     _check(ctx, _lib.ddp_destroy(ctx))
 
 
@@ -176,6 +184,20 @@ def ddp_get_bucket_ptr(ctx, b: int, r: int) -> int:
 
 def ddp_mark_ready(ctx, param_id: int) -> None:
     _check(ctx, _lib.ddp_mark_ready(ctx, param_id))
+
+
+def ddp_mark_ready_local(ctx, param_id: int, used) -> None:
+    """used: R flags, non-zero = that replica produced a gradient for the parameter."""
+    arr = np.ascontiguousarray([1 if u else 0 for u in used], dtype=np.uint8)
+    if arr.size != _replicas.get(ctx.value, arr.size):     # the library reads exactly R bytes
+        raise ValueError(f"used has {arr.size} flags, the context has {_replicas[ctx.value]} replicas")
+    _check(ctx, _lib.ddp_mark_ready_local(ctx, param_id, _as(arr, C.c_uint8)))
+
+
+def ddp_get_global_used(ctx, n: int) -> np.ndarray:
+    used = np.zeros(n, dtype=np.uint8)
+    _check(ctx, _lib.ddp_get_global_used(ctx, _as(used, C.c_uint8)))
+    return used
 
 
 def ddp_mark_ready_many(ctx, ids) -> None:

@@ -69,16 +69,32 @@ struct ddp_ctx {
     void* d_tables = nullptr;                // one allocation holding all segment tables
     int32_t* d_tile_seg = nullptr;           // [tiles] segment index of every tile
     ddp::SegTables tables{};
-    uint8_t* d_unused = nullptr;
-    uint8_t* h_unused = nullptr;             // pinned
+    // participation flags: [segment][replica], 1 = the replica used the parameter
+    int32_t find_unused = 0;                 // 1: parameters nobody used keep their gradients
+    std::vector<uint8_t> local_cur;          // running iteration (rows of marked parameters are valid)
+    std::vector<uint8_t> acc_used;           // recorded by ddp_no_sync_accumulate since the last finalize
+    std::vector<uint8_t> bucket_zero;        // per bucket: some flag of the running iteration is 0
+    bool iter_zero = false;                  // any flag of the running iteration is 0
+    int64_t iteration = 0;
+    int64_t pin_ready_iter = -1;             // iteration for which the pinned staging buffer was claimed
+    std::vector<uint8_t> global_closed;      // [n] host view of the closed iteration's global bitmap
+    bool global_on_device = false;           // closed iteration: the bitmap kernel ran, result in h_global
+    uint8_t* d_local = nullptr;              // [G*R]
+    uint8_t* d_global = nullptr;             // [G]
+    uint8_t* h_local[2] = {nullptr, nullptr};   // pinned staging, one per iteration parity
+    uint8_t* h_global = nullptr;             // pinned
+    hipEvent_t ev_local[2] = {nullptr, nullptr};
+    hipEvent_t ev_global = nullptr;
+    bool local_in_flight[2] = {false, false};
+    bool global_in_flight = false;
     void** d_micro = nullptr;
     void** h_micro = nullptr;                // pinned
     void** d_emit = nullptr;
     void** h_emit = nullptr;                 // pinned
     int64_t emit_cap = 0;                    // pointers
     std::vector<hipEvent_t> ev_ready;        // one per bucket
-    hipEvent_t ev_done = nullptr, ev_flags = nullptr, ev_micro = nullptr, ev_emit = nullptr;
-    bool flags_in_flight = false, micro_in_flight = false, emit_in_flight = false;
+    hipEvent_t ev_done = nullptr, ev_micro = nullptr, ev_emit = nullptr;
+    bool micro_in_flight = false, emit_in_flight = false;
 
     std::vector<std::pair<int32_t, int32_t>> log_running, log_closed;
     std::vector<uint8_t> used_running, used_closed;
@@ -86,7 +102,6 @@ struct ddp_ctx {
     size_t open_group = static_cast<size_t>(-1);   // timing mode 2: the running iteration's entry
     bool ordered_in_call = false;   // reduce stream already ordered after backward in this API call
     std::vector<int32_t> deferred;  // buckets made launchable by the running API call, not yet enqueued
-    const uint8_t* deferred_flags = nullptr;
     std::string err;
 };
 
@@ -143,7 +158,7 @@ void drop_timed(ddp_ctx* c) {
 // Enqueue on the reduce stream everything buckets [first, last] need, as one
 // launch per kernel.  The buckets are consecutive, hold one element type, and
 // their tiles and slab ranges are contiguous.
-int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, const uint8_t* d_unused) {
+int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
     const ddp::BucketInfo& bf = c->plan.buckets[first];
     const ddp::BucketInfo& bl = c->plan.buckets[last];
     const int seg_begin = bf.seg_begin;
@@ -153,6 +168,27 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, const uint8_t* d_u
     int64_t bytes = 0;
     for (int32_t b = first; b <= last; ++b) bytes += static_cast<int64_t>(c->plan.buckets[b].bytes());
     const int32_t id = first + 65536 * (last - first);
+    // Participation flags travel to the device only for launches that hold a
+    // zero flag (a replica that did not use a parameter, or a parameter nobody
+    // marked); everything else runs without a flag table.
+    const uint8_t* d_flags = nullptr;
+    bool need_flags = false;
+    for (int32_t b = first; b <= last; ++b) need_flags = need_flags || c->bucket_zero[b] != 0;
+    if (need_flags) {
+        const int par = static_cast<int>(c->iteration & 1);
+        if (c->pin_ready_iter != c->iteration) {      // first use in this iteration: the copies of
+            if (c->local_in_flight[par])               // two iterations ago must have left the buffer
+                HIPCHK(c, hipEventSynchronize(c->ev_local[par]));
+            c->pin_ready_iter = c->iteration;
+        }
+        const size_t off = static_cast<size_t>(seg_begin) * c->R;
+        const size_t len = static_cast<size_t>(seg_end - seg_begin) * c->R;
+        std::memcpy(c->h_local[par] + off, c->local_cur.data() + off, len);
+        HIPCHK(c, hipMemcpyAsync(c->d_local + off, c->h_local[par] + off, len, hipMemcpyHostToDevice, c->reduce));
+        HIPCHK(c, hipEventRecord(c->ev_local[par], c->reduce));
+        c->local_in_flight[par] = true;
+        d_flags = c->d_local;
+    }
     if (c->backward != c->reduce) {
         // Order the buckets after the gradient-producing work enqueued so far.
         // If the backward stream has already drained there is nothing to wait
@@ -190,7 +226,7 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, const uint8_t* d_u
         const int64_t nvec = (c->bucket_slab_off[last] - c->bucket_slab_off[first]) / 16 + c->bucket_vecs[last];
         if ((rc = timed_begin(c, DDP_K_PACK, id, c->reduce, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_pack(c->tables, tile_base, ntiles, c->slabs, c->slab_stride, c->R,
-                                   d_unused, c->copy_nt_store != 0, c->reduce));
+                                   d_flags, c->copy_nt_store != 0, c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, c->reduce, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_flat_reduce(bf.dtype, in0, c->slab_stride, out, nvec, c->R, sc,
@@ -199,8 +235,9 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, const uint8_t* d_u
     } else {
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, c->reduce, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_fused_reduce(bf.dtype, c->tables, tile_base, ntiles, c->R,
-                                           c->write_all ? c->R : 1, d_unused, sc, c->unroll,
-                                           bytes >= c->pair_min_bytes, c->nontemporal != 0, c->reduce));
+                                           c->write_all ? c->R : 1, d_flags, c->find_unused != 0, sc,
+                                           c->unroll, bytes >= c->pair_min_bytes, c->nontemporal != 0,
+                                           c->reduce));
         if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
     }
     return DDP_OK;
@@ -213,8 +250,6 @@ int32_t flush_deferred(ddp_ctx* c) {
     if (c->deferred.empty()) return DDP_OK;
     std::vector<int32_t> todo;
     todo.swap(c->deferred);
-    const uint8_t* flags = c->deferred_flags;
-    c->deferred_flags = nullptr;
     if (c->plan_only) return DDP_OK;
     HIPCHK(c, hipSetDevice(c->device));
     size_t i = 0;
@@ -229,7 +264,7 @@ int32_t flush_deferred(ddp_ctx* c) {
                 ++j;
             }
         }
-        const int32_t st = launch_range(c, todo[i], todo[j], flags);
+        const int32_t st = launch_range(c, todo[i], todo[j]);
         if (st != DDP_OK) return st;
         i = j + 1;
     }
@@ -237,10 +272,9 @@ int32_t flush_deferred(ddp_ctx* c) {
 }
 
 // Bucket b has become launchable: log it and queue it for flush_deferred.
-void note_launch(ddp_ctx* c, int32_t b, const uint8_t* d_unused, int32_t call_index) {
+void note_launch(ddp_ctx* c, int32_t b, int32_t call_index) {
     c->log_running.emplace_back(b, call_index);
     c->deferred.push_back(b);
-    c->deferred_flags = d_unused;
 }
 
 // Frees what ddp_build_buckets allocates (also after a build that failed half
@@ -252,12 +286,17 @@ void release_build(ddp_ctx* c) {
     if (c->slabs) (void)hipFree(c->slabs);
     if (c->d_tables) (void)hipFree(c->d_tables);
     if (c->d_tile_seg) (void)hipFree(c->d_tile_seg);
-    if (c->d_unused) (void)hipFree(c->d_unused);
+    if (c->d_local) (void)hipFree(c->d_local);
+    if (c->d_global) (void)hipFree(c->d_global);
     if (c->d_micro) (void)hipFree(c->d_micro);
-    if (c->h_unused) (void)hipHostFree(c->h_unused);
+    for (int k = 0; k < 2; ++k) {
+        if (c->h_local[k]) (void)hipHostFree(c->h_local[k]);
+        c->h_local[k] = nullptr;
+    }
+    if (c->h_global) (void)hipHostFree(c->h_global);
     if (c->h_micro) (void)hipHostFree(c->h_micro);
-    c->slabs = nullptr; c->d_tables = nullptr; c->d_tile_seg = nullptr; c->d_unused = nullptr;
-    c->d_micro = nullptr; c->h_unused = nullptr; c->h_micro = nullptr;
+    c->slabs = nullptr; c->d_tables = nullptr; c->d_tile_seg = nullptr; c->d_local = nullptr;
+    c->d_global = nullptr; c->d_micro = nullptr; c->h_global = nullptr; c->h_micro = nullptr;
 }
 
 void release_device(ddp_ctx* c) {
@@ -268,7 +307,7 @@ void release_device(ddp_ctx* c) {
     if (!c->reduce || !c->backward) (void)hipStreamSynchronize(nullptr);
     drop_timed(c);
     release_build(c);
-    for (hipEvent_t* e : {&c->ev_done, &c->ev_flags, &c->ev_micro, &c->ev_emit})
+    for (hipEvent_t* e : {&c->ev_done, &c->ev_micro, &c->ev_emit, &c->ev_local[0], &c->ev_local[1], &c->ev_global})
         if (*e) { (void)hipEventDestroy(*e); *e = nullptr; }
     if (c->d_emit) (void)hipFree(c->d_emit);
     if (c->h_emit) (void)hipHostFree(c->h_emit);
@@ -313,7 +352,9 @@ int32_t ddp_create(ddp_ctx** out, int32_t R, int32_t device, void* reduce_stream
         if (e == hipSuccess) e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device);
         if (e == hipSuccess && khz > 0) c->wall_clock_khz = khz;
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_done, kOrderEvent);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_flags, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_local[0], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_local[1], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_global, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_micro, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_emit, hipEventDisableTiming);
         if (e != hipSuccess) {
@@ -358,6 +399,9 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
         case DDP_OPT_EMIT_BUSY_BLOCKS:
             if (value < 0 || value > 4096) return fail(c, DDP_ERR_ARG, "busy blocks outside [0, 4096]");
             c->emit_busy_blocks = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_FIND_UNUSED:
+            c->find_unused = value != 0;
             return DDP_OK;
         case DDP_OPT_COALESCE:
             if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
@@ -426,6 +470,10 @@ int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
     const int32_t nb = static_cast<int32_t>(c->plan.buckets.size());
     c->used_running.assign(n, 0);
     c->used_closed.assign(n, 0);
+    c->local_cur.assign(static_cast<size_t>(n) * c->R, 0);
+    c->acc_used.assign(static_cast<size_t>(n) * c->R, 0);
+    c->bucket_zero.assign(nb, 0);
+    c->global_closed.assign(n, 0);
 
     if (!c->plan_only) {
         // slab layout: bucket bases aligned to 256 bytes, lengths padded to 16
@@ -511,8 +559,12 @@ int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
             c->tables.tile_seg = c->d_tile_seg;
         }
 
-        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_unused), static_cast<size_t>(n) + 16));
-        HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_unused), static_cast<size_t>(n), hipHostMallocDefault));
+        const size_t flag_bytes = static_cast<size_t>(n) * R;
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_local), flag_bytes + 16));
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_global), static_cast<size_t>(n) + 16));
+        for (int k = 0; k < 2; ++k)
+            HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_local[k]), flag_bytes, hipHostMallocDefault));
+        HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_global), static_cast<size_t>(n), hipHostMallocDefault));
         HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_micro), sizeof(void*) * R * n));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_micro), sizeof(void*) * R * n, hipHostMallocDefault));
         c->ev_ready.resize(nb, nullptr);
@@ -562,13 +614,32 @@ int32_t ddp_get_bucket_ptr(const ddp_ctx* c, int32_t b, int32_t r, void** ptr) {
     return DDP_OK;
 }
 
-static int32_t mark_one(ddp_ctx* c, int32_t param_id) {
+// Writes the participation row of a parameter: used[r] (null = every replica),
+// OR what no_sync iterations recorded.  Returns whether any replica used it.
+static bool set_participation(ddp_ctx* c, int32_t param_id, const uint8_t* used) {
+    const ddp::ParamInfo& p = c->plan.params[param_id];
+    const size_t row = static_cast<size_t>(p.segment) * c->R;
+    bool any = false, zero = false;
+    for (int32_t r = 0; r < c->R; ++r) {
+        const uint8_t eff = ((used == nullptr || used[r] != 0) || c->acc_used[row + r] != 0) ? 1 : 0;
+        c->local_cur[row + r] = eff;
+        any = any || eff != 0;
+        zero = zero || eff == 0;
+    }
+    if (zero) {
+        c->bucket_zero[p.bucket] = 1;
+        c->iter_zero = true;
+    }
+    return any;
+}
+
+static int32_t mark_one(ddp_ctx* c, int32_t param_id, const uint8_t* used) {
     std::vector<int32_t> launch;
     const int rc = c->tracker.mark(param_id, launch);
     if (rc == -1) return fail(c, DDP_ERR_ARG, "ddp_mark_ready: parameter id out of range");
     if (rc == -2) return fail(c, DDP_ERR_ALREADY_READY, "ddp_mark_ready: parameter already marked in this iteration");
-    c->used_running[param_id] = 1;
-    for (int32_t b : launch) note_launch(c, b, nullptr, c->tracker.marks() - 1);
+    if (set_participation(c, param_id, used)) c->used_running[param_id] = 1;
+    for (int32_t b : launch) note_launch(c, b, c->tracker.marks() - 1);
     if (c->coalesce <= 0) return flush_deferred(c);
     return DDP_OK;
 }
@@ -577,7 +648,17 @@ int32_t ddp_mark_ready(ddp_ctx* c, int32_t param_id) {
     if (!c) return DDP_ERR_ARG;
     if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready before ddp_build_buckets");
     c->ordered_in_call = false;
-    const int32_t st = mark_one(c, param_id);
+    const int32_t st = mark_one(c, param_id, nullptr);
+    if (st != DDP_OK) return st;
+    return flush_deferred(c);
+}
+
+int32_t ddp_mark_ready_local(ddp_ctx* c, int32_t param_id, const uint8_t* used) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready_local before ddp_build_buckets");
+    if (!used) return fail(c, DDP_ERR_ARG, "ddp_mark_ready_local: used is null");
+    c->ordered_in_call = false;
+    const int32_t st = mark_one(c, param_id, used);
     if (st != DDP_OK) return st;
     return flush_deferred(c);
 }
@@ -587,7 +668,7 @@ int32_t ddp_mark_ready_many(ddp_ctx* c, const int32_t* ids, int32_t count) {
     if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready_many before ddp_build_buckets");
     c->ordered_in_call = false;
     for (int32_t k = 0; k < count; ++k) {
-        const int32_t st = mark_one(c, ids[k]);
+        const int32_t st = mark_one(c, ids[k], nullptr);
         if (st != DDP_OK) {
             (void)flush_deferred(c);   // what the earlier marks completed is still launched
             return st;
@@ -604,23 +685,20 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     c->ordered_in_call = false;
     std::vector<int32_t> launch;
     c->tracker.drain(launch);
-    const uint8_t* flags = nullptr;
-    if (!c->plan_only) {
-        HIPCHK(c, hipSetDevice(c->device));
-        if (marks < n) {
-            // Parameters never marked: reduce as zeros without reading them.
-            // Every bucket launched before this point was complete, so only
-            // the buckets in `launch` can contain such parameters.
-            if (c->flags_in_flight) HIPCHK(c, hipEventSynchronize(c->ev_flags));
-            for (int32_t i = 0; i < n; ++i) c->h_unused[i] = c->tracker.marked(i) ? 0 : 1;
-            HIPCHK(c, hipMemcpyAsync(c->d_unused, c->h_unused, static_cast<size_t>(n),
-                                     hipMemcpyHostToDevice, c->reduce));
-            HIPCHK(c, hipEventRecord(c->ev_flags, c->reduce));
-            c->flags_in_flight = true;
-            flags = c->d_unused;
-        }
+    if (!c->plan_only) HIPCHK(c, hipSetDevice(c->device));
+    if (marks < n) {
+        // Parameters never marked in this iteration: what earlier no_sync
+        // iterations recorded still counts (Section 3.2.4); replicas without any
+        // record contribute zeros and are not read.  Every bucket launched
+        // before this point was complete, so only the buckets in `launch` can
+        // contain such parameters.
+        for (int32_t i = 0; i < n; ++i)
+            if (!c->tracker.marked(i)) {
+                static const uint8_t nobody[DDP_MAX_REPLICAS] = {0};
+                if (set_participation(c, i, nobody)) c->used_running[i] = 1;
+            }
     }
-    for (int32_t b : launch) note_launch(c, b, flags, marks);
+    for (int32_t b : launch) note_launch(c, b, marks);
     {
         const int32_t st = flush_deferred(c);
         if (st != DDP_OK) return st;
@@ -630,13 +708,34 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             HIPCHK(c, hipEventRecord(c->timed[c->open_group].stop, c->reduce));
             c->open_group = static_cast<size_t>(-1);
         }
+        if (c->iter_zero) {
+            // The bitmap step of Section 4.2: the host bitmap goes to the device
+            // with a non-blocking copy and one extra reduction (an OR over the
+            // replicas) yields the parameters that somebody used.
+            const int par = static_cast<int>(c->iteration & 1);
+            if (c->pin_ready_iter != c->iteration) {
+                if (c->local_in_flight[par]) HIPCHK(c, hipEventSynchronize(c->ev_local[par]));
+                c->pin_ready_iter = c->iteration;
+            }
+            const size_t flag_bytes = static_cast<size_t>(n) * c->R;
+            std::memcpy(c->h_local[par], c->local_cur.data(), flag_bytes);
+            HIPCHK(c, hipMemcpyAsync(c->d_local, c->h_local[par], flag_bytes, hipMemcpyHostToDevice, c->reduce));
+            HIPCHK(c, hipEventRecord(c->ev_local[par], c->reduce));
+            c->local_in_flight[par] = true;
+            HIPCHK(c, ddp::launch_bitmap_or(c->d_local, c->d_global, n, c->R, c->reduce));
+            if (c->global_in_flight) HIPCHK(c, hipEventSynchronize(c->ev_global));
+            HIPCHK(c, hipMemcpyAsync(c->h_global, c->d_global, static_cast<size_t>(n), hipMemcpyDeviceToHost, c->reduce));
+            HIPCHK(c, hipEventRecord(c->ev_global, c->reduce));
+            c->global_in_flight = true;
+        }
         if (c->pipeline == DDP_PIPELINE_STAGED) {
             size_t slot;
             int32_t rc;
             if ((rc = timed_begin(c, DDP_K_UNPACK, -1, c->reduce, &slot)) != DDP_OK) return rc;
             HIPCHK(c, ddp::launch_unpack(c->tables, 0, c->h_tile0[n],
                                          c->slabs + static_cast<int64_t>(c->R) * c->slab_stride,
-                                         c->write_all ? c->R : 1, c->copy_nt_store != 0, c->reduce));
+                                         c->write_all ? c->R : 1, c->iter_zero ? c->d_global : nullptr,
+                                         c->find_unused != 0, c->copy_nt_store != 0, c->reduce));
             if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
         }
         if (c->backward != c->reduce) {
@@ -648,7 +747,34 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     c->log_running.clear();
     c->used_closed = c->used_running;
     std::fill(c->used_running.begin(), c->used_running.end(), 0);
+    // host view of the global bitmap (all ones unless a flag was zero)
+    for (int32_t i = 0; i < n; ++i) {
+        const size_t row = static_cast<size_t>(c->plan.params[i].segment) * c->R;
+        uint8_t any = 0;
+        for (int32_t r = 0; r < c->R; ++r) any |= c->local_cur[row + r];
+        c->global_closed[i] = any;
+    }
+    c->global_on_device = c->iter_zero && !c->plan_only;
+    std::fill(c->acc_used.begin(), c->acc_used.end(), 0);
+    std::fill(c->bucket_zero.begin(), c->bucket_zero.end(), 0);
+    c->iter_zero = false;
+    ++c->iteration;
     c->tracker.new_iteration();
+    return DDP_OK;
+}
+
+int32_t ddp_get_global_used(ddp_ctx* c, uint8_t* used) {
+    if (!c || !used) return DDP_ERR_ARG;
+    if (!c->built) return DDP_ERR_STATE;
+    const int32_t n = static_cast<int32_t>(c->plan.params.size());
+    if (c->global_on_device) {
+        // what the bitmap kernel computed, brought back by the copy enqueued at finalize
+        HIPCHK(c, hipSetDevice(c->device));
+        HIPCHK(c, hipEventSynchronize(c->ev_global));
+        for (int32_t i = 0; i < n; ++i) used[i] = c->h_global[c->plan.params[i].segment];
+    } else {
+        std::memcpy(used, c->global_closed.data(), static_cast<size_t>(n));
+    }
     return DDP_OK;
 }
 
@@ -697,9 +823,14 @@ int32_t ddp_no_sync_accumulate(ddp_ctx* c, void* const* micro) {
     if ((rc = timed_begin(c, DDP_K_ACCUMULATE, -1, c->backward, &slot)) != DDP_OK) return rc;
     HIPCHK(c, ddp::launch_accumulate(c->tables, c->h_tile0[n], c->R, n, c->d_micro, c->backward));
     if ((rc = timed_end(c, slot, c->backward)) != DDP_OK) return rc;
-    for (int32_t i = 0; i < n; ++i)
+    for (int32_t i = 0; i < n; ++i) {
+        const size_t row = static_cast<size_t>(c->plan.params[i].segment) * R;
         for (int64_t r = 0; r < R; ++r)
-            if (micro[r * n + i]) { c->used_running[i] = 1; break; }
+            if (micro[r * n + i]) {
+                c->acc_used[row + r] = 1;
+                c->used_running[i] = 1;
+            }
+    }
     return DDP_OK;
 }
 
@@ -762,11 +893,12 @@ int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, cons
             c->ordered_in_call = false;
             HIPCHK(c, ddp::launch_emit(ticks, d_rows ? d_rows + 2 * R * k : nullptr, c->R,
                                        c->plan.params[p].numel, ddp::elem_size(c->plan.params[p].dtype),
-                                       c->emit_busy_blocks, reinterpret_cast<float*>(c->d_unused),
+                                       c->emit_busy_blocks,
+                                       reinterpret_cast<float*>(c->d_global + round_up(n, 4)),   // spare tail
                                        c->backward));
         }
         if (mark) {
-            const int32_t st = mark_one(c, p);
+            const int32_t st = mark_one(c, p, nullptr);
             if (st != DDP_OK) {
                 (void)flush_deferred(c);
                 return st;

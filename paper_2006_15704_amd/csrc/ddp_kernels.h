@@ -60,15 +60,20 @@ struct Scale {       // y = use_mul ? s * mul : s / div
 // All segment launches cover the tiles [tile_base, tile_base + ntiles) of the
 // global tile numbering (tile0 / tile_seg).
 
-// K1: gradients -> flat replica slabs for all `nrep` replicas.  unused (may be
-// null): per-parameter flags, 1 = write zeros and do not read the gradient.
+// K1: gradients -> flat replica slabs for all `nrep` replicas.  local (may be
+// null = every replica used every parameter): participation flags
+// [segment][replica]; 0 = write zeros into that replica's slot and do not read
+// its tensor.
 hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
-                       int64_t slab_stride, int nrep, const uint8_t* unused, bool nt_store,
+                       int64_t slab_stride, int nrep, const uint8_t* local, bool nt_store,
                        hipStream_t s);
 
-// K3: averaged slab -> gradient tensors of replicas [0, nrep).
+// K3: averaged slab -> gradient tensors of replicas [0, nrep).  global_used (may
+// be null): per segment, 0 = no replica used the parameter; with keep_unused
+// such parameters are not written.
 hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
-                         const char* out_slab, int nrep, bool nt_store, hipStream_t s);
+                         const char* out_slab, int nrep, const uint8_t* global_used, bool keep_unused,
+                         bool nt_store, hipStream_t s);
 
 // K2 (staged): out[v] = scale(sum_r in_r[v]) over nvec 16-byte vectors;
 // in_r = in0 + r*stride.  unroll = vectors per thread (1, 2 or 4);
@@ -78,11 +83,16 @@ hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* 
                               hipStream_t s);
 
 // K2 (fused): gather R replicas through the segment table, reduce, scatter to
-// the gradient tensors of replicas [0, nwrite).  pair = blocks take two tiles
-// each (for large launches).
+// the gradient tensors of replicas [0, nwrite).  local / keep_unused as above
+// (a replica with flag 0 contributes +0 and is not read; a parameter nobody
+// used is skipped with keep_unused, else written as zeros).  pair = blocks
+// take two tiles each (for large launches).
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
-                               int R, int nwrite, const uint8_t* unused, Scale sc, int unroll,
-                               bool pair, bool nontemporal, hipStream_t s);
+                               int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
+                               int unroll, bool pair, bool nontemporal, hipStream_t s);
+
+// global[g] = OR_r local[g*R + r]  (the bitmap AllReduce of Section 4.2).
+hipError_t launch_bitmap_or(const uint8_t* local, uint8_t* global, int G, int R, hipStream_t s);
 
 // K4: grad[r][g] += micro[r*n + param[g]] for all segments and replicas
 // (null micro pointers are skipped).  ntiles = tile0[G].

@@ -214,7 +214,8 @@ __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __
 template <bool PACK, bool NTS>
 __global__ __launch_bounds__(BLOCK) void seg_copy_kernel(SegTables t, int64_t tile_base,
                                                          char* slab0, int64_t slab_stride,
-                                                         const uint8_t* __restrict__ unused) {
+                                                         const uint8_t* __restrict__ flags,
+                                                         int keep_unused) {
     const int64_t tile = tile_base + blockIdx.x;
     const int r = blockIdx.y;
     const int g = t.tile_seg[tile];
@@ -222,7 +223,12 @@ __global__ __launch_bounds__(BLOCK) void seg_copy_kernel(SegTables t, int64_t ti
     const int64_t numel = si.numel;
     const int64_t ltile = tile - si.tile0;
     char* grad = static_cast<char*>(t.grad[static_cast<int64_t>(g) * t.R + r]);
-    const bool zero = PACK && unused != nullptr && unused[si.param] != 0;
+    // PACK: flags = per (segment, replica) participation, 0 = the replica did
+    // not use the parameter: its slot gets zeros and its tensor is not read.
+    // UNPACK: flags = global bitmap per segment, 0 = no replica used the
+    // parameter: with keep_unused its gradients are left as they are.
+    const bool zero = PACK && flags != nullptr && flags[static_cast<int64_t>(g) * t.R + r] == 0;
+    if (!PACK && keep_unused && flags != nullptr && flags[g] == 0) return;
     const char* src;
     char* dst;
     if (PACK) {
@@ -385,17 +391,20 @@ __global__ __launch_bounds__(BLOCK) void flat_reduce_kernel(const char* __restri
 // and lanes are predicated.  The C pointers are fetched first (one scalar
 // load), then all C*U vector loads are issued, then the adds run in order.
 template <int DT, bool NT, int C, int U>
-__device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r,
+__device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r, uint64_t used,
                                           const int64_t (&off)[U], const bool (&ok)[U],
                                           float (&acc)[U][Fmt<DT>::VEC]) {
     const char* base[C];
 #pragma unroll
     for (int i = 0; i < C; ++i) base[i] = static_cast<const char*>(row[r + i]);
     u32x4 x[C][U];
+    // a replica that did not use the parameter contributes +0 in its place in
+    // the sum, and its tensor is not read
 #pragma unroll
     for (int i = 0; i < C; ++i)
 #pragma unroll
-        for (int u = 0; u < U; ++u) x[i][u] = ok[u] ? load16<NT>(base[i] + off[u]) : zero16();
+        for (int u = 0; u < U; ++u)
+            x[i][u] = (ok[u] && ((used >> (r + i)) & 1u)) ? load16<NT>(base[i] + off[u]) : zero16();
 #pragma unroll
     for (int i = 0; i < C; ++i)
 #pragma unroll
@@ -404,23 +413,36 @@ __device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r,
 
 template <int DT>
 __device__ __forceinline__ void reduce_element(const SegTables& t, int g, int R, int nwrite,
-                                               int64_t idx, bool zero, const Scale& sc) {
+                                               int64_t idx, bool zero, uint64_t used, const Scale& sc) {
     constexpr int ES = Fmt<DT>::ES;
     float y = 0.0f;
     if (!zero) {
         float s = -0.0f;
-        for (int r = 0; r < R; ++r)
-            s += Fmt<DT>::load1(static_cast<const char*>(t.grad[static_cast<int64_t>(g) * t.R + r]) + idx * ES);
+        for (int r = 0; r < R; ++r) {
+            float x = 0.0f;
+            if ((used >> r) & 1u)
+                x = Fmt<DT>::load1(static_cast<const char*>(t.grad[static_cast<int64_t>(g) * t.R + r]) + idx * ES);
+            s += x;
+        }
         y = apply_scale(sc, s);
     }
     for (int w = 0; w < nwrite; ++w)
         Fmt<DT>::store1(static_cast<char*>(t.grad[static_cast<int64_t>(g) * t.R + w]) + idx * ES, y);
 }
 
+// Block-uniform: the R participation bytes of a segment as a bit mask.
+__device__ __forceinline__ uint64_t used_mask(const uint8_t* __restrict__ flags, int R) {
+    uint64_t m = 0;
+    for (int r = 0; r < R; ++r)
+        if (flags[r] != 0) m |= uint64_t(1) << r;
+    return m;
+}
+
 // One tile of the fused gather-reduce-scatter.
 template <int DT, bool NT, int U>
 __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int R, int nwrite,
-                                           const uint8_t* __restrict__ unused, const Scale& sc) {
+                                           const uint8_t* __restrict__ local, int keep_unused,
+                                           const Scale& sc) {
     constexpr int ES = Fmt<DT>::ES;
     constexpr int VEC = Fmt<DT>::VEC;
     const int g = t.tile_seg[tile];
@@ -434,13 +456,19 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
     for (int i = 0; i < 8; ++i) pre[i] = static_cast<const char*>(row[i]);
     const int64_t numel = si.numel;
     const int64_t ltile = tile - si.tile0;
-    const bool zero = unused != nullptr && unused[si.param] != 0;
+    // participation of the R replicas in this parameter (bit r = replica r used
+    // it); without a flag table every replica did
+    const uint64_t everyone = R >= 64 ? ~uint64_t(0) : ((uint64_t(1) << R) - 1);
+    const uint64_t used = local != nullptr ? used_mask(local + static_cast<int64_t>(g) * t.R, R) : everyone;
+    if (used == 0 && keep_unused) return;   // globally unused: the gradients stay as they are
+    const bool zero = used == 0;            // ... or become zeros
+    const bool all_used = used == everyone;
     const int sh = si.lead_bytes() / ES;    // replica 0's tensor starts this many elements past a 16-byte boundary
     const bool fast = si.congruent();       // every replica's tensor sits at the same offset modulo 16
     const int64_t e_tile = ltile * (TILE_BYTES / ES) - sh;
 
-    if (fast && !zero && e_tile >= 0 && e_tile + TILE_BYTES / ES <= numel) {
-        // the whole tile is inside the segment and every replica is aligned alike
+    if (fast && all_used && e_tile >= 0 && e_tile + TILE_BYTES / ES <= numel) {
+        // the whole tile is inside the segment, every replica took part and all are aligned alike
         const int64_t tile_byte = e_tile * ES;
 #pragma unroll 1
         for (int step = 0; step < TILE_VECS / (BLOCK * U); ++step) {
@@ -479,10 +507,10 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
         }
         if (!zero && fast) {
             int r = 0;
-            for (; r + 8 <= R; r += 8) chunk_seg<DT, NT, 8, U>(row, r, off, ok, acc);
-            if (r + 4 <= R) { chunk_seg<DT, NT, 4, U>(row, r, off, ok, acc); r += 4; }
-            if (r + 2 <= R) { chunk_seg<DT, NT, 2, U>(row, r, off, ok, acc); r += 2; }
-            if (r < R) { chunk_seg<DT, NT, 1, U>(row, r, off, ok, acc); }
+            for (; r + 8 <= R; r += 8) chunk_seg<DT, NT, 8, U>(row, r, used, off, ok, acc);
+            if (r + 4 <= R) { chunk_seg<DT, NT, 4, U>(row, r, used, off, ok, acc); r += 4; }
+            if (r + 2 <= R) { chunk_seg<DT, NT, 2, U>(row, r, used, off, ok, acc); r += 2; }
+            if (r < R) { chunk_seg<DT, NT, 1, U>(row, r, used, off, ok, acc); }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -510,7 +538,7 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
             } else {
                 for (int i = 0; i < VEC; ++i) {
                     const int64_t idx = e[u] + i;
-                    if (idx >= 0 && idx < numel) reduce_element<DT>(t, g, R, nwrite, idx, zero, sc);
+                    if (idx >= 0 && idx < numel) reduce_element<DT>(t, g, R, nwrite, idx, zero, used, sc);
                 }
             }
         }
@@ -520,9 +548,9 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
 template <int DT, bool NT, int U>
 __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int64_t tile_base, int R,
                                                              int nwrite,
-                                                             const uint8_t* __restrict__ unused,
-                                                             Scale sc) {
-    fused_tile<DT, NT, U>(t, tile_base + blockIdx.x, R, nwrite, unused, sc);
+                                                             const uint8_t* __restrict__ local,
+                                                             int keep_unused, Scale sc) {
+    fused_tile<DT, NT, U>(t, tile_base + blockIdx.x, R, nwrite, local, keep_unused, sc);
 }
 
 // Large launches: a block takes two neighbouring tiles.  When both lie inside
@@ -531,8 +559,8 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int64_
 template <int DT, bool NT, int U>
 __global__ __launch_bounds__(BLOCK) void fused_reduce_pair_kernel(SegTables t, int64_t tile_base,
                                                                   int64_t tile_end, int R, int nwrite,
-                                                                  const uint8_t* __restrict__ unused,
-                                                                  Scale sc) {
+                                                                  const uint8_t* __restrict__ local,
+                                                                  int keep_unused, Scale sc) {
     constexpr int ES = Fmt<DT>::ES;
     constexpr int VEC = Fmt<DT>::VEC;
     constexpr int U2 = 2 * U;
@@ -549,8 +577,10 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_pair_kernel(SegTables t, i
             for (int i = 0; i < 8; ++i) pre[i] = static_cast<const char*>(row[i]);
             const int sh = si.lead_bytes() / ES;
             const int64_t e_tile = (tile_a - si.tile0) * (TILE_BYTES / ES) - sh;
-            const bool zero = unused != nullptr && unused[si.param] != 0;
-            if (si.congruent() && !zero && e_tile >= 0 && e_tile + 2 * (TILE_BYTES / ES) <= si.numel) {
+            const bool all_used =
+                local == nullptr ||
+                used_mask(local + static_cast<int64_t>(g) * t.R, R) == (R >= 64 ? ~uint64_t(0) : ((uint64_t(1) << R) - 1));
+            if (si.congruent() && all_used && e_tile >= 0 && e_tile + 2 * (TILE_BYTES / ES) <= si.numel) {
                 const int64_t tile_byte = e_tile * ES;
                 uint32_t lane_off[U2];
                 float acc[U2][VEC];
@@ -569,11 +599,11 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_pair_kernel(SegTables t, i
                 return;
             }
         }
-        fused_tile<DT, NT, U>(t, tile_a, R, nwrite, unused, sc);
-        fused_tile<DT, NT, U>(t, tile_b, R, nwrite, unused, sc);
+        fused_tile<DT, NT, U>(t, tile_a, R, nwrite, local, keep_unused, sc);
+        fused_tile<DT, NT, U>(t, tile_b, R, nwrite, local, keep_unused, sc);
         return;
     }
-    fused_tile<DT, NT, U>(t, tile_a, R, nwrite, unused, sc);
+    fused_tile<DT, NT, U>(t, tile_a, R, nwrite, local, keep_unused, sc);
 }
 
 // ---- K4: no_sync accumulation ---------------------------------------------
@@ -641,6 +671,18 @@ __global__ __launch_bounds__(BLOCK) void accumulate_kernel(SegTables t, int n,
     }
 }
 
+// ---- global participation bitmap ---------------------------------------------
+// The one-GPU form of the extra AllReduce on the unused-parameter bitmap
+// (Section 4.2): global[g] = OR over the R replicas of local[g][r].
+__global__ __launch_bounds__(BLOCK) void bitmap_or_kernel(const uint8_t* __restrict__ local,
+                                                          uint8_t* __restrict__ global, int G, int R) {
+    const int g = blockIdx.x * BLOCK + threadIdx.x;
+    if (g >= G) return;
+    uint8_t any = 0;
+    for (int r = 0; r < R; ++r) any |= local[static_cast<int64_t>(g) * R + r] != 0 ? 1 : 0;
+    global[g] = any;
+}
+
 // ---- K6: synthetic backward emitter -----------------------------------------
 // Every wave waits until `ticks` of the constant-rate wall clock have passed
 // (at most MAX_SPINS polls, so the kernel always ends), then replica
@@ -684,21 +726,23 @@ inline hipError_t after_launch() { return hipGetLastError(); }
 
 // ---- launch wrappers ---------------------------------------------------------
 hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
-                       int64_t slab_stride, int nrep, const uint8_t* unused, bool nt_store,
+                       int64_t slab_stride, int nrep, const uint8_t* local, bool nt_store,
                        hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
-    if (nt_store) hipLaunchKernelGGL((seg_copy_kernel<true, true>), grid, dim3(BLOCK), 0, s, t, tile_base, slab0, slab_stride, unused);
-    else hipLaunchKernelGGL((seg_copy_kernel<true, false>), grid, dim3(BLOCK), 0, s, t, tile_base, slab0, slab_stride, unused);
+    if (nt_store) hipLaunchKernelGGL((seg_copy_kernel<true, true>), grid, dim3(BLOCK), 0, s, t, tile_base, slab0, slab_stride, local, 0);
+    else hipLaunchKernelGGL((seg_copy_kernel<true, false>), grid, dim3(BLOCK), 0, s, t, tile_base, slab0, slab_stride, local, 0);
     return after_launch();
 }
 
 hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
-                         const char* out_slab, int nrep, bool nt_store, hipStream_t s) {
+                         const char* out_slab, int nrep, const uint8_t* global_used, bool keep_unused,
+                         bool nt_store, hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
-    if (nt_store) hipLaunchKernelGGL((seg_copy_kernel<false, true>), grid, dim3(BLOCK), 0, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), static_cast<const uint8_t*>(nullptr));
-    else hipLaunchKernelGGL((seg_copy_kernel<false, false>), grid, dim3(BLOCK), 0, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), static_cast<const uint8_t*>(nullptr));
+    const int keep = keep_unused ? 1 : 0;
+    if (nt_store) hipLaunchKernelGGL((seg_copy_kernel<false, true>), grid, dim3(BLOCK), 0, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), global_used, keep);
+    else hipLaunchKernelGGL((seg_copy_kernel<false, false>), grid, dim3(BLOCK), 0, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), global_used, keep);
     return after_launch();
 }
 
@@ -736,36 +780,37 @@ hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* 
 
 template <int DT, int U>
 static void fused_dispatch(bool nt, dim3 grid, hipStream_t s, const SegTables& t, int64_t tile_base,
-                           int R, int nwrite, const uint8_t* unused, Scale sc) {
-    if (nt) hipLaunchKernelGGL((fused_reduce_kernel<DT, true, U>), grid, dim3(BLOCK), 0, s, t, tile_base, R, nwrite, unused, sc);
-    else hipLaunchKernelGGL((fused_reduce_kernel<DT, false, U>), grid, dim3(BLOCK), 0, s, t, tile_base, R, nwrite, unused, sc);
+                           int R, int nwrite, const uint8_t* local, int keep, Scale sc) {
+    if (nt) hipLaunchKernelGGL((fused_reduce_kernel<DT, true, U>), grid, dim3(BLOCK), 0, s, t, tile_base, R, nwrite, local, keep, sc);
+    else hipLaunchKernelGGL((fused_reduce_kernel<DT, false, U>), grid, dim3(BLOCK), 0, s, t, tile_base, R, nwrite, local, keep, sc);
 }
 
 template <int DT>
 static void fused_unroll(int unroll, bool pair, bool nt, int64_t ntiles, hipStream_t s,
                          const SegTables& t, int64_t tile_base, int R, int nwrite,
-                         const uint8_t* unused, Scale sc) {
+                         const uint8_t* local, int keep, Scale sc) {
     constexpr int UMAX = TILE_VECS / BLOCK;      // a tile holds at most this many vectors per thread
     if (pair) {
         dim3 grid(static_cast<unsigned>((ntiles + 1) / 2));
-        if (nt) hipLaunchKernelGGL((fused_reduce_pair_kernel<DT, true, UMAX>), grid, dim3(BLOCK), 0, s, t, tile_base, tile_base + ntiles, R, nwrite, unused, sc);
-        else hipLaunchKernelGGL((fused_reduce_pair_kernel<DT, false, UMAX>), grid, dim3(BLOCK), 0, s, t, tile_base, tile_base + ntiles, R, nwrite, unused, sc);
+        if (nt) hipLaunchKernelGGL((fused_reduce_pair_kernel<DT, true, UMAX>), grid, dim3(BLOCK), 0, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc);
+        else hipLaunchKernelGGL((fused_reduce_pair_kernel<DT, false, UMAX>), grid, dim3(BLOCK), 0, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc);
         return;
     }
     dim3 grid(static_cast<unsigned>(ntiles));
-    if (unroll >= 4 && UMAX >= 4) fused_dispatch<DT, (UMAX >= 4 ? 4 : 1)>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
-    else if (unroll >= 2 && UMAX >= 2) fused_dispatch<DT, (UMAX >= 2 ? 2 : 1)>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
-    else fused_dispatch<DT, 1>(nt, grid, s, t, tile_base, R, nwrite, unused, sc);
+    if (unroll >= 4 && UMAX >= 4) fused_dispatch<DT, (UMAX >= 4 ? 4 : 1)>(nt, grid, s, t, tile_base, R, nwrite, local, keep, sc);
+    else if (unroll >= 2 && UMAX >= 2) fused_dispatch<DT, (UMAX >= 2 ? 2 : 1)>(nt, grid, s, t, tile_base, R, nwrite, local, keep, sc);
+    else fused_dispatch<DT, 1>(nt, grid, s, t, tile_base, R, nwrite, local, keep, sc);
 }
 
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
-                               int R, int nwrite, const uint8_t* unused, Scale sc, int unroll,
-                               bool pair, bool nontemporal, hipStream_t s) {
+                               int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
+                               int unroll, bool pair, bool nontemporal, hipStream_t s) {
     if (ntiles <= 0) return hipSuccess;
+    const int keep = keep_unused ? 1 : 0;
     switch (dtype) {
-        case 0: fused_unroll<0>(unroll, pair, nontemporal, ntiles, s, t, tile_base, R, nwrite, unused, sc); break;
-        case 1: fused_unroll<1>(unroll, pair, nontemporal, ntiles, s, t, tile_base, R, nwrite, unused, sc); break;
-        case 2: fused_unroll<2>(unroll, pair, nontemporal, ntiles, s, t, tile_base, R, nwrite, unused, sc); break;
+        case 0: fused_unroll<0>(unroll, pair, nontemporal, ntiles, s, t, tile_base, R, nwrite, local, keep, sc); break;
+        case 1: fused_unroll<1>(unroll, pair, nontemporal, ntiles, s, t, tile_base, R, nwrite, local, keep, sc); break;
+        case 2: fused_unroll<2>(unroll, pair, nontemporal, ntiles, s, t, tile_base, R, nwrite, local, keep, sc); break;
         default: return hipErrorInvalidValue;
     }
     return after_launch();
@@ -776,6 +821,12 @@ hipError_t launch_accumulate(const SegTables& t, int64_t ntiles, int R, int n, v
     if (ntiles <= 0 || R <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(R));
     hipLaunchKernelGGL(accumulate_kernel, grid, dim3(BLOCK), 0, s, t, n, micro);
+    return after_launch();
+}
+
+hipError_t launch_bitmap_or(const uint8_t* local, uint8_t* global, int G, int R, hipStream_t s) {
+    if (G <= 0) return hipSuccess;
+    hipLaunchKernelGGL(bitmap_or_kernel, dim3((G + BLOCK - 1) / BLOCK), dim3(BLOCK), 0, s, local, global, G, R);
     return after_launch();
 }
 

@@ -186,3 +186,44 @@ def test_bert_large_no_sync_r32_with_unmarked_parameters(pipeline):
     probe = [p for p in range(0, n, 37) if p not in unused_set]
     for p in probe:                          # everywhere: finite averages
         assert np.isfinite(grads.download(0, p)).all()
+
+
+def test_resnet50_partial_participation_r8():
+    """ResNet-50 shapes, R = 8, 25 MiB cap, launched as the benchmark does;
+    every (replica, parameter) pair takes part with probability 0.8, six
+    parameters are used by nobody (Section 4.2's globally unused parameters)
+    and keep their gradients.  Whole model compared with the oracle, both
+    pipelines, every replica written."""
+    d, harness = lib()
+    numel = workloads.numel_of(workloads.WORKLOAD_SHAPES["resnet50"]())
+    n, R, cap = len(numel), 8, 25 * MIB
+    rng = np.random.default_rng(21)
+    flag = (rng.random((R, n)) < 0.8).astype(np.uint8)
+    nobody = [0, 1, 57, 58, 100, n - 1]
+    flag[:, nobody] = 0
+    progress("participation: generating replicas")
+    reps = gen(6, numel, R, 1e-2, FP32)
+    for r in range(R):
+        for p in range(n):
+            if not flag[r, p]:
+                reps[r][p][:] = np.nan
+    marks = [(p, flag[:, p].tolist()) for p in range(n - 1, -1, -1)]
+    progress("participation: oracle")
+    want, asg, wlog, glob = oracle.synchronize_local(numel, [FP32] * n, cap, reps, marks, find_unused=True)
+    assert sorted(np.flatnonzero(glob == 0).tolist()) == sorted(nobody)
+    grads = harness.DeviceGrads(numel, [FP32] * n, R)
+    for pipeline in (STAGED, FUSED):
+        progress(f"participation: pipeline {pipeline}")
+        for r in range(R):
+            grads.upload_replica(r, reps[r])
+        with harness.Session(grads, cap, pipeline, True) as s:
+            d.ddp_set_option(s.ctx, d.DDP_OPT_FIND_UNUSED, 1)
+            for p, used in marks:
+                d.ddp_mark_ready_local(s.ctx, p, used)
+            d.ddp_finalize_backward(s.ctx)
+            d.ddp_synchronize(s.ctx)
+            assert d.ddp_get_launch_log(s.ctx, 1) == wlog
+            assert d.ddp_get_global_used(s.ctx, n).tolist() == glob.tolist()
+        for r in (0, 3, R - 1):
+            for p in range(n):
+                check_bits(grads.download(r, p), want[r][p], f"pipeline {pipeline} replica {r} parameter {p}")

@@ -168,6 +168,69 @@ def test_error_codes(d):
         d.ddp_destroy(ctx)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_participation_bitmap_host_logic_matches_oracle(d, seed):
+    """Per-replica ready marks on a plan-only context: launch log, used map and
+    the global bitmap (here the host's OR, no device involved) against the
+    oracle's, over two iterations so that the flags are seen to reset."""
+    rng = np.random.default_rng(1000 + seed)
+    n, R = int(rng.integers(1, 60)), int(rng.integers(1, 9))
+    numel = [int(x) for x in rng.integers(0, 3000, size=n)]
+    dtype = [int(x) for x in rng.integers(0, 3, size=n)]
+    cap = int(rng.choice([0, 1000, 8192]))
+    ctx = d.ddp_create(R, d.DDP_DEVICE_NONE)
+    try:
+        d.ddp_register_params(ctx, numel, dtype, None)
+        d.ddp_build_buckets(ctx, cap)
+        d.ddp_set_option(ctx, d.DDP_OPT_FIND_UNUSED, seed & 1)
+        for it in range(2):
+            order = [int(p) for p in rng.permutation(n)][: int(rng.integers(0, n + 1))]
+            marks = [(p, [int(x) for x in rng.integers(0, 2, size=R)]) for p in order]
+            grads = [[np.zeros(x, dtype=oracle.STORAGE[t]) for x, t in zip(numel, dtype)] for _ in range(R)]
+            _, asg, wlog, glob = oracle.synchronize_local(numel, dtype, cap, grads, marks)
+            for p, used in marks:
+                if all(used) and (p & 1):
+                    d.ddp_mark_ready(ctx, p)
+                else:
+                    d.ddp_mark_ready_local(ctx, p, used)
+            d.ddp_finalize_backward(ctx)
+            assert d.ddp_get_launch_log(ctx, 1) == wlog
+            assert d.ddp_get_global_used(ctx, n).tolist() == glob.tolist()
+            assert d.ddp_get_used_map(ctx, n, 1).tolist() == glob.tolist()
+    finally:
+        d.ddp_destroy(ctx)
+
+
+def test_participation_argument_errors(d):
+    ctx = d.ddp_create(3, d.DDP_DEVICE_NONE)
+    try:
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_mark_ready_local(ctx, 0, [1, 1, 1])
+        assert e.value.code == d.DDP_ERR_STATE
+        d.ddp_register_params(ctx, [4, 4], [0, 0], None)
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_get_global_used(ctx, 2)
+        assert e.value.code == d.DDP_ERR_STATE
+        d.ddp_build_buckets(ctx, 0)
+        with pytest.raises(ValueError):
+            d.ddp_mark_ready_local(ctx, 0, [1, 1])             # two flags for three replicas
+        raw = d.binding._lib.ddp_mark_ready_local
+        assert raw(ctx, 0, None) == d.DDP_ERR_ARG              # null flag array
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_mark_ready_local(ctx, 2, [1, 0, 1])
+        assert e.value.code == d.DDP_ERR_ARG
+        d.ddp_mark_ready_local(ctx, 1, [0, 0, 1])
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_mark_ready_local(ctx, 1, [1, 1, 1])
+        assert e.value.code == d.DDP_ERR_ALREADY_READY
+        d.ddp_finalize_backward(ctx)
+        assert d.ddp_get_global_used(ctx, 2).tolist() == [0, 1]
+        d.ddp_finalize_backward(ctx)                            # nothing marked at all
+        assert d.ddp_get_global_used(ctx, 2).tolist() == [0, 0]
+    finally:
+        d.ddp_destroy(ctx)
+
+
 def test_compute_context_without_gpu_fails_loudly(d):
     import torch
     if torch.cuda.is_available():
