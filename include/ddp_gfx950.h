@@ -95,6 +95,16 @@ typedef struct ddp_ctx ddp_ctx;
                                      knob.  1 = gradients of parameters that no replica used in the
                                      iteration (the global bitmap of Section 4.2 says so) are left
                                      exactly as they are; 0 (default) = they are written as zeros */
+#define DDP_OPT_REDUCE_STREAMS 12  /* between iterations: number of reduction streams, 1 (default) to 8.
+                                     The launches of an iteration take the streams in turn: the
+                                     caller's reduce_stream first, then streams the library creates
+                                     (default priority).  This is the one-GPU form of Section 3.3's
+                                     round-robin process groups (Section 5.4 measures rr1/rr3/rr5):
+                                     launches are still enqueued in bucket order, but buckets on
+                                     different streams may run at the same time.  Every stream waits
+                                     for backward_stream like reduce_stream does, and at finalize all
+                                     of them are joined into reduce_stream before the averaged
+                                     gradients are handed back.  Results are unchanged */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 

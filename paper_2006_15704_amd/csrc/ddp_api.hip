@@ -54,6 +54,7 @@ struct ddp_ctx {
                                                   // launch while it stays within this many bytes
     int64_t pair_min_bytes = int64_t(48) << 20;   // buckets at least this large use paired tiles
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
+    int32_t n_streams = 1;                        // reduction streams taken in turn by the launches
 
     bool registered = false, built = false;
     ddp::BucketPlan plan;
@@ -100,7 +101,17 @@ struct ddp_ctx {
     std::vector<uint8_t> used_running, used_closed;
     std::vector<TimedLaunch> timed;
     size_t open_group = static_cast<size_t>(-1);   // timing mode 2: the running iteration's entry
-    bool ordered_in_call = false;   // reduce stream already ordered after backward in this API call
+    // Reduction streams: lane 0 is the caller's reduce stream, lanes 1.. are created by the library
+    // (DDP_OPT_REDUCE_STREAMS).  The launches of an iteration take the lanes in turn.
+    static constexpr int kMaxLanes = 8;
+    hipStream_t lane[kMaxLanes] = {};
+    hipEvent_t ev_join[kMaxLanes] = {};           // lane's work of the iteration is done (waited for by lane 0)
+    hipEvent_t call_event = nullptr;              // backward-stream position of the running API call
+    bool lane_used[kMaxLanes] = {};               // lane received work in the running iteration
+    bool lane_ordered[kMaxLanes] = {};            // lane already waits for ev_call in the running API call
+    int64_t launches_in_iter = 0;
+    bool backward_idle_in_call = false;           // backward stream was found drained in this API call
+    bool ordered_in_call = false;   // backward stream position of this API call already examined
     std::vector<int32_t> deferred;  // buckets made launchable by the running API call, not yet enqueued
     std::string err;
 };
@@ -155,7 +166,16 @@ void drop_timed(ddp_ctx* c) {
     c->open_group = static_cast<size_t>(-1);
 }
 
-// Enqueue on the reduce stream everything buckets [first, last] need, as one
+// A new API call begins: whatever the caller enqueued on the backward stream
+// since the last call has to be ordered before the launches of this one.
+void new_call(ddp_ctx* c) {
+    c->ordered_in_call = false;
+    c->backward_idle_in_call = false;
+    c->call_event = nullptr;
+    for (bool& b : c->lane_ordered) b = false;
+}
+
+// Enqueue on a reduction stream everything buckets [first, last] need, as one
 // launch per kernel.  The buckets are consecutive, hold one element type, and
 // their tiles and slab ranges are contiguous.
 int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
@@ -168,6 +188,32 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
     int64_t bytes = 0;
     for (int32_t b = first; b <= last; ++b) bytes += static_cast<int64_t>(c->plan.buckets[b].bytes());
     const int32_t id = first + 65536 * (last - first);
+    // the launches of an iteration take the reduction streams in turn
+    const int lane = static_cast<int>(c->launches_in_iter++ % c->n_streams);
+    const hipStream_t st = c->lane[lane];
+    c->lane_used[lane] = true;
+    if (st != c->backward && !c->lane_ordered[lane]) {
+        // Order the buckets after the gradient-producing work enqueued so far.
+        // If the backward stream has already drained there is nothing to wait
+        // for, and the queue packets are saved.  Within one API call the caller
+        // cannot enqueue anything in between, so one look at the backward stream
+        // (and at most one event on it) serves every bucket the call launches;
+        // each reduction stream waits for that event once.
+        if (!c->ordered_in_call) {
+            const hipError_t q = hipStreamQuery(c->backward);
+            if (q == hipErrorNotReady) {
+                HIPCHK(c, hipEventRecord(c->ev_ready[first], c->backward));
+                c->call_event = c->ev_ready[first];
+            } else if (q == hipSuccess) {
+                c->backward_idle_in_call = true;
+            } else {
+                return fail(c, DDP_ERR_HIP, std::string("hipStreamQuery: ") + hipGetErrorString(q));
+            }
+            c->ordered_in_call = true;
+        }
+        if (!c->backward_idle_in_call) HIPCHK(c, hipStreamWaitEvent(st, c->call_event, 0));
+        c->lane_ordered[lane] = true;
+    }
     // Participation flags travel to the device only for launches that hold a
     // zero flag (a replica that did not use a parameter, or a parameter nobody
     // marked); everything else runs without a flag table.
@@ -184,27 +230,10 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
         const size_t off = static_cast<size_t>(seg_begin) * c->R;
         const size_t len = static_cast<size_t>(seg_end - seg_begin) * c->R;
         std::memcpy(c->h_local[par] + off, c->local_cur.data() + off, len);
-        HIPCHK(c, hipMemcpyAsync(c->d_local + off, c->h_local[par] + off, len, hipMemcpyHostToDevice, c->reduce));
-        HIPCHK(c, hipEventRecord(c->ev_local[par], c->reduce));
-        c->local_in_flight[par] = true;
+        // After the ordering above the stream is also behind the previous iteration's readers of
+        // the table; finalize records ev_local[par] once every stream of the iteration is joined.
+        HIPCHK(c, hipMemcpyAsync(c->d_local + off, c->h_local[par] + off, len, hipMemcpyHostToDevice, st));
         d_flags = c->d_local;
-    }
-    if (c->backward != c->reduce) {
-        // Order the buckets after the gradient-producing work enqueued so far.
-        // If the backward stream has already drained there is nothing to wait
-        // for, and the two queue packets are saved.  Within one API call the
-        // caller cannot enqueue anything in between, so one ordering point
-        // serves every bucket the call launches.
-        if (!c->ordered_in_call) {
-            const hipError_t q = hipStreamQuery(c->backward);
-            if (q == hipErrorNotReady) {
-                HIPCHK(c, hipEventRecord(c->ev_ready[first], c->backward));
-                HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_ready[first], 0));
-            } else if (q != hipSuccess) {
-                return fail(c, DDP_ERR_HIP, std::string("hipStreamQuery: ") + hipGetErrorString(q));
-            }
-            c->ordered_in_call = true;
-        }
     }
     const ddp::Scale sc = make_scale(c->R);
     size_t slot;
@@ -214,7 +243,7 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
         TimedLaunch t{DDP_K_ITERATION, 0, nullptr, nullptr};
         HIPCHK(c, hipEventCreateWithFlags(&t.start, kTimingEvent));
         HIPCHK(c, hipEventCreateWithFlags(&t.stop, kTimingEvent));
-        HIPCHK(c, hipEventRecord(t.start, c->reduce));
+        HIPCHK(c, hipEventRecord(t.start, st));
         c->timed.push_back(t);
         c->open_group = c->timed.size() - 1;
     }
@@ -224,21 +253,21 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
         char* out = c->slabs + static_cast<int64_t>(c->R) * c->slab_stride + c->bucket_slab_off[first];
         // the range of the slab from the first bucket's base to the last one's padded end
         const int64_t nvec = (c->bucket_slab_off[last] - c->bucket_slab_off[first]) / 16 + c->bucket_vecs[last];
-        if ((rc = timed_begin(c, DDP_K_PACK, id, c->reduce, &slot)) != DDP_OK) return rc;
+        if ((rc = timed_begin(c, DDP_K_PACK, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_pack(c->tables, tile_base, ntiles, c->slabs, c->slab_stride, c->R,
-                                   d_flags, c->copy_nt_store != 0, c->reduce));
-        if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
-        if ((rc = timed_begin(c, DDP_K_REDUCE, id, c->reduce, &slot)) != DDP_OK) return rc;
+                                   d_flags, c->copy_nt_store != 0, st));
+        if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
+        if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_flat_reduce(bf.dtype, in0, c->slab_stride, out, nvec, c->R, sc,
-                                          c->reduce_blocks, c->unroll, c->nontemporal != 0, c->reduce));
-        if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
+                                          c->reduce_blocks, c->unroll, c->nontemporal != 0, st));
+        if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     } else {
-        if ((rc = timed_begin(c, DDP_K_REDUCE, id, c->reduce, &slot)) != DDP_OK) return rc;
+        if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_fused_reduce(bf.dtype, c->tables, tile_base, ntiles, c->R,
                                            c->write_all ? c->R : 1, d_flags, c->find_unused != 0, sc,
                                            c->unroll, bytes >= c->pair_min_bytes, c->nontemporal != 0,
-                                           c->reduce));
-        if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
+                                           st));
+        if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     }
     return DDP_OK;
 }
@@ -305,6 +334,14 @@ void release_device(ddp_ctx* c) {
     if (c->reduce) (void)hipStreamSynchronize(c->reduce);
     if (c->backward) (void)hipStreamSynchronize(c->backward);
     if (!c->reduce || !c->backward) (void)hipStreamSynchronize(nullptr);
+    for (int l = 1; l < ddp_ctx::kMaxLanes; ++l) {
+        if (c->lane[l]) {
+            (void)hipStreamSynchronize(c->lane[l]);
+            (void)hipStreamDestroy(c->lane[l]);
+            c->lane[l] = nullptr;
+        }
+        if (c->ev_join[l]) { (void)hipEventDestroy(c->ev_join[l]); c->ev_join[l] = nullptr; }
+    }
     drop_timed(c);
     release_build(c);
     for (hipEvent_t* e : {&c->ev_done, &c->ev_micro, &c->ev_emit, &c->ev_local[0], &c->ev_local[1], &c->ev_global})
@@ -339,6 +376,7 @@ int32_t ddp_create(ddp_ctx** out, int32_t R, int32_t device, void* reduce_stream
     c->plan_only = device == DDP_DEVICE_NONE;
     c->reduce = static_cast<hipStream_t>(reduce_stream);
     c->backward = static_cast<hipStream_t>(backward_stream);
+    c->lane[0] = c->reduce;
     if (!c->plan_only) {
         int count = 0;
         hipError_t e = hipGetDeviceCount(&count);
@@ -402,6 +440,22 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             return DDP_OK;
         case DDP_OPT_FIND_UNUSED:
             c->find_unused = value != 0;
+            return DDP_OK;
+        case DDP_OPT_REDUCE_STREAMS:
+            if (value < 1 || value > ddp_ctx::kMaxLanes)
+                return fail(c, DDP_ERR_ARG, "number of reduction streams outside [1, 8]");
+            if (c->tracker.marks() != 0 || !c->log_running.empty())
+                return fail(c, DDP_ERR_STATE, "reduction streams can only change between iterations");
+            if (!c->plan_only) {
+                HIPCHK(c, hipSetDevice(c->device));
+                for (int l = 1; l < value; ++l) {
+                    if (c->lane[l]) continue;
+                    // default priority, and no implicit ordering with the legacy default stream
+                    HIPCHK(c, hipStreamCreateWithFlags(&c->lane[l], hipStreamNonBlocking));
+                    HIPCHK(c, hipEventCreateWithFlags(&c->ev_join[l], kOrderEvent));
+                }
+            }
+            c->n_streams = static_cast<int32_t>(value);
             return DDP_OK;
         case DDP_OPT_COALESCE:
             if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
@@ -647,7 +701,7 @@ static int32_t mark_one(ddp_ctx* c, int32_t param_id, const uint8_t* used) {
 int32_t ddp_mark_ready(ddp_ctx* c, int32_t param_id) {
     if (!c) return DDP_ERR_ARG;
     if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready before ddp_build_buckets");
-    c->ordered_in_call = false;
+    new_call(c);
     const int32_t st = mark_one(c, param_id, nullptr);
     if (st != DDP_OK) return st;
     return flush_deferred(c);
@@ -657,7 +711,7 @@ int32_t ddp_mark_ready_local(ddp_ctx* c, int32_t param_id, const uint8_t* used) 
     if (!c) return DDP_ERR_ARG;
     if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready_local before ddp_build_buckets");
     if (!used) return fail(c, DDP_ERR_ARG, "ddp_mark_ready_local: used is null");
-    c->ordered_in_call = false;
+    new_call(c);
     const int32_t st = mark_one(c, param_id, used);
     if (st != DDP_OK) return st;
     return flush_deferred(c);
@@ -666,7 +720,7 @@ int32_t ddp_mark_ready_local(ddp_ctx* c, int32_t param_id, const uint8_t* used) 
 int32_t ddp_mark_ready_many(ddp_ctx* c, const int32_t* ids, int32_t count) {
     if (!c || (count > 0 && !ids) || count < 0) return DDP_ERR_ARG;
     if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_mark_ready_many before ddp_build_buckets");
-    c->ordered_in_call = false;
+    new_call(c);
     for (int32_t k = 0; k < count; ++k) {
         const int32_t st = mark_one(c, ids[k], nullptr);
         if (st != DDP_OK) {
@@ -682,7 +736,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_finalize_backward before ddp_build_buckets");
     const int32_t n = static_cast<int32_t>(c->plan.params.size());
     const int32_t marks = c->tracker.marks();
-    c->ordered_in_call = false;
+    new_call(c);
     std::vector<int32_t> launch;
     c->tracker.drain(launch);
     if (!c->plan_only) HIPCHK(c, hipSetDevice(c->device));
@@ -704,6 +758,12 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
         if (st != DDP_OK) return st;
     }
     if (!c->plan_only) {
+        // every reduction stream that received work in this iteration joins the caller's
+        for (int l = 1; l < ddp_ctx::kMaxLanes; ++l)
+            if (c->lane_used[l]) {
+                HIPCHK(c, hipEventRecord(c->ev_join[l], c->lane[l]));
+                HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_join[l], 0));
+            }
         if (c->open_group != static_cast<size_t>(-1)) {      // closes this iteration's bucket launches
             HIPCHK(c, hipEventRecord(c->timed[c->open_group].stop, c->reduce));
             c->open_group = static_cast<size_t>(-1);
@@ -758,6 +818,8 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     std::fill(c->acc_used.begin(), c->acc_used.end(), 0);
     std::fill(c->bucket_zero.begin(), c->bucket_zero.end(), 0);
     c->iter_zero = false;
+    for (bool& b : c->lane_used) b = false;
+    c->launches_in_iter = 0;
     ++c->iteration;
     c->tracker.new_iteration();
     return DDP_OK;
@@ -783,6 +845,8 @@ int32_t ddp_synchronize(ddp_ctx* c) {
     if (c->plan_only) return fail(c, DDP_ERR_NO_DEVICE, "plan-only context has nothing to wait for");
     HIPCHK(c, hipSetDevice(c->device));
     HIPCHK(c, hipStreamSynchronize(c->backward));
+    for (int l = 1; l < ddp_ctx::kMaxLanes; ++l)
+        if (c->lane[l]) HIPCHK(c, hipStreamSynchronize(c->lane[l]));
     HIPCHK(c, hipStreamSynchronize(c->reduce));
     return DDP_OK;
 }
@@ -856,7 +920,7 @@ int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, cons
             return fail(c, DDP_ERR_ARG, "ddp_synth_backward: delay outside [0, 100 ms]");
     }
     HIPCHK(c, hipSetDevice(c->device));
-    c->ordered_in_call = false;
+    new_call(c);
     void** d_rows = nullptr;
     if (src_ptrs && count > 0) {
         const int64_t need = 2 * R * count;
@@ -890,7 +954,7 @@ int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, cons
             // buckets completed so far go out before more backward work is enqueued
             const int32_t stf = flush_deferred(c);
             if (stf != DDP_OK) return stf;
-            c->ordered_in_call = false;
+            new_call(c);
             HIPCHK(c, ddp::launch_emit(ticks, d_rows ? d_rows + 2 * R * k : nullptr, c->R,
                                        c->plan.params[p].numel, ddp::elem_size(c->plan.params[p].dtype),
                                        c->emit_busy_blocks,

@@ -396,3 +396,57 @@ def test_coalesced_launches_keep_order_results_and_cover_every_bucket(pipeline):
         assert len(ids) < len(asg.buckets)          # something was in fact coalesced
     for p in range(n):
         assert grads.download(0, p).tobytes() == want[p].tobytes(), f"parameter {p}"
+
+
+# ---- several reduction streams -----------------------------------------------------------------
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("streams", [2, 3, 8])
+def test_round_robin_reduction_streams_give_the_same_results(pipeline, streams):
+    """DDP_OPT_REDUCE_STREAMS (the one-GPU form of Section 3.3's round-robin
+    process groups): same launch log, same bits, for ready marks given one at
+    a time, with never-marked parameters, and with coalesced launches."""
+    d, _ = lib()
+    rng = np.random.default_rng(17)
+    n, R = 60, 4
+    numel = [int(x) for x in rng.integers(0, 6000, size=n)]
+    reps = gaussian_reps(17, numel, R, 1e-2)
+    order = [int(p) for p in rng.permutation(n)][: n - 5]
+    for extra in ((), ((d.DDP_OPT_COALESCE, 40000),), ((d.DDP_OPT_TIMING, 1),), ((d.DDP_OPT_TIMING, 2),)):
+        run_sync(numel, [FP32] * n, reps, 12000, pipeline, order=order, one_by_one=not extra,
+                 write_all=True, options=((d.DDP_OPT_REDUCE_STREAMS, streams),) + extra)
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+@pytest.mark.parametrize("same_stream", [False, True])
+def test_round_robin_streams_wait_for_the_backward_stream(pipeline, same_stream):
+    """Gradient memory starts as NaN and is written by the synthetic backward
+    stream after a delay; every reduction stream has to wait for it, over
+    several iterations enqueued without host synchronization in between."""
+    d, harness = lib()
+    numel = workloads.numel_of(workloads.tiny_shapes()) + [5000, 300, 4096, 77]
+    n, R, cap = len(numel), 3, 4096
+    grads = harness.DeviceGrads(numel, [FP32] * n, R, fill=0xFF)
+    srcs, wants = [], []
+    for it in range(3):
+        reps = [workloads.gaussian_replica(91 + it, r, 0, numel, 1.0) for r in range(R)]
+        src = harness.DeviceGrads(numel, [FP32] * n, R)
+        for r in range(R):
+            src.upload_replica(r, reps[r])
+        srcs.append(src)
+        wants.append(oracle.synchronize(numel, [FP32] * n, cap, reps)[0])
+    keep = harness.DeviceGrads(numel, [FP32] * n, 3, fill=0)       # copies of each iteration's result
+    import torch
+    with harness.Session(grads, cap, pipeline, same_stream=same_stream) as s:
+        d.ddp_set_option(s.ctx, d.DDP_OPT_REDUCE_STREAMS, 4)
+        order = list(range(n - 1, -1, -1))
+        for it in range(3):
+            d.ddp_synth_backward(s.ctx, order, [100_000] * n, srcs[it].ptrs(), True)
+            d.ddp_finalize_backward(s.ctx)
+            # work enqueued on the backward stream after finalize sees the averaged gradients
+            with torch.cuda.stream(s.backward_stream):
+                keep.bufs[it].copy_(grads.bufs[0], non_blocking=True)
+        d.ddp_synchronize(s.ctx)
+        torch.cuda.synchronize()
+        for it in range(3):
+            for i in range(n):
+                assert keep.download(it, i).tobytes() == wants[it][i].tobytes(), f"iteration {it} parameter {i}"

@@ -277,3 +277,36 @@ def test_no_sync_participation_accumulates_into_the_bitmap(pipeline, find_unused
         d.ddp_finalize_backward(s.ctx)
         d.ddp_synchronize(s.ctx)
         assert d.ddp_get_global_used(s.ctx, n).tolist() == [0] * n
+
+
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_participation_with_several_reduction_streams(pipeline):
+    """Flag tables travel on whichever stream launches the bucket; four
+    iterations with different masks are enqueued with no host synchronization
+    between them (only the result of the last one can be checked then, plus
+    the bitmap of each)."""
+    d, harness = lib()
+    n, R, cap = 40, 4, 9000
+    numel, dtypes, reps, _, _, _ = random_case(80, n, R, FP32, 6000, n_unmarked=0, n_nobody=0)
+    reps = [[workloads.gaussian_grad(80, r, 0, p, numel[p], 1e-2, FP32) for p in range(n)] for r in range(R)]
+    grads = harness.DeviceGrads(numel, dtypes, R)
+    for r in range(R):
+        grads.upload_replica(r, reps[r])
+    state = [[x.copy() for x in row] for row in reps]
+    with harness.Session(grads, cap, pipeline, True) as s:
+        d.ddp_set_option(s.ctx, d.DDP_OPT_REDUCE_STREAMS, 3)
+        d.ddp_set_option(s.ctx, d.DDP_OPT_FIND_UNUSED, 1)
+        for it in range(4):
+            rng = np.random.default_rng(81 + it)
+            order = [int(p) for p in rng.permutation(n)][: n - 3]
+            marks = [(p, [int(rng.random() < 0.6) for _ in range(R)]) for p in order]
+            state, _, wlog, glob = oracle.synchronize_local(numel, dtypes, cap, state, marks, find_unused=True)
+            for p, used in marks:
+                d.ddp_mark_ready_local(s.ctx, p, used)
+            d.ddp_finalize_backward(s.ctx)
+            assert d.ddp_get_launch_log(s.ctx, 1) == wlog
+            assert d.ddp_get_global_used(s.ctx, n).tolist() == glob.tolist()
+        d.ddp_synchronize(s.ctx)
+        for r in range(R):
+            for p in range(n):
+                assert grads.download(r, p).tobytes() == state[r][p].tobytes(), f"r{r} p{p}"

@@ -231,6 +231,25 @@ def test_participation_argument_errors(d):
         d.ddp_destroy(ctx)
 
 
+def test_reduction_stream_option_is_validated(d):
+    ctx, _ = plan(d, [4, 4, 4], [0, 0, 0], 0)
+    try:
+        for bad in (0, -1, 9):
+            with pytest.raises(d.DdpError) as e:
+                d.ddp_set_option(ctx, d.DDP_OPT_REDUCE_STREAMS, bad)
+            assert e.value.code == d.DDP_ERR_ARG
+        d.ddp_set_option(ctx, d.DDP_OPT_REDUCE_STREAMS, 8)
+        d.ddp_mark_ready(ctx, 2)
+        with pytest.raises(d.DdpError) as e:                 # not in the middle of an iteration
+            d.ddp_set_option(ctx, d.DDP_OPT_REDUCE_STREAMS, 2)
+        assert e.value.code == d.DDP_ERR_STATE
+        d.ddp_finalize_backward(ctx)
+        d.ddp_set_option(ctx, d.DDP_OPT_REDUCE_STREAMS, 2)
+        assert d.ddp_get_launch_log(ctx, 1) == [(0, 0), (1, 1), (2, 1)]
+    finally:
+        d.ddp_destroy(ctx)
+
+
 def test_compute_context_without_gpu_fails_loudly(d):
     import torch
     if torch.cuda.is_available():
