@@ -81,6 +81,8 @@ def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup
         if args.coalesce_mib is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE,
                                (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * (1 << 20)))
+        if args.streams is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_STREAMS, args.streams)
         if args.pair_min_mib is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_PAIR_MIN_BYTES, int(args.pair_min_mib * (1 << 20)))
 
@@ -127,6 +129,8 @@ def main() -> int:
                     help="skip the extra measurement of the staged pipeline's kernels")
     ap.add_argument("--no-coalesce-leg", action="store_true",
                     help="skip the extra measurement with coalesced launches")
+    ap.add_argument("--no-streams-leg", action="store_true",
+                    help="skip the extra measurement with two reduction streams")
     ap.add_argument("--no-accumulate-leg", action="store_true",
                     help="skip the extra measurement of the no_sync accumulation kernel")
     ap.add_argument("--reduce-blocks", type=int, default=None)
@@ -137,6 +141,8 @@ def main() -> int:
     ap.add_argument("--coalesce-mib", type=float, default=None,
                     help="buckets completed by one call share a launch up to this many MiB "
                          "(DDP_OPT_COALESCE; negative = no limit)")
+    ap.add_argument("--streams", type=int, default=None,
+                    help="reduction streams taken in turn by the bucket launches (DDP_OPT_REDUCE_STREAMS)")
     ap.add_argument("--copy-nt-store", action="store_true",
                     help="staged pipeline: pack/unpack store with the non-temporal hint")
     ap.add_argument("--same-stream", action="store_true",
@@ -292,6 +298,22 @@ def main() -> int:
             "launches_per_step": int(co_launches.sum()) // args.steps,
             "reduce_gbps": round((R + 1) * B * len(co_ms) / float(co_ms.sum()) / 1e6, 1),
             "frac_of_hbm_peak": round((R + 1) * B * len(co_ms) / float(co_ms.sum()) / 1e6 / HBM_PEAK_GBPS, 4),
+        }
+
+    if args.pipeline == "fused" and args.streams is None and not args.no_streams_leg:
+        # the same steps with the bucket launches alternating between two reduction streams
+        # (DDP_OPT_REDUCE_STREAMS): neighbouring buckets overlap, so only the iteration as a
+        # whole has a duration
+        args.streams = 2
+        rr = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
+        args.streams = None
+        rr_ms, _ = rr["iteration"]
+        out["two_streams"] = {
+            "ms_per_step": round(rr["ms_per_step"], 4),
+            "value_gbps": round((R + W) * B / rr["ms_per_step"] / 1e6, 1),
+            "reduce_gbps": round((R + 1) * B * len(rr_ms) / float(rr_ms.sum()) / 1e6, 1),
+            "frac_of_hbm_peak": round((R + 1) * B * len(rr_ms) / float(rr_ms.sum()) / 1e6 / HBM_PEAK_GBPS, 4),
+            "note": "(R+1)*B per iteration / time from the first launch to the join of both streams",
         }
 
     if not args.no_accumulate_leg:

@@ -21,6 +21,7 @@ one JSON object per line.  Run:  python -m paper_2006_15704_amd.sweep
 from __future__ import annotations
 
 import argparse
+import itertools
 import json
 import os
 import statistics
@@ -66,6 +67,10 @@ def main() -> int:
     ap.add_argument("--busy-blocks", type=int, default=0,
                     help="delay kernels use this many thread blocks doing arithmetic instead of "
                          "one sleeping block")
+    ap.add_argument("--streams", default="1",
+                    help="comma list: numbers of reduction streams (DDP_OPT_REDUCE_STREAMS)")
+    ap.add_argument("--coalesce-mib", type=float, default=0,
+                    help="DDP_OPT_COALESCE in MiB (0 = off, negative = no limit)")
     ap.add_argument("--produce", action="store_true",
                     help="the synthetic backward also writes every gradient (copies it from a "
                          "source buffer after the delay), which keeps the memory system busy "
@@ -94,13 +99,18 @@ def main() -> int:
     caps = [int(x) for x in args.caps_mib.split(",")]
     delays = [int(x) for x in args.delays_us.split(",")]
 
-    for pipe in args.pipelines.split(","):
+    stream_counts = [int(x) for x in args.streams.split(",")]
+    for pipe, n_streams in itertools.product(args.pipelines.split(","), stream_counts):
         code = lib.DDP_PIPELINE_FUSED if pipe == "fused" else lib.DDP_PIPELINE_STAGED
         for cap_mib in caps:
             cap = lib.DDP_CAP_WHOLE_MODEL if cap_mib < 0 else cap_mib * MIB
             with harness.Session(grads, cap, code) as s:
                 ctx = s.ctx
                 lib.ddp_set_option(ctx, lib.DDP_OPT_EMIT_BUSY_BLOCKS, args.busy_blocks)
+                lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_STREAMS, n_streams)
+                if args.coalesce_mib:
+                    lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE,
+                                       (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * MIB))
 
                 def sync():
                     lib.ddp_synchronize(ctx)
@@ -127,7 +137,8 @@ def main() -> int:
                     exposed = t_tot - t_bwd
                     print(json.dumps({
                         "workload": args.workload, "dtype": args.dtype, "R": R, "pipeline": pipe,
-                        "cap_mib": cap_mib, "n_buckets": s.n_buckets, "delay_us_per_param": d_us,
+                        "cap_mib": cap_mib, "n_buckets": s.n_buckets, "streams": n_streams,
+                        "coalesce_mib": args.coalesce_mib, "delay_us_per_param": d_us,
                         "backward_writes_gradients": bool(src_ptrs), "busy_blocks": args.busy_blocks,
                         "t_backward_ms": round(t_bwd, 4), "t_sync_ms": round(t_sync, 4),
                         "t_total_ms": round(t_tot, 4), "exposed_ms": round(exposed, 4),
