@@ -27,6 +27,9 @@ Data Parallel Training", arXiv 2006.15704):
     whether a parameter's gradients are written at all.
   * Section 3.2.4: under no_sync, gradients of several backward passes
     accumulate into the same tensor and are synchronized once afterwards.
+  * Section 6.2.1 (gradient order prediction): the backward order seen by
+    the hooks is traced and the parameter-to-bucket mapping is rebuilt to
+    follow it (`traced_visit_order`, `assign_buckets_in_order`).
 
 The method is an exact reorganisation of the plain definition
 
@@ -45,7 +48,10 @@ greedy-partition brute force, unique-tag round trips, integer-valued inputs
 against exact integer arithmetic, the float64 definition within the textbook
 summation bound, exhaustive 16-bit conversion checks against library
 conversions, the tiny linear-regression mean-gradient identity, the no_sync
-identity and hand-worked launch schedules.
+identity and hand-worked launch schedules; for the traced-order mapping the
+reduction to the pinned default assignment, a hand-worked example, partition
+invariants, the earliest-possible-launch property and a brute-force search
+over small cases.
 
 Not pinned by anything in the paper: absolute timings and the best bucket
 size (the paper's curves are figures that are not available) -- "parity
@@ -155,6 +161,64 @@ def assign_buckets(numel: Sequence[int], dtype: Sequence[int],
 
 
 # --------------------------------------------------------------------------
+# bucket assignment from a traced backward order  (Section 6.2.1)
+# --------------------------------------------------------------------------
+def traced_visit_order(ready_sequence: Sequence[int], n: int) -> List[int]:
+    """The order in which a rebuilt mapping visits the parameters: first the
+    parameters of the traced iteration in the order their gradients became
+    ready, then the ones the trace never saw, in reverse registration order
+    (the default guess of Algorithm 1 for everything without evidence)."""
+    order: List[int] = []
+    seen = set()
+    for p in ready_sequence:
+        p = int(p)
+        if p < 0 or p >= n:
+            raise ValueError(f"parameter id {p} out of range")
+        if p in seen:
+            raise ValueError(f"parameter {p} appears twice in the trace")
+        seen.add(p)
+        order.append(p)
+    for i in range(n - 1, -1, -1):
+        if i not in seen:
+            order.append(i)
+    return order
+
+
+def assign_buckets_in_order(numel: Sequence[int], dtype: Sequence[int], cap_bytes: int,
+                            visit_order: Sequence[int]) -> Assignment:
+    """Section 6.2.1: the parameter-to-bucket mapping is updated to follow a
+    traced backward order.  The allocation rule is Algorithm 1's, only the
+    visiting order changes from n-1, ..., 0 to `visit_order` (a permutation
+    of the parameter indices): the open bucket is closed before a parameter
+    that would push it past cap_bytes or that has another element type; a
+    total equal to the cap fits; buckets are numbered as they are opened;
+    offsets are dense and counted in elements."""
+    n = len(numel)
+    if n != len(dtype):
+        raise ValueError("numel and dtype differ in length")
+    if sorted(int(i) for i in visit_order) != list(range(n)):
+        raise ValueError("visit_order is not a permutation of the parameters")
+    bucket_of = np.full(n, -1, dtype=np.int32)
+    offset_of = np.zeros(n, dtype=np.int64)
+    buckets: List[Bucket] = []
+    for i in (int(v) for v in visit_order):
+        size = int(numel[i]) * ESIZE[int(dtype[i])]
+        start_new = (not buckets
+                     or buckets[-1].dtype != int(dtype[i])
+                     or buckets[-1].nbytes + size > cap_bytes)
+        if start_new:
+            buckets.append(Bucket(dtype=int(dtype[i])))
+        bk = buckets[-1]
+        bucket_of[i] = len(buckets) - 1
+        offset_of[i] = bk.elems
+        bk.params.append(i)
+        bk.elems += int(numel[i])
+    return Assignment(bucket_of, offset_of, buckets,
+                      np.asarray(numel, dtype=np.int64),
+                      np.asarray(dtype, dtype=np.int32))
+
+
+# --------------------------------------------------------------------------
 # pack / reduce / unpack
 # --------------------------------------------------------------------------
 def pack_bucket(asg: Assignment, b: int, grads: Sequence[np.ndarray],
@@ -257,16 +321,19 @@ def launch_schedule(asg: Assignment,
 # --------------------------------------------------------------------------
 def synchronize(numel: Sequence[int], dtype: Sequence[int], cap_bytes: int,
                 replica_grads: Sequence[Sequence[np.ndarray]],
-                ready_sequence: Optional[Sequence[int]] = None):
+                ready_sequence: Optional[Sequence[int]] = None,
+                visit_order: Optional[Sequence[int]] = None):
     """One synchronization: assign, then per bucket in launch order pack the
     R replica copies, reduce and average, and unpack.  `replica_grads[r][i]`
     is replica r's gradient of parameter i.  Parameters missing from
     `ready_sequence` (default: all are marked, in reverse registration
-    order) are reduced as zeros and are not read.
+    order) are reduced as zeros and are not read.  With `visit_order` the
+    buckets are the ones rebuilt from a traced order (Section 6.2.1).
     Returns (outs, assignment, launch_log)."""
     n = len(numel)
     R = len(replica_grads)
-    asg = assign_buckets(numel, dtype, cap_bytes)
+    asg = (assign_buckets(numel, dtype, cap_bytes) if visit_order is None
+           else assign_buckets_in_order(numel, dtype, cap_bytes, visit_order))
     if ready_sequence is None:
         ready_sequence = list(range(n - 1, -1, -1))
     marked = set(int(p) for p in ready_sequence)
@@ -298,7 +365,8 @@ def synchronize_local(numel: Sequence[int], dtype: Sequence[int], cap_bytes: int
                       replica_grads: Sequence[Sequence[np.ndarray]],
                       marks: Sequence[Tuple[int, Sequence[int]]],
                       find_unused: bool = True,
-                      prior_used: Optional[np.ndarray] = None):
+                      prior_used: Optional[np.ndarray] = None,
+                      visit_order: Optional[Sequence[int]] = None):
     """One synchronization in which every replica has its own set of used
     parameters.  `marks` is the sequence of ready marks, each (parameter,
     used[R]); `prior_used[r][i]` (optional) carries participation recorded by
@@ -311,7 +379,8 @@ def synchronize_local(numel: Sequence[int], dtype: Sequence[int], cap_bytes: int
     Returns (outs[R][n] -- every replica's view of its gradient tensors after
     the synchronization --, assignment, launch_log, global_used)."""
     n, R = len(numel), len(replica_grads)
-    asg = assign_buckets(numel, dtype, cap_bytes)
+    asg = (assign_buckets(numel, dtype, cap_bytes) if visit_order is None
+           else assign_buckets_in_order(numel, dtype, cap_bytes, visit_order))
     local = np.zeros((R, n), dtype=np.uint8) if prior_used is None else (np.asarray(prior_used) != 0).astype(np.uint8)
     order = []
     for p, used in marks:
