@@ -165,6 +165,8 @@ def main() -> int:
 
     import torch
     import workloads
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # a fresh checkout has no library yet
     import paper_2006_15704_amd as lib
     from paper_2006_15704_amd import harness
 

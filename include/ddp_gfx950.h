@@ -167,6 +167,27 @@ int32_t ddp_register_params(ddp_ctx* ctx, int32_t n, const int64_t* numel,
  * twice -> DDP_ERR_STATE; allocation failure -> DDP_ERR_HIP. */
 int32_t ddp_build_buckets(ddp_ctx* ctx, uint64_t cap_bytes);
 
+/* Section 6.2.1 (gradient order prediction): rebuilds the parameter-to-bucket
+ * mapping so that it follows the traced backward order.  The parameters are
+ * visited in the order of the ready marks of the iteration closed by the latest
+ * ddp_finalize_backward (ddp_get_ready_order(ctx, 1, ...)), followed by the
+ * parameters that iteration never marked in reverse registration order; the
+ * allocation rule is that of ddp_build_buckets (with an empty trace the result
+ * is the default mapping).  Only between iterations: any ready mark since the
+ * last finalize, or a ddp_no_sync_accumulate not yet followed by a
+ * synchronization -> DDP_ERR_STATE.  The call waits for both streams, frees and
+ * rebuilds the library's tables and flat buffers (the paper calls this
+ * re-allocation costly and to be done rarely), and clears the closed launch log
+ * and the kernel times; gradient memory is untouched.  Returns the new number
+ * of buckets, or a negative error; after a DDP_ERR_HIP the context has no
+ * buckets (as before ddp_build_buckets). */
+int32_t ddp_rebuild_buckets(ddp_ctx* ctx, uint64_t cap_bytes);
+
+/* The trace: ids[0..*n) = parameters in the order of their ready marks in the
+ * running (which = 0) or the latest closed (which = 1) iteration.  At most cap
+ * ids are written; *n is always the full count. */
+int32_t ddp_get_ready_order(const ddp_ctx* ctx, int32_t which, int32_t* ids, int32_t cap, int32_t* n);
+
 /* bucket_of[n], elem_offset[n] (host, caller-allocated): bucket index and
  * element offset inside the bucket for every parameter. */
 int32_t ddp_get_assignment(const ddp_ctx* ctx, int32_t* bucket_of, int64_t* elem_offset);

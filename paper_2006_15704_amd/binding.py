@@ -42,7 +42,8 @@ DDP_K_PACK, DDP_K_REDUCE, DDP_K_UNPACK, DDP_K_ACCUMULATE, DDP_K_ITERATION = 0, 1
 
 EXPORTS = [
     "ddp_version", "ddp_last_error", "ddp_create", "ddp_destroy", "ddp_set_option",
-    "ddp_register_params", "ddp_build_buckets", "ddp_get_assignment",
+    "ddp_register_params", "ddp_build_buckets", "ddp_rebuild_buckets", "ddp_get_ready_order",
+    "ddp_get_assignment",
     "ddp_get_bucket_info", "ddp_get_bucket_ptr", "ddp_mark_ready", "ddp_mark_ready_local",
     "ddp_get_global_used",
     "ddp_mark_ready_many", "ddp_finalize_backward", "ddp_synchronize",
@@ -59,7 +60,7 @@ class DdpError(RuntimeError):
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
-        f"{LIB_PATH} is missing: build it with `python -m paper_2006_15704_amd.build` "
+        f"{LIB_PATH} is missing: build it with `python paper_2006_15704_amd/build.py` "
         "(there is no fallback implementation)")
 
 _lib = C.CDLL(LIB_PATH)
@@ -73,6 +74,8 @@ _lib.ddp_destroy.argtypes = [_vp]
 _lib.ddp_set_option.argtypes = [_vp, _i32, _i64]
 _lib.ddp_register_params.argtypes = [_vp, _i32, C.POINTER(_i64), C.POINTER(_i32), C.POINTER(_vp)]
 _lib.ddp_build_buckets.argtypes = [_vp, _u64]
+_lib.ddp_rebuild_buckets.argtypes = [_vp, _u64]
+_lib.ddp_get_ready_order.argtypes = [_vp, _i32, C.POINTER(_i32), _i32, C.POINTER(_i32)]
 _lib.ddp_get_assignment.argtypes = [_vp, C.POINTER(_i32), C.POINTER(_i64)]
 _lib.ddp_get_bucket_info.argtypes = [_vp, _i32, C.POINTER(_i64), C.POINTER(_i32), C.POINTER(_i32)]
 _lib.ddp_get_bucket_ptr.argtypes = [_vp, _i32, _i32, C.POINTER(_vp)]
@@ -211,6 +214,20 @@ def ddp_finalize_backward(ctx) -> None:
 
 def ddp_synchronize(ctx) -> None:
     _check(ctx, _lib.ddp_synchronize(ctx))
+
+
+def ddp_rebuild_buckets(ctx, cap_bytes: int) -> int:
+    """New number of buckets; the mapping follows the closed iteration's ready order."""
+    return _check(ctx, _lib.ddp_rebuild_buckets(ctx, cap_bytes))
+
+
+def ddp_get_ready_order(ctx, which: int = 1):
+    """Parameters in the order of their ready marks: running (0) or last closed (1) iteration."""
+    n = _i32()
+    _check(ctx, _lib.ddp_get_ready_order(ctx, which, None, 0, C.byref(n)))
+    ids = np.zeros(max(n.value, 1), dtype=np.int32)
+    _check(ctx, _lib.ddp_get_ready_order(ctx, which, _as(ids, _i32), n.value, C.byref(n)))
+    return [int(x) for x in ids[: n.value]]
 
 
 def ddp_get_launch_log(ctx, which: int = 1):

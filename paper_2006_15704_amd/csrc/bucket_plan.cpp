@@ -2,11 +2,20 @@
 
 namespace ddp {
 
-void BucketPlan::assign(uint64_t cap_bytes) {
-    buckets.clear();
+bool BucketPlan::assign(uint64_t cap_bytes, const std::vector<int32_t>* order) {
     const int n = (int)params.size();
+    if (order) {
+        if ((int)order->size() != n) return false;
+        std::vector<uint8_t> seen(n, 0);
+        for (int32_t i : *order) {
+            if (i < 0 || i >= n || seen[i]) return false;
+            seen[i] = 1;
+        }
+    }
+    buckets.clear();
     bool open = false;
-    for (int i = n - 1; i >= 0; --i) {
+    for (int k = 0; k < n; ++k) {
+        const int i = order ? (*order)[k] : n - 1 - k;
         ParamInfo& p = params[i];
         const uint64_t size = (uint64_t)p.numel * (uint64_t)elem_size(p.dtype);
         if (open) {
@@ -31,6 +40,7 @@ void BucketPlan::assign(uint64_t cap_bytes) {
         b.seg_begin = seg;
         for (int32_t i : b.params) params[i].segment = seg++;
     }
+    return true;
 }
 
 void ReadyTracker::reset(const BucketPlan& plan) {

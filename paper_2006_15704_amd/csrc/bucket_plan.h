@@ -24,7 +24,7 @@ struct ParamInfo {
 };
 
 struct BucketInfo {
-    std::vector<int32_t> params;   // fill order: descending registration index
+    std::vector<int32_t> params;   // fill order (default: descending registration index)
     int64_t elems = 0;
     int32_t dtype = 0;
     int32_t seg_begin = 0;         // first global segment index
@@ -35,7 +35,10 @@ struct BucketPlan {
     std::vector<ParamInfo> params;
     std::vector<BucketInfo> buckets;
     // Fills bucket / offset / segment of every parameter and the bucket list.
-    void assign(uint64_t cap_bytes);
+    // Parameters are visited in `order` (a permutation of the indices; Section
+    // 6.2.1: a traced backward order) or, without one, in reverse registration
+    // order (Algorithm 1).  Returns false if `order` is not a permutation.
+    bool assign(uint64_t cap_bytes, const std::vector<int32_t>* order = nullptr);
 };
 
 // Pending counts and in-order launch.  launch decisions are returned to the

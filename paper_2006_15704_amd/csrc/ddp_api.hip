@@ -98,6 +98,7 @@ struct ddp_ctx {
     bool micro_in_flight = false, emit_in_flight = false;
 
     std::vector<std::pair<int32_t, int32_t>> log_running, log_closed;
+    std::vector<int32_t> order_running, order_closed;   // ready marks in the order they came (the trace)
     std::vector<uint8_t> used_running, used_closed;
     std::vector<TimedLaunch> timed;
     size_t open_group = static_cast<size_t>(-1);   // timing mode 2: the running iteration's entry
@@ -514,11 +515,11 @@ int32_t ddp_register_params(ddp_ctx* c, int32_t n, const int64_t* numel, const i
     return DDP_OK;
 }
 
-int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
-    if (!c) return DDP_ERR_ARG;
-    if (!c->registered) return fail(c, DDP_ERR_STATE, "ddp_build_buckets before ddp_register_params");
-    if (c->built) return fail(c, DDP_ERR_STATE, "ddp_build_buckets called twice");
-    c->plan.assign(cap_bytes);
+// Assigns the buckets (visiting the parameters in `order`, or in reverse
+// registration order without one) and builds everything that depends on the
+// assignment: tracker, flag tables, slabs, segment tables, events.
+static int32_t build_internal(ddp_ctx* c, uint64_t cap_bytes, const std::vector<int32_t>* order) {
+    if (!c->plan.assign(cap_bytes, order)) return fail(c, DDP_ERR_ARG, "visit order is not a permutation");
     c->tracker.reset(c->plan);
     const int32_t n = static_cast<int32_t>(c->plan.params.size());
     const int32_t nb = static_cast<int32_t>(c->plan.buckets.size());
@@ -635,6 +636,67 @@ int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
     return nb;
 }
 
+int32_t ddp_build_buckets(ddp_ctx* c, uint64_t cap_bytes) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->registered) return fail(c, DDP_ERR_STATE, "ddp_build_buckets before ddp_register_params");
+    if (c->built) return fail(c, DDP_ERR_STATE, "ddp_build_buckets called twice");
+    return build_internal(c, cap_bytes, nullptr);
+}
+
+int32_t ddp_rebuild_buckets(ddp_ctx* c, uint64_t cap_bytes) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_rebuild_buckets before ddp_build_buckets");
+    if (c->tracker.marks() != 0 || !c->deferred.empty())
+        return fail(c, DDP_ERR_STATE, "ddp_rebuild_buckets in the middle of an iteration");
+    for (uint8_t u : c->acc_used)
+        if (u) return fail(c, DDP_ERR_STATE, "ddp_rebuild_buckets between a no_sync accumulation and its synchronization");
+    const int32_t n = static_cast<int32_t>(c->plan.params.size());
+    // visit order: the trace of the closed iteration, then what it never saw in
+    // reverse registration order
+    std::vector<int32_t> order = c->order_closed;
+    {
+        std::vector<uint8_t> seen(n, 0);
+        for (int32_t p : order) seen[p] = 1;
+        for (int32_t i = n - 1; i >= 0; --i)
+            if (!seen[i]) order.push_back(i);
+    }
+    if (!c->plan_only) {
+        // nothing may still use the tables, slabs and staging buffers that are about to be freed
+        HIPCHK(c, hipSetDevice(c->device));
+        HIPCHK(c, hipStreamSynchronize(c->backward));
+        for (int l = 1; l < ddp_ctx::kMaxLanes; ++l)
+            if (c->lane[l]) HIPCHK(c, hipStreamSynchronize(c->lane[l]));
+        HIPCHK(c, hipStreamSynchronize(c->reduce));
+        if (c->global_on_device) {      // keep the closed iteration's bitmap readable
+            for (int32_t i = 0; i < n; ++i) c->global_closed[i] = c->h_global[c->plan.params[i].segment];
+            c->global_on_device = false;
+        }
+        drop_timed(c);
+        c->local_in_flight[0] = c->local_in_flight[1] = false;
+        c->global_in_flight = false;
+        c->micro_in_flight = false;
+        c->pin_ready_iter = -1;
+    }
+    const std::vector<uint8_t> keep_global = c->global_closed, keep_used = c->used_closed;
+    c->built = false;
+    const int32_t nb = build_internal(c, cap_bytes, &order);
+    if (nb < 0) return nb;
+    c->global_closed = keep_global;     // indexed by parameter: unaffected by the new mapping
+    c->used_closed = keep_used;
+    c->log_closed.clear();              // its bucket numbers belong to the old mapping
+    return nb;
+}
+
+int32_t ddp_get_ready_order(const ddp_ctx* c, int32_t which, int32_t* ids, int32_t cap, int32_t* n) {
+    if (!c || !n || cap < 0 || (which != 0 && which != 1)) return DDP_ERR_ARG;
+    if (!c->built) return DDP_ERR_STATE;
+    const std::vector<int32_t>& o = which == 0 ? c->order_running : c->order_closed;
+    *n = static_cast<int32_t>(o.size());
+    for (int32_t i = 0; i < *n && i < cap; ++i)
+        if (ids) ids[i] = o[i];
+    return DDP_OK;
+}
+
 int32_t ddp_get_assignment(const ddp_ctx* c, int32_t* bucket_of, int64_t* elem_offset) {
     if (!c || !bucket_of || !elem_offset) return DDP_ERR_ARG;
     if (!c->built) return DDP_ERR_STATE;
@@ -692,6 +754,7 @@ static int32_t mark_one(ddp_ctx* c, int32_t param_id, const uint8_t* used) {
     const int rc = c->tracker.mark(param_id, launch);
     if (rc == -1) return fail(c, DDP_ERR_ARG, "ddp_mark_ready: parameter id out of range");
     if (rc == -2) return fail(c, DDP_ERR_ALREADY_READY, "ddp_mark_ready: parameter already marked in this iteration");
+    c->order_running.push_back(param_id);
     if (set_participation(c, param_id, used)) c->used_running[param_id] = 1;
     for (int32_t b : launch) note_launch(c, b, c->tracker.marks() - 1);
     if (c->coalesce <= 0) return flush_deferred(c);
@@ -805,6 +868,8 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     }
     c->log_closed.swap(c->log_running);
     c->log_running.clear();
+    c->order_closed.swap(c->order_running);
+    c->order_running.clear();
     c->used_closed = c->used_running;
     std::fill(c->used_running.begin(), c->used_running.end(), 0);
     // host view of the global bitmap (all ones unless a flag was zero)

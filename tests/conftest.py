@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    # a fresh checkout has no library yet: build it once (an existing one is used as it is)
+    import __graft_entry__
+    __graft_entry__.ensure_built()
+
+
 def _gpu_present() -> bool:
     try:
         import torch

@@ -250,6 +250,80 @@ def test_reduction_stream_option_is_validated(d):
         d.ddp_destroy(ctx)
 
 
+@pytest.mark.parametrize("seed", range(20))
+def test_rebuild_from_trace_matches_oracle(d, seed):
+    """Section 6.2.1 on a plan-only context: the trace the library records is
+    the ready order; the rebuilt mapping and the following iteration's launch
+    log equal the oracle's; a second rebuild follows the newer trace."""
+    rng = np.random.default_rng(3000 + seed)
+    n = int(rng.integers(1, 100))
+    numel = [int(x) for x in rng.integers(0, 4000, size=n)]
+    dtype = [0] * n if seed % 2 else [int(x) for x in rng.integers(0, 3, size=n)]
+    cap = int(rng.choice([0, 1000, 8192, 60000]))
+    ctx, nb = plan(d, numel, dtype, cap, R=3)
+    try:
+        assert d.ddp_get_ready_order(ctx, 1) == []
+        for it in range(3):
+            order = [int(p) for p in rng.permutation(n)]
+            if (seed + it) % 3 == 0:
+                order = order[: int(rng.integers(0, n + 1))]
+            for k, p in enumerate(order):
+                d.ddp_mark_ready(ctx, p)
+                if k == 0:
+                    assert d.ddp_get_ready_order(ctx, 0) == [p]
+            d.ddp_finalize_backward(ctx)
+            assert d.ddp_get_ready_order(ctx, 1) == order
+            assert d.ddp_get_ready_order(ctx, 0) == []
+            cap2 = int(rng.choice([cap, 500, 20000]))
+            visit = oracle.traced_visit_order(order, n)
+            asg = oracle.assign_buckets_in_order(numel, dtype, cap2, visit)
+            assert d.ddp_rebuild_buckets(ctx, cap2) == len(asg.buckets)
+            bucket_of, offset = d.ddp_get_assignment(ctx, n)
+            assert bucket_of.tolist() == asg.bucket_of.tolist()
+            assert offset.tolist() == asg.offset_of.tolist()
+            for b, bk in enumerate(asg.buckets):
+                assert d.ddp_get_bucket_info(ctx, b) == (bk.elems, len(bk.params), bk.dtype)
+            assert d.ddp_get_launch_log(ctx, 1) == []            # old bucket numbers are gone
+            assert d.ddp_get_ready_order(ctx, 1) == order        # the trace stays
+            # the same backward order again: every bucket goes out with its last gradient
+            d.ddp_mark_ready_many(ctx, order)
+            d.ddp_finalize_backward(ctx)
+            assert d.ddp_get_launch_log(ctx, 1) == oracle.launch_schedule(asg, order)
+    finally:
+        d.ddp_destroy(ctx)
+
+
+def test_rebuild_state_errors_and_empty_trace(d):
+    ctx = d.ddp_create(2, d.DDP_DEVICE_NONE)
+    try:
+        d.ddp_register_params(ctx, [100, 200, 50, 400, 25, 300], [0] * 6, None)
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_rebuild_buckets(ctx, 1600)
+        assert e.value.code == d.DDP_ERR_STATE
+        assert d.ddp_build_buckets(ctx, 1600) == 3
+        # no iteration closed yet: the trace is empty and the mapping stays the default one
+        assert d.ddp_rebuild_buckets(ctx, 1600) == 3
+        assert d.ddp_get_assignment(ctx, 6)[0].tolist() == [2, 2, 2, 1, 0, 0]
+        d.ddp_mark_ready(ctx, 4)
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_rebuild_buckets(ctx, 1600)
+        assert e.value.code == d.DDP_ERR_STATE
+        for p in (5, 1, 3):
+            d.ddp_mark_ready(ctx, p)
+        d.ddp_finalize_backward(ctx)
+        assert d.ddp_get_launch_log(ctx, 1) == [(0, 1), (1, 3), (2, 4)]
+        assert d.ddp_rebuild_buckets(ctx, 1600) == 4
+        bucket_of, offset = d.ddp_get_assignment(ctx, 6)
+        assert bucket_of.tolist() == [3, 1, 3, 2, 0, 0] and offset.tolist() == [50, 0, 0, 0, 0, 25]
+        for p in (4, 5, 1, 3):
+            d.ddp_mark_ready(ctx, p)
+        d.ddp_finalize_backward(ctx)
+        assert d.ddp_get_launch_log(ctx, 1) == [(0, 1), (1, 2), (2, 3), (3, 4)]
+        assert d.ddp_get_used_map(ctx, 6, 1).tolist() == [0, 1, 0, 1, 1, 1]
+    finally:
+        d.ddp_destroy(ctx)
+
+
 def test_compute_context_without_gpu_fails_loudly(d):
     import torch
     if torch.cuda.is_available():
