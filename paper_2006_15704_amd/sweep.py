@@ -71,6 +71,11 @@ def main() -> int:
                     help="comma list: numbers of reduction streams (DDP_OPT_REDUCE_STREAMS)")
     ap.add_argument("--coalesce-mib", type=float, default=0,
                     help="DDP_OPT_COALESCE in MiB (0 = off, negative = no limit)")
+    ap.add_argument("--shuffle-blocks", type=int, default=0,
+                    help="backward order = reverse registration order cut into blocks of this many "
+                         "parameters, the blocks shuffled (0 = plain reverse order).  Every "
+                         "configuration is then measured twice: with the default mapping and after "
+                         "ddp_rebuild_buckets has followed the traced order (Section 6.2.1)")
     ap.add_argument("--produce", action="store_true",
                     help="the synthetic backward also writes every gradient (copies it from a "
                          "source buffer after the delay), which keeps the memory system busy "
@@ -96,6 +101,11 @@ def main() -> int:
         src_ptrs = src.ptrs()
     torch.cuda.synchronize()
     order = list(range(n - 1, -1, -1))
+    if args.shuffle_blocks > 0:
+        import numpy as np
+        blocks = [order[i:i + args.shuffle_blocks] for i in range(0, n, args.shuffle_blocks)]
+        perm = np.random.default_rng(1).permutation(len(blocks))
+        order = [p for b in perm for p in blocks[int(b)]]
     caps = [int(x) for x in args.caps_mib.split(",")]
     delays = [int(x) for x in args.delays_us.split(",")]
 
@@ -119,32 +129,41 @@ def main() -> int:
                     lib.ddp_synth_backward(ctx, order, None, None, True)
                     lib.ddp_finalize_backward(ctx)
 
-                for _ in range(3):
-                    sync_alone()
-                t_sync = timed(sync_alone, sync, args.reps, torch, s.backward_stream)
-                for d_us in delays:
-                    dl = [d_us * 1000] * n
+                for mapping in (("default", "rebuilt") if args.shuffle_blocks > 0 else ("default",)):
+                    if mapping == "rebuilt":
+                        sync_alone()                       # leaves the trace of this order
+                        sync()
+                        n_buckets = lib.ddp_rebuild_buckets(ctx, cap)
+                    else:
+                        n_buckets = s.n_buckets
+                    for _ in range(3):
+                        sync_alone()
+                    t_sync = timed(sync_alone, sync, args.reps, torch, s.backward_stream)
+                    for d_us in delays:
+                        dl = [d_us * 1000] * n
 
-                    def backward_alone():
-                        lib.ddp_synth_backward(ctx, order, dl, src_ptrs, False)
+                        def backward_alone():
+                            lib.ddp_synth_backward(ctx, order, dl, src_ptrs, False)
 
-                    def backward_and_sync():
-                        lib.ddp_synth_backward(ctx, order, dl, src_ptrs, True)
-                        lib.ddp_finalize_backward(ctx)
+                        def backward_and_sync():
+                            lib.ddp_synth_backward(ctx, order, dl, src_ptrs, True)
+                            lib.ddp_finalize_backward(ctx)
 
-                    t_bwd = timed(backward_alone, sync, args.reps, torch, s.backward_stream) if (d_us > 0 or src_ptrs) else 0.0
-                    t_tot = timed(backward_and_sync, sync, args.reps, torch, s.backward_stream)
-                    exposed = t_tot - t_bwd
-                    print(json.dumps({
-                        "workload": args.workload, "dtype": args.dtype, "R": R, "pipeline": pipe,
-                        "cap_mib": cap_mib, "n_buckets": s.n_buckets, "streams": n_streams,
-                        "coalesce_mib": args.coalesce_mib, "delay_us_per_param": d_us,
-                        "backward_writes_gradients": bool(src_ptrs), "busy_blocks": args.busy_blocks,
-                        "t_backward_ms": round(t_bwd, 4), "t_sync_ms": round(t_sync, 4),
-                        "t_total_ms": round(t_tot, 4), "exposed_ms": round(exposed, 4),
-                        "overlap": round(1.0 - exposed / t_sync, 3) if t_sync > 0 else None,
-                        "sync_gbps_alg": round((R + 1) * B / t_sync / 1e6, 1),
-                    }), flush=True)
+                        t_bwd = timed(backward_alone, sync, args.reps, torch, s.backward_stream) if (d_us > 0 or src_ptrs) else 0.0
+                        t_tot = timed(backward_and_sync, sync, args.reps, torch, s.backward_stream)
+                        exposed = t_tot - t_bwd
+                        print(json.dumps({
+                            "workload": args.workload, "dtype": args.dtype, "R": R, "pipeline": pipe,
+                            "cap_mib": cap_mib, "n_buckets": n_buckets, "streams": n_streams,
+                            "coalesce_mib": args.coalesce_mib, "delay_us_per_param": d_us,
+                            "order": f"blocks of {args.shuffle_blocks} shuffled" if args.shuffle_blocks else "reverse",
+                            "mapping": mapping,
+                            "backward_writes_gradients": bool(src_ptrs), "busy_blocks": args.busy_blocks,
+                            "t_backward_ms": round(t_bwd, 4), "t_sync_ms": round(t_sync, 4),
+                            "t_total_ms": round(t_tot, 4), "exposed_ms": round(exposed, 4),
+                            "overlap": round(1.0 - exposed / t_sync, 3) if t_sync > 0 else None,
+                            "sync_gbps_alg": round((R + 1) * B / t_sync / 1e6, 1),
+                        }), flush=True)
     return 0
 
 
