@@ -4,8 +4,12 @@
 One "step" is one pass of the whole hot path over one batch of synthetic
 gradients, through the C ABI: ready marks for every parameter in reverse
 registration order (each bucket is launched as soon as it is complete and its
-predecessors have been launched), then the finalizing step.  Inputs are
-resident in HBM before the timed region starts.  The default pipeline is the
+predecessors have been launched), then the finalizing step.  The marks of a
+step arrive in one call, so with the library's defaults consecutive buckets
+share a kernel launch up to 100 MiB (DDP_OPT_COALESCE); the
+`one_launch_per_bucket` and `two_streams` sub-objects report the same steps
+with a launch per bucket.  Inputs are resident in HBM before the timed region
+starts.  The default pipeline is the
 one-pass (fused) one; `--pipeline staged` times the literal pack / reduce /
 unpack pipeline instead, and the default run also reports the staged
 pipeline's per-kernel rates in a `staged` sub-object.
@@ -15,9 +19,9 @@ Prints ONE JSON line.
             average written W = 1 times -- the algorithmic end-to-end bytes of
             one synchronization divided by the measured step time.
   roofline  the reduce kernel (the dominant one) against the 8 TB/s HBM peak:
-            algorithmic bytes per launch (R + 1) * bucket_bytes divided by the
-            average launch duration, measured with HIP events on the reduction
-            stream inside the timed region.
+            algorithmic bytes per launch = (R + 1) * bytes of the buckets the
+            launch covers, divided by the average launch duration, measured
+            with HIP events on the reduction stream inside the timed region.
   cpu_baseline  the CPU oracle on the same workload.
 """
 from __future__ import annotations
@@ -128,7 +132,7 @@ def main() -> int:
     ap.add_argument("--no-staged-leg", action="store_true",
                     help="skip the extra measurement of the staged pipeline's kernels")
     ap.add_argument("--no-coalesce-leg", action="store_true",
-                    help="skip the extra measurement with coalesced launches")
+                    help="skip the extra measurement with one launch per bucket")
     ap.add_argument("--no-streams-leg", action="store_true",
                     help="skip the extra measurement with two reduction streams")
     ap.add_argument("--no-accumulate-leg", action="store_true",
@@ -140,7 +144,8 @@ def main() -> int:
                     help="fused pipeline: bucket size from which blocks take two tiles")
     ap.add_argument("--coalesce-mib", type=float, default=None,
                     help="buckets completed by one call share a launch up to this many MiB "
-                         "(DDP_OPT_COALESCE; negative = no limit)")
+                         "(DDP_OPT_COALESCE; 0 = one launch per bucket, negative = no limit; "
+                         "default: the library's, 100 MiB)")
     ap.add_argument("--streams", type=int, default=None,
                     help="reduction streams taken in turn by the bucket launches (DDP_OPT_REDUCE_STREAMS)")
     ap.add_argument("--copy-nt-store", action="store_true",
@@ -289,33 +294,35 @@ def main() -> int:
         }
 
     if args.pipeline == "fused" and args.coalesce_mib is None and not args.no_coalesce_leg:
-        # the same steps with DDP_OPT_COALESCE: buckets completed by one call share a launch
-        args.coalesce_mib = 100.0
-        co = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
+        # the same steps with one launch per bucket (DDP_OPT_COALESCE = 0), as when the ready marks
+        # arrive in separate calls during a real backward pass
+        args.coalesce_mib = 0.0
+        pb = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
         args.coalesce_mib = None
-        co_ms, co_launches = co["iteration"]
-        out["coalesced_100mib"] = {
-            "ms_per_step": round(co["ms_per_step"], 4),
-            "value_gbps": round((R + W) * B / co["ms_per_step"] / 1e6, 1),
-            "launches_per_step": int(co_launches.sum()) // args.steps,
-            "reduce_gbps": round((R + 1) * B * len(co_ms) / float(co_ms.sum()) / 1e6, 1),
-            "frac_of_hbm_peak": round((R + 1) * B * len(co_ms) / float(co_ms.sum()) / 1e6 / HBM_PEAK_GBPS, 4),
+        pb_ms, pb_launches = pb["iteration"]
+        out["one_launch_per_bucket"] = {
+            "ms_per_step": round(pb["ms_per_step"], 4),
+            "value_gbps": round((R + W) * B / pb["ms_per_step"] / 1e6, 1),
+            "launches_per_step": int(pb_launches.sum()) // args.steps,
+            "reduce_gbps": round((R + 1) * B * len(pb_ms) / float(pb_ms.sum()) / 1e6, 1),
+            "frac_of_hbm_peak": round((R + 1) * B * len(pb_ms) / float(pb_ms.sum()) / 1e6 / HBM_PEAK_GBPS, 4),
         }
 
     if args.pipeline == "fused" and args.streams is None and not args.no_streams_leg:
-        # the same steps with the bucket launches alternating between two reduction streams
+        # one launch per bucket, the launches alternating between two reduction streams
         # (DDP_OPT_REDUCE_STREAMS): neighbouring buckets overlap, so only the iteration as a
         # whole has a duration
         args.streams = 2
+        keep_coalesce, args.coalesce_mib = args.coalesce_mib, 0.0
         rr = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
-        args.streams = None
+        args.streams, args.coalesce_mib = None, keep_coalesce
         rr_ms, _ = rr["iteration"]
         out["two_streams"] = {
             "ms_per_step": round(rr["ms_per_step"], 4),
             "value_gbps": round((R + W) * B / rr["ms_per_step"] / 1e6, 1),
             "reduce_gbps": round((R + 1) * B * len(rr_ms) / float(rr_ms.sum()) / 1e6, 1),
             "frac_of_hbm_peak": round((R + 1) * B * len(rr_ms) / float(rr_ms.sum()) / 1e6 / HBM_PEAK_GBPS, 4),
-            "note": "(R+1)*B per iteration / time from the first launch to the join of both streams",
+            "note": "one launch per bucket; (R+1)*B per iteration / time from the first launch to the join of both streams",
         }
 
     if not args.no_accumulate_leg:

@@ -75,9 +75,11 @@ typedef struct ddp_ctx ddp_ctx;
                                      (0 = one block per tile) */
 #define DDP_OPT_NONTEMPORAL    5  /* any time: 1 (default) = read-once inputs are loaded, and the
                                      averages stored, with the non-temporal hint; 0 = plain */
-#define DDP_OPT_PAIR_MIN_BYTES 7  /* any time: fused pipeline, buckets of at least this many bytes
-                                     are reduced with two tiles per thread block (more loads in
-                                     flight per thread; pays off on large launches).  Default 48 MiB */
+#define DDP_OPT_PAIR_MIN_BYTES 7  /* any time: fused pipeline, launches of at least this many bytes
+                                     whose tensors average at least 256 tiles (2 MiB) are reduced
+                                     with two tiles per thread block (more loads in flight per
+                                     thread; pays off on long launches of large tensors).  Default
+                                     48 MiB */
 #define DDP_OPT_EMIT_BUSY_BLOCKS 8 /* any time: ddp_synth_backward's delay kernel.  0 (default): one
                                      thread block that sleeps between clock polls; n > 0: n blocks
                                      that do arithmetic between polls, so that the delay loads the
@@ -89,8 +91,10 @@ typedef struct ddp_ctx ddp_ctx;
                                      between two of its kernels) and that are consecutive and of one
                                      element type share ONE launch per kernel as long as the launch
                                      stays within `value` bytes of bucket data (INT64_MAX: no
-                                     limit); order and results are unchanged.  Default 0 = one
-                                     launch per bucket */
+                                     limit); order and results are unchanged.  0 = one launch per
+                                     bucket.  Default 100 MiB (measured: short launches pay a fixed
+                                     start-up and drain cost each, launches far beyond 100 MiB lose
+                                     throughput again) */
 #define DDP_OPT_FIND_UNUSED   11  /* any time between iterations: the paper's find_unused_parameters
                                      knob.  1 = gradients of parameters that no replica used in the
                                      iteration (the global bitmap of Section 4.2 says so) are left

@@ -50,9 +50,10 @@ struct ddp_ctx {
     int32_t nontemporal = 1;
     int32_t unroll = 2;
     int32_t copy_nt_store = 0;
-    int64_t coalesce = 0;                         // > 0: consecutive buckets of one API call share a
+    int64_t coalesce = int64_t(100) << 20;        // > 0: consecutive buckets of one API call share a
                                                   // launch while it stays within this many bytes
-    int64_t pair_min_bytes = int64_t(48) << 20;   // buckets at least this large use paired tiles
+    int64_t pair_min_bytes = int64_t(48) << 20;   // launches at least this large use paired tiles ...
+    static constexpr int64_t kPairMinTilesPerSegment = 256;   // ... if their tensors are large on average
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
     int32_t n_streams = 1;                        // reduction streams taken in turn by the launches
 
@@ -263,10 +264,15 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
                                           c->reduce_blocks, c->unroll, c->nontemporal != 0, st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     } else {
+        // Paired tiles keep more loads in flight per thread, which pays on long launches made of
+        // large tensors (most tiles interior); with many small tensors the pairs fall back to two
+        // tiles one after the other and only lengthen the blocks.
+        const bool pair = bytes >= c->pair_min_bytes &&
+                          ntiles >= ddp_ctx::kPairMinTilesPerSegment * static_cast<int64_t>(seg_end - seg_begin);
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_fused_reduce(bf.dtype, c->tables, tile_base, ntiles, c->R,
                                            c->write_all ? c->R : 1, d_flags, c->find_unused != 0, sc,
-                                           c->unroll, bytes >= c->pair_min_bytes, c->nontemporal != 0,
+                                           c->unroll, pair, c->nontemporal != 0,
                                            st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     }

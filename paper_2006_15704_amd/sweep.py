@@ -118,9 +118,8 @@ def main() -> int:
                 ctx = s.ctx
                 lib.ddp_set_option(ctx, lib.DDP_OPT_EMIT_BUSY_BLOCKS, args.busy_blocks)
                 lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_STREAMS, n_streams)
-                if args.coalesce_mib:
-                    lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE,
-                                       (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * MIB))
+                lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE,
+                                   (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * MIB))
 
                 def sync():
                     lib.ddp_synchronize(ctx)

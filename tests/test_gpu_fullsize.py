@@ -61,9 +61,16 @@ def test_model_shapes_r8_fp32(name, config_id, sigma, nb):
     grads = harness.DeviceGrads(numel, [FP32] * n, R)
     for r in range(1, R):
         grads.upload_replica(r, reps[r])
-    for pipeline in (STAGED, FUSED):
+    # the library's defaults (what bench.py's headline line times), then one launch per bucket,
+    # then one launch per bucket on two reduction streams (the benchmark's other legs)
+    configs = [(STAGED, ()), (FUSED, ()), (FUSED, ((d.DDP_OPT_COALESCE, 0),)),
+               (FUSED, ((d.DDP_OPT_COALESCE, 0), (d.DDP_OPT_REDUCE_STREAMS, 2)))]
+    for pipeline, options in configs:
+        progress(f"{name}: pipeline {pipeline} options {options}")
         grads.upload_replica(0, reps[0])
         with harness.Session(grads, 25 * MIB, pipeline) as s:
+            for opt, val in options:
+                d.ddp_set_option(s.ctx, opt, val)
             assert s.n_buckets == nb
             bucket_of, offset = d.ddp_get_assignment(s.ctx, n)
             assert bucket_of.tolist() == asg.bucket_of.tolist() and offset.tolist() == asg.offset_of.tolist()
