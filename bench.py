@@ -87,6 +87,10 @@ def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup
                                (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * (1 << 20)))
         if args.streams is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_STREAMS, args.streams)
+        if args.blocks_per_cu is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_BLOCKS_PER_CU, args.blocks_per_cu)
+        if args.cap_min_mib is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_CAP_MIN_BYTES, int(args.cap_min_mib * (1 << 20)))
         if args.pair_min_mib is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_PAIR_MIN_BYTES, int(args.pair_min_mib * (1 << 20)))
 
@@ -148,6 +152,11 @@ def main() -> int:
                          "default: the library's, 100 MiB)")
     ap.add_argument("--streams", type=int, default=None,
                     help="reduction streams taken in turn by the bucket launches (DDP_OPT_REDUCE_STREAMS)")
+    ap.add_argument("--blocks-per-cu", type=int, default=None,
+                    help="reduce kernels: resident thread blocks per compute unit "
+                         "(DDP_OPT_REDUCE_BLOCKS_PER_CU; 0 = no cap)")
+    ap.add_argument("--cap-min-mib", type=float, default=None,
+                    help="launch size from which that cap applies (DDP_OPT_REDUCE_CAP_MIN_BYTES)")
     ap.add_argument("--copy-nt-store", action="store_true",
                     help="staged pipeline: pack/unpack store with the non-temporal hint")
     ap.add_argument("--same-stream", action="store_true",

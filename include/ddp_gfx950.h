@@ -78,8 +78,8 @@ typedef struct ddp_ctx ddp_ctx;
 #define DDP_OPT_PAIR_MIN_BYTES 7  /* any time: fused pipeline, launches of at least this many bytes
                                      whose tensors average at least 256 tiles (2 MiB) are reduced
                                      with two tiles per thread block (more loads in flight per
-                                     thread; pays off on long launches of large tensors).  Default
-                                     48 MiB */
+                                     thread; pays off on long launches of large tensors).  0 = every
+                                     launch, whatever its tensors.  Default 48 MiB */
 #define DDP_OPT_EMIT_BUSY_BLOCKS 8 /* any time: ddp_synth_backward's delay kernel.  0 (default): one
                                      thread block that sleeps between clock polls; n > 0: n blocks
                                      that do arithmetic between polls, so that the delay loads the
@@ -109,6 +109,17 @@ typedef struct ddp_ctx ddp_ctx;
                                      for backward_stream like reduce_stream does, and at finalize all
                                      of them are joined into reduce_stream before the averaged
                                      gradients are handed back.  Results are unchanged */
+#define DDP_OPT_REDUCE_BLOCKS_PER_CU 13 /* any time: cap on the thread blocks of the reduce kernels that
+                                     are resident on one compute unit at a time (an LDS allocation
+                                     the kernels do not touch enforces it).  A block keeps R x 2
+                                     16-byte loads per thread in flight, so two or three blocks per
+                                     unit fill the memory system; more only interleave more request
+                                     streams at the DRAM channels and throughput drops.  0 = no cap
+                                     (registers decide: 5, or 3 with paired tiles).  Default 2 */
+#define DDP_OPT_REDUCE_CAP_MIN_BYTES 14 /* any time: the cap applies to launches of at least this many
+                                     bytes of bucket data (measured: it gains 1 to 2.5 points of
+                                     HBM peak from 50 MiB up and loses 1.5 to 3 on launches of 25
+                                     MiB and less).  Default 40 MiB */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 

@@ -56,6 +56,9 @@ struct ddp_ctx {
     static constexpr int64_t kPairMinTilesPerSegment = 256;   // ... if their tensors are large on average
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
     int32_t n_streams = 1;                        // reduction streams taken in turn by the launches
+    int32_t blocks_per_cu = 2;                    // reduce kernels: resident blocks per compute unit (0 = no cap)
+    int64_t cap_min_bytes = int64_t(40) << 20;    // ... applied to launches of at least this many bytes
+    int64_t lds_per_cu = 160 * 1024;              // read from the device at creation
 
     bool registered = false, built = false;
     ddp::BucketPlan plan;
@@ -132,6 +135,13 @@ int32_t fail(ddp_ctx* c, int32_t code, const std::string& msg) {
         if (e_ != hipSuccess)                                                              \
             return fail((c), DDP_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
     } while (0)
+
+// Bytes of unused dynamic LDS per block that leave room for exactly
+// blocks_per_cu blocks on a compute unit.
+unsigned occupancy_lds(const ddp_ctx* c, int64_t launch_bytes) {
+    if (c->blocks_per_cu <= 0 || launch_bytes < c->cap_min_bytes) return 0;
+    return static_cast<unsigned>((c->lds_per_cu / c->blocks_per_cu) & ~int64_t(1023));
+}
 
 ddp::Scale make_scale(int R) {
     ddp::Scale sc;
@@ -257,23 +267,24 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
         const int64_t nvec = (c->bucket_slab_off[last] - c->bucket_slab_off[first]) / 16 + c->bucket_vecs[last];
         if ((rc = timed_begin(c, DDP_K_PACK, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_pack(c->tables, tile_base, ntiles, c->slabs, c->slab_stride, c->R,
-                                   d_flags, c->copy_nt_store != 0, st));
+                                   d_flags, c->copy_nt_store != 0, 0, st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_flat_reduce(bf.dtype, in0, c->slab_stride, out, nvec, c->R, sc,
-                                          c->reduce_blocks, c->unroll, c->nontemporal != 0, st));
+                                          c->reduce_blocks, c->unroll, c->nontemporal != 0,
+                                          occupancy_lds(c, bytes), st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     } else {
         // Paired tiles keep more loads in flight per thread, which pays on long launches made of
         // large tensors (most tiles interior); with many small tensors the pairs fall back to two
         // tiles one after the other and only lengthen the blocks.
         const bool pair = bytes >= c->pair_min_bytes &&
-                          ntiles >= ddp_ctx::kPairMinTilesPerSegment * static_cast<int64_t>(seg_end - seg_begin);
+                          (c->pair_min_bytes == 0 ||      // 0 = always (lets tests reach every path of the kernel)
+                           ntiles >= ddp_ctx::kPairMinTilesPerSegment * static_cast<int64_t>(seg_end - seg_begin));
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_fused_reduce(bf.dtype, c->tables, tile_base, ntiles, c->R,
                                            c->write_all ? c->R : 1, d_flags, c->find_unused != 0, sc,
-                                           c->unroll, pair, c->nontemporal != 0,
-                                           st));
+                                           c->unroll, pair, c->nontemporal != 0, occupancy_lds(c, bytes), st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     }
     return DDP_OK;
@@ -396,6 +407,9 @@ int32_t ddp_create(ddp_ctx** out, int32_t R, int32_t device, void* reduce_stream
         int khz = 0;
         if (e == hipSuccess) e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device);
         if (e == hipSuccess && khz > 0) c->wall_clock_khz = khz;
+        int lds = 0;
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device);
+        if (e == hipSuccess && lds >= 64 * 1024) c->lds_per_cu = lds;
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_done, kOrderEvent);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_local[0], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_local[1], hipEventDisableTiming);
@@ -447,6 +461,14 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             return DDP_OK;
         case DDP_OPT_FIND_UNUSED:
             c->find_unused = value != 0;
+            return DDP_OK;
+        case DDP_OPT_REDUCE_BLOCKS_PER_CU:
+            if (value < 0 || value > 16) return fail(c, DDP_ERR_ARG, "blocks per compute unit outside [0, 16]");
+            c->blocks_per_cu = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_REDUCE_CAP_MIN_BYTES:
+            if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
+            c->cap_min_bytes = value;
             return DDP_OK;
         case DDP_OPT_REDUCE_STREAMS:
             if (value < 1 || value > ddp_ctx::kMaxLanes)
@@ -864,7 +886,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             HIPCHK(c, ddp::launch_unpack(c->tables, 0, c->h_tile0[n],
                                          c->slabs + static_cast<int64_t>(c->R) * c->slab_stride,
                                          c->write_all ? c->R : 1, c->iter_zero ? c->d_global : nullptr,
-                                         c->find_unused != 0, c->copy_nt_store != 0, c->reduce));
+                                         c->find_unused != 0, c->copy_nt_store != 0, 0, c->reduce));
             if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
         }
         if (c->backward != c->reduce) {
@@ -956,7 +978,7 @@ int32_t ddp_no_sync_accumulate(ddp_ctx* c, void* const* micro) {
     size_t slot;
     int32_t rc;
     if ((rc = timed_begin(c, DDP_K_ACCUMULATE, -1, c->backward, &slot)) != DDP_OK) return rc;
-    HIPCHK(c, ddp::launch_accumulate(c->tables, c->h_tile0[n], c->R, n, c->d_micro, c->backward));
+    HIPCHK(c, ddp::launch_accumulate(c->tables, c->h_tile0[n], c->R, n, c->d_micro, 0, c->backward));
     if ((rc = timed_end(c, slot, c->backward)) != DDP_OK) return rc;
     for (int32_t i = 0; i < n; ++i) {
         const size_t row = static_cast<size_t>(c->plan.params[i].segment) * R;

@@ -58,7 +58,9 @@ struct Scale {       // y = use_mul ? s * mul : s / div
 };
 
 // All segment launches cover the tiles [tile_base, tile_base + ntiles) of the
-// global tile numbering (tile0 / tile_seg).
+// global tile numbering (tile0 / tile_seg).  `lds` in K1-K4: bytes of dynamic
+// LDS per block that the kernels do not use; they cap the number of blocks
+// resident on a compute unit (0 = no cap).
 
 // K1: gradients -> flat replica slabs for all `nrep` replicas.  local (may be
 // null = every replica used every parameter): participation flags
@@ -66,21 +68,21 @@ struct Scale {       // y = use_mul ? s * mul : s / div
 // its tensor.
 hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
                        int64_t slab_stride, int nrep, const uint8_t* local, bool nt_store,
-                       hipStream_t s);
+                       unsigned lds, hipStream_t s);
 
 // K3: averaged slab -> gradient tensors of replicas [0, nrep).  global_used (may
 // be null): per segment, 0 = no replica used the parameter; with keep_unused
 // such parameters are not written.
 hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
                          const char* out_slab, int nrep, const uint8_t* global_used, bool keep_unused,
-                         bool nt_store, hipStream_t s);
+                         bool nt_store, unsigned lds, hipStream_t s);
 
 // K2 (staged): out[v] = scale(sum_r in_r[v]) over nvec 16-byte vectors;
 // in_r = in0 + r*stride.  unroll = vectors per thread (1, 2 or 4);
 // max_blocks > 0 bounds the grid (blocks then loop).
 hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* out, int64_t nvec,
                               int R, Scale sc, int max_blocks, int unroll, bool nontemporal,
-                              hipStream_t s);
+                              unsigned lds, hipStream_t s);
 
 // K2 (fused): gather R replicas through the segment table, reduce, scatter to
 // the gradient tensors of replicas [0, nwrite).  local / keep_unused as above
@@ -89,7 +91,7 @@ hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* 
 // take two tiles each (for large launches).
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
-                               int unroll, bool pair, bool nontemporal, hipStream_t s);
+                               int unroll, bool pair, bool nontemporal, unsigned lds, hipStream_t s);
 
 // global[g] = OR_r local[g*R + r]  (the bitmap AllReduce of Section 4.2).
 hipError_t launch_bitmap_or(const uint8_t* local, uint8_t* global, int G, int R, hipStream_t s);
@@ -97,7 +99,7 @@ hipError_t launch_bitmap_or(const uint8_t* local, uint8_t* global, int G, int R,
 // K4: grad[r][g] += micro[r*n + param[g]] for all segments and replicas
 // (null micro pointers are skipped).  ntiles = tile0[G].
 hipError_t launch_accumulate(const SegTables& t, int64_t ntiles, int R, int n, void* const* micro,
-                             hipStream_t s);
+                             unsigned lds, hipStream_t s);
 
 // K6: wait `ticks` of the device wall clock (bounded), then copy
 // src_r -> dst_r (nelem elements of es bytes) for r < R, where

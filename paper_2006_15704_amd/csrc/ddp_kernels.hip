@@ -11,6 +11,9 @@
 // local gradient accumulation of no_sync (Section 3.2.4).
 #include "ddp_kernels.h"
 
+#include <mutex>
+#include <set>
+
 namespace ddp {
 namespace {
 
@@ -722,106 +725,125 @@ __global__ __launch_bounds__(BLOCK) void emit_kernel(int64_t ticks, void* const*
 
 inline hipError_t after_launch() { return hipGetLastError(); }
 
+// Every kernel here streams through HBM and needs only a few resident blocks per
+// CU to keep the memory system full; more blocks mean more interleaved request
+// streams at the DRAM channels and measurably less throughput.  `lds` bytes of
+// dynamic LDS that no kernel touches cap the number of resident blocks
+// (a CU has 160 KiB of LDS): 0 = no cap.
+constexpr unsigned kLdsNoOptIn = 64 * 1024;
+
+template <typename... KArgs, typename... Args>
+static hipError_t launch(void (*kernel)(KArgs...), dim3 grid, unsigned lds, hipStream_t s, Args... args) {
+    if (lds > kLdsNoOptIn) {
+        // allocations above 64 KiB must be allowed per kernel; once is enough
+        static std::mutex mu;
+        static std::set<const void*> raised;
+        std::lock_guard<std::mutex> lock(mu);
+        if (raised.find(reinterpret_cast<const void*>(kernel)) == raised.end()) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            if (e != hipSuccess) return e;
+            raised.insert(reinterpret_cast<const void*>(kernel));
+        }
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), lds, s, static_cast<KArgs>(args)...);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 // ---- launch wrappers ---------------------------------------------------------
 hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
                        int64_t slab_stride, int nrep, const uint8_t* local, bool nt_store,
-                       hipStream_t s) {
+                       unsigned lds, hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
-    if (nt_store) hipLaunchKernelGGL((seg_copy_kernel<true, true>), grid, dim3(BLOCK), 0, s, t, tile_base, slab0, slab_stride, local, 0);
-    else hipLaunchKernelGGL((seg_copy_kernel<true, false>), grid, dim3(BLOCK), 0, s, t, tile_base, slab0, slab_stride, local, 0);
-    return after_launch();
+    if (nt_store) return launch(seg_copy_kernel<true, true>, grid, lds, s, t, tile_base, slab0, slab_stride, local, 0);
+    return launch(seg_copy_kernel<true, false>, grid, lds, s, t, tile_base, slab0, slab_stride, local, 0);
 }
 
 hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
                          const char* out_slab, int nrep, const uint8_t* global_used, bool keep_unused,
-                         bool nt_store, hipStream_t s) {
+                         bool nt_store, unsigned lds, hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
     const int keep = keep_unused ? 1 : 0;
-    if (nt_store) hipLaunchKernelGGL((seg_copy_kernel<false, true>), grid, dim3(BLOCK), 0, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), global_used, keep);
-    else hipLaunchKernelGGL((seg_copy_kernel<false, false>), grid, dim3(BLOCK), 0, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), global_used, keep);
-    return after_launch();
+    if (nt_store) return launch(seg_copy_kernel<false, true>, grid, lds, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), global_used, keep);
+    return launch(seg_copy_kernel<false, false>, grid, lds, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), global_used, keep);
 }
 
 template <int DT, int U>
-static void flat_reduce_dispatch(bool nt, int64_t nrows, int max_blocks, hipStream_t s,
+static hipError_t flat_reduce_dispatch(bool nt, int64_t nrows, int max_blocks, unsigned lds, hipStream_t s,
                                  const char* in0, int64_t stride, char* out, int64_t nvec, int R,
                                  Scale sc) {
     int64_t blocks = nrows;
     if (max_blocks > 0 && blocks > max_blocks) blocks = max_blocks;
     dim3 grid(static_cast<unsigned>(blocks));
-    if (nt) hipLaunchKernelGGL((flat_reduce_kernel<DT, true, U>), grid, dim3(BLOCK), 0, s, in0, stride, out, nvec, R, sc);
-    else hipLaunchKernelGGL((flat_reduce_kernel<DT, false, U>), grid, dim3(BLOCK), 0, s, in0, stride, out, nvec, R, sc);
+    if (nt) return launch(flat_reduce_kernel<DT, true, U>, grid, lds, s, in0, stride, out, nvec, R, sc);
+    return launch(flat_reduce_kernel<DT, false, U>, grid, lds, s, in0, stride, out, nvec, R, sc);
 }
 
 template <int DT>
-static void flat_reduce_unroll(int unroll, bool nt, int max_blocks, hipStream_t s, const char* in0,
-                               int64_t stride, char* out, int64_t nvec, int R, Scale sc) {
-    if (unroll >= 4) flat_reduce_dispatch<DT, 4>(nt, (nvec + BLOCK * 4 - 1) / (BLOCK * 4), max_blocks, s, in0, stride, out, nvec, R, sc);
-    else if (unroll >= 2) flat_reduce_dispatch<DT, 2>(nt, (nvec + BLOCK * 2 - 1) / (BLOCK * 2), max_blocks, s, in0, stride, out, nvec, R, sc);
-    else flat_reduce_dispatch<DT, 1>(nt, (nvec + BLOCK - 1) / BLOCK, max_blocks, s, in0, stride, out, nvec, R, sc);
+static hipError_t flat_reduce_unroll(int unroll, bool nt, int max_blocks, unsigned lds, hipStream_t s,
+                                     const char* in0, int64_t stride, char* out, int64_t nvec, int R, Scale sc) {
+    if (unroll >= 4) return flat_reduce_dispatch<DT, 4>(nt, (nvec + BLOCK * 4 - 1) / (BLOCK * 4), max_blocks, lds, s, in0, stride, out, nvec, R, sc);
+    if (unroll >= 2) return flat_reduce_dispatch<DT, 2>(nt, (nvec + BLOCK * 2 - 1) / (BLOCK * 2), max_blocks, lds, s, in0, stride, out, nvec, R, sc);
+    return flat_reduce_dispatch<DT, 1>(nt, (nvec + BLOCK - 1) / BLOCK, max_blocks, lds, s, in0, stride, out, nvec, R, sc);
 }
 
 hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* out, int64_t nvec,
                               int R, Scale sc, int max_blocks, int unroll, bool nontemporal,
-                              hipStream_t s) {
+                              unsigned lds, hipStream_t s) {
     if (nvec <= 0) return hipSuccess;
     switch (dtype) {
-        case 0: flat_reduce_unroll<0>(unroll, nontemporal, max_blocks, s, in0, stride, out, nvec, R, sc); break;
-        case 1: flat_reduce_unroll<1>(unroll, nontemporal, max_blocks, s, in0, stride, out, nvec, R, sc); break;
-        case 2: flat_reduce_unroll<2>(unroll, nontemporal, max_blocks, s, in0, stride, out, nvec, R, sc); break;
+        case 0: return flat_reduce_unroll<0>(unroll, nontemporal, max_blocks, lds, s, in0, stride, out, nvec, R, sc);
+        case 1: return flat_reduce_unroll<1>(unroll, nontemporal, max_blocks, lds, s, in0, stride, out, nvec, R, sc);
+        case 2: return flat_reduce_unroll<2>(unroll, nontemporal, max_blocks, lds, s, in0, stride, out, nvec, R, sc);
         default: return hipErrorInvalidValue;
     }
-    return after_launch();
 }
 
 template <int DT, int U>
-static void fused_dispatch(bool nt, dim3 grid, hipStream_t s, const SegTables& t, int64_t tile_base,
-                           int R, int nwrite, const uint8_t* local, int keep, Scale sc) {
-    if (nt) hipLaunchKernelGGL((fused_reduce_kernel<DT, true, U>), grid, dim3(BLOCK), 0, s, t, tile_base, R, nwrite, local, keep, sc);
-    else hipLaunchKernelGGL((fused_reduce_kernel<DT, false, U>), grid, dim3(BLOCK), 0, s, t, tile_base, R, nwrite, local, keep, sc);
+static hipError_t fused_dispatch(bool nt, dim3 grid, unsigned lds, hipStream_t s, const SegTables& t,
+                                 int64_t tile_base, int R, int nwrite, const uint8_t* local, int keep, Scale sc) {
+    if (nt) return launch(fused_reduce_kernel<DT, true, U>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
+    return launch(fused_reduce_kernel<DT, false, U>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
 }
 
 template <int DT>
-static void fused_unroll(int unroll, bool pair, bool nt, int64_t ntiles, hipStream_t s,
-                         const SegTables& t, int64_t tile_base, int R, int nwrite,
-                         const uint8_t* local, int keep, Scale sc) {
+static hipError_t fused_unroll(int unroll, bool pair, bool nt, int64_t ntiles, unsigned lds, hipStream_t s,
+                               const SegTables& t, int64_t tile_base, int R, int nwrite,
+                               const uint8_t* local, int keep, Scale sc) {
     constexpr int UMAX = TILE_VECS / BLOCK;      // a tile holds at most this many vectors per thread
     if (pair) {
         dim3 grid(static_cast<unsigned>((ntiles + 1) / 2));
-        if (nt) hipLaunchKernelGGL((fused_reduce_pair_kernel<DT, true, UMAX>), grid, dim3(BLOCK), 0, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc);
-        else hipLaunchKernelGGL((fused_reduce_pair_kernel<DT, false, UMAX>), grid, dim3(BLOCK), 0, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc);
-        return;
+        if (nt) return launch(fused_reduce_pair_kernel<DT, true, UMAX>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc);
+        return launch(fused_reduce_pair_kernel<DT, false, UMAX>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc);
     }
     dim3 grid(static_cast<unsigned>(ntiles));
-    if (unroll >= 4 && UMAX >= 4) fused_dispatch<DT, (UMAX >= 4 ? 4 : 1)>(nt, grid, s, t, tile_base, R, nwrite, local, keep, sc);
-    else if (unroll >= 2 && UMAX >= 2) fused_dispatch<DT, (UMAX >= 2 ? 2 : 1)>(nt, grid, s, t, tile_base, R, nwrite, local, keep, sc);
-    else fused_dispatch<DT, 1>(nt, grid, s, t, tile_base, R, nwrite, local, keep, sc);
+    if (unroll >= 4 && UMAX >= 4) return fused_dispatch<DT, (UMAX >= 4 ? 4 : 1)>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
+    if (unroll >= 2 && UMAX >= 2) return fused_dispatch<DT, (UMAX >= 2 ? 2 : 1)>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
+    return fused_dispatch<DT, 1>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
 }
 
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
-                               int unroll, bool pair, bool nontemporal, hipStream_t s) {
+                               int unroll, bool pair, bool nontemporal, unsigned lds, hipStream_t s) {
     if (ntiles <= 0) return hipSuccess;
     const int keep = keep_unused ? 1 : 0;
     switch (dtype) {
-        case 0: fused_unroll<0>(unroll, pair, nontemporal, ntiles, s, t, tile_base, R, nwrite, local, keep, sc); break;
-        case 1: fused_unroll<1>(unroll, pair, nontemporal, ntiles, s, t, tile_base, R, nwrite, local, keep, sc); break;
-        case 2: fused_unroll<2>(unroll, pair, nontemporal, ntiles, s, t, tile_base, R, nwrite, local, keep, sc); break;
+        case 0: return fused_unroll<0>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc);
+        case 1: return fused_unroll<1>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc);
+        case 2: return fused_unroll<2>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc);
         default: return hipErrorInvalidValue;
     }
-    return after_launch();
 }
 
 hipError_t launch_accumulate(const SegTables& t, int64_t ntiles, int R, int n, void* const* micro,
-                             hipStream_t s) {
+                             unsigned lds, hipStream_t s) {
     if (ntiles <= 0 || R <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(R));
-    hipLaunchKernelGGL(accumulate_kernel, grid, dim3(BLOCK), 0, s, t, n, micro);
-    return after_launch();
+    return launch(accumulate_kernel, grid, lds, s, t, n, micro);
 }
 
 hipError_t launch_bitmap_or(const uint8_t* local, uint8_t* global, int G, int R, hipStream_t s) {

@@ -163,7 +163,11 @@ def test_kernel_variants_give_the_same_bits(dtype, unroll):
         for nt in (1, 0):
             opts = [(d.DDP_OPT_REDUCE_UNROLL, unroll), (d.DDP_OPT_PAIR_MIN_BYTES, pair_min),
                     (d.DDP_OPT_NONTEMPORAL, nt), (d.DDP_OPT_COPY_NT_STORE, nt),
-                    (d.DDP_OPT_COALESCE, (1 << 62) if pair_min == 0 else 0)]
+                    (d.DDP_OPT_COALESCE, (1 << 62) if pair_min == 0 else 0),
+                    # occupancy cap of the reduce kernels: none, one block per unit (the largest
+                    # LDS allocation), three
+                    (d.DDP_OPT_REDUCE_CAP_MIN_BYTES, 0),
+                    (d.DDP_OPT_REDUCE_BLOCKS_PER_CU, (0 if nt else 1) if pair_min == 0 else 3)]
             for pipeline in (STAGED, FUSED):
                 run_sync(numel, [dtype] * len(numel), reps, 1 << 22, pipeline, order=order, skew=skew,
                          options=opts, write_all=(nt == 0))

@@ -234,6 +234,13 @@ def test_participation_argument_errors(d):
 def test_reduction_stream_option_is_validated(d):
     ctx, _ = plan(d, [4, 4, 4], [0, 0, 0], 0)
     try:
+        for opt, bad in ((d.DDP_OPT_REDUCE_BLOCKS_PER_CU, -1), (d.DDP_OPT_REDUCE_BLOCKS_PER_CU, 17),
+                         (d.DDP_OPT_REDUCE_CAP_MIN_BYTES, -1), (d.DDP_OPT_COALESCE, -1), (99, 0)):
+            with pytest.raises(d.DdpError) as e:
+                d.ddp_set_option(ctx, opt, bad)
+            assert e.value.code == d.DDP_ERR_ARG
+        d.ddp_set_option(ctx, d.DDP_OPT_REDUCE_BLOCKS_PER_CU, 0)
+        d.ddp_set_option(ctx, d.DDP_OPT_REDUCE_CAP_MIN_BYTES, 1 << 40)
         for bad in (0, -1, 9):
             with pytest.raises(d.DdpError) as e:
                 d.ddp_set_option(ctx, d.DDP_OPT_REDUCE_STREAMS, bad)
