@@ -89,6 +89,8 @@ def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup
             lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_STREAMS, args.streams)
         if args.blocks_per_cu is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_BLOCKS_PER_CU, args.blocks_per_cu)
+        if args.copy_blocks_per_cu is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_COPY_BLOCKS_PER_CU, args.copy_blocks_per_cu)
         if args.cap_min_mib is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_CAP_MIN_BYTES, int(args.cap_min_mib * (1 << 20)))
         if args.pair_min_mib is not None:
@@ -155,6 +157,12 @@ def main() -> int:
     ap.add_argument("--blocks-per-cu", type=int, default=None,
                     help="reduce kernels: resident thread blocks per compute unit "
                          "(DDP_OPT_REDUCE_BLOCKS_PER_CU; 0 = no cap)")
+    ap.add_argument("--copy-blocks-per-cu", type=int, default=None,
+                    help="pack / unpack / accumulate kernels: resident blocks per compute unit "
+                         "(DDP_OPT_COPY_BLOCKS_PER_CU; 0 = no cap)")
+    ap.add_argument("--acc-blocks-per-cu", type=int, default=None,
+                    help="accumulate kernel: resident blocks per compute unit "
+                         "(DDP_OPT_ACCUMULATE_BLOCKS_PER_CU; 0 = no cap)")
     ap.add_argument("--cap-min-mib", type=float, default=None,
                     help="launch size from which that cap applies (DDP_OPT_REDUCE_CAP_MIN_BYTES)")
     ap.add_argument("--copy-nt-store", action="store_true",
@@ -339,6 +347,8 @@ def main() -> int:
         micro = harness.DeviceGrads(numel, [dtype] * n, R, fill=0)
         ptrs = micro.ptrs()
         with harness.Session(grads, cap, codes[args.pipeline]) as s:
+            if args.acc_blocks_per_cu is not None:
+                lib.ddp_set_option(s.ctx, lib.DDP_OPT_ACCUMULATE_BLOCKS_PER_CU, args.acc_blocks_per_cu)
             for _ in range(2):
                 lib.ddp_no_sync_accumulate(s.ctx, ptrs)
             lib.ddp_synchronize(s.ctx)

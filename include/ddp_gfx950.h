@@ -120,6 +120,12 @@ typedef struct ddp_ctx ddp_ctx;
                                      bytes of bucket data (measured: it gains 1 to 2.5 points of
                                      HBM peak from 50 MiB up and loses 1.5 to 3 on launches of 25
                                      MiB and less).  Default 40 MiB */
+#define DDP_OPT_COPY_BLOCKS_PER_CU 15 /* any time: the same kind of cap for the pack and unpack kernels,
+                                     which keep only one or two loads per thread in flight and want
+                                     many blocks (measured: no gain from any cap, a quarter of the
+                                     rate lost at 2 or 3).  Default 0 = no cap */
+#define DDP_OPT_ACCUMULATE_BLOCKS_PER_CU 16 /* any time: likewise for the accumulate kernel (two loads
+                                     and a store per vector; registers allow 8 blocks).  Default 4 */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 

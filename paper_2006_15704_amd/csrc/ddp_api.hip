@@ -58,6 +58,8 @@ struct ddp_ctx {
     int32_t n_streams = 1;                        // reduction streams taken in turn by the launches
     int32_t blocks_per_cu = 2;                    // reduce kernels: resident blocks per compute unit (0 = no cap)
     int64_t cap_min_bytes = int64_t(40) << 20;    // ... applied to launches of at least this many bytes
+    int32_t copy_blocks_per_cu = 0;               // pack / unpack kernels: the same kind of cap (0 = none)
+    int32_t acc_blocks_per_cu = 4;                // accumulate kernel: likewise
     int64_t lds_per_cu = 160 * 1024;              // read from the device at creation
 
     bool registered = false, built = false;
@@ -142,6 +144,12 @@ unsigned occupancy_lds(const ddp_ctx* c, int64_t launch_bytes) {
     if (c->blocks_per_cu <= 0 || launch_bytes < c->cap_min_bytes) return 0;
     return static_cast<unsigned>((c->lds_per_cu / c->blocks_per_cu) & ~int64_t(1023));
 }
+
+unsigned lds_for_blocks(const ddp_ctx* c, int32_t blocks) {
+    if (blocks <= 0) return 0;
+    return static_cast<unsigned>((c->lds_per_cu / blocks) & ~int64_t(1023));
+}
+unsigned copy_lds(const ddp_ctx* c) { return lds_for_blocks(c, c->copy_blocks_per_cu); }
 
 ddp::Scale make_scale(int R) {
     ddp::Scale sc;
@@ -267,7 +275,7 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
         const int64_t nvec = (c->bucket_slab_off[last] - c->bucket_slab_off[first]) / 16 + c->bucket_vecs[last];
         if ((rc = timed_begin(c, DDP_K_PACK, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_pack(c->tables, tile_base, ntiles, c->slabs, c->slab_stride, c->R,
-                                   d_flags, c->copy_nt_store != 0, 0, st));
+                                   d_flags, c->copy_nt_store != 0, copy_lds(c), st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_flat_reduce(bf.dtype, in0, c->slab_stride, out, nvec, c->R, sc,
@@ -465,6 +473,14 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
         case DDP_OPT_REDUCE_BLOCKS_PER_CU:
             if (value < 0 || value > 16) return fail(c, DDP_ERR_ARG, "blocks per compute unit outside [0, 16]");
             c->blocks_per_cu = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_COPY_BLOCKS_PER_CU:
+            if (value < 0 || value > 16) return fail(c, DDP_ERR_ARG, "blocks per compute unit outside [0, 16]");
+            c->copy_blocks_per_cu = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_ACCUMULATE_BLOCKS_PER_CU:
+            if (value < 0 || value > 16) return fail(c, DDP_ERR_ARG, "blocks per compute unit outside [0, 16]");
+            c->acc_blocks_per_cu = static_cast<int32_t>(value);
             return DDP_OK;
         case DDP_OPT_REDUCE_CAP_MIN_BYTES:
             if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
@@ -886,7 +902,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             HIPCHK(c, ddp::launch_unpack(c->tables, 0, c->h_tile0[n],
                                          c->slabs + static_cast<int64_t>(c->R) * c->slab_stride,
                                          c->write_all ? c->R : 1, c->iter_zero ? c->d_global : nullptr,
-                                         c->find_unused != 0, c->copy_nt_store != 0, 0, c->reduce));
+                                         c->find_unused != 0, c->copy_nt_store != 0, copy_lds(c), c->reduce));
             if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
         }
         if (c->backward != c->reduce) {
@@ -978,7 +994,8 @@ int32_t ddp_no_sync_accumulate(ddp_ctx* c, void* const* micro) {
     size_t slot;
     int32_t rc;
     if ((rc = timed_begin(c, DDP_K_ACCUMULATE, -1, c->backward, &slot)) != DDP_OK) return rc;
-    HIPCHK(c, ddp::launch_accumulate(c->tables, c->h_tile0[n], c->R, n, c->d_micro, 0, c->backward));
+    HIPCHK(c, ddp::launch_accumulate(c->tables, c->h_tile0[n], c->R, n, c->d_micro,
+                                     lds_for_blocks(c, c->acc_blocks_per_cu), c->backward));
     if ((rc = timed_end(c, slot, c->backward)) != DDP_OK) return rc;
     for (int32_t i = 0; i < n; ++i) {
         const size_t row = static_cast<size_t>(c->plan.params[i].segment) * R;
