@@ -45,6 +45,8 @@ WORKLOADS = {
     # name: (shape list, config id, R, sigma, dtype code, cap bytes)
     "resnet50": ("resnet50", 2, 8, 1e-2, 0, 25 << 20),
     "bert_large": ("bert_large", 3, 8, 1e-3, 0, 25 << 20),
+    "resnet50_fp16_r16": ("resnet50", 4, 16, 1e-2, 1, 25 << 20),      # the bucket-size sweep's configuration
+    "bert_large_bf16": ("bert_large", 3, 8, 1e-3, 2, 25 << 20),        # diagnostic: 16-bit storage at BERT size
     "tiny": ("tiny", 1, 2, 1.0, 0, 16384),
     "uniform": ("uniform", 9, 8, 1e-2, 0, 25 << 20),     # diagnostic: 40 single-tensor 25 MiB buckets
 }

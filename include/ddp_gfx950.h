@@ -125,7 +125,7 @@ typedef struct ddp_ctx ddp_ctx;
                                      many blocks (measured: no gain from any cap, a quarter of the
                                      rate lost at 2 or 3).  Default 0 = no cap */
 #define DDP_OPT_ACCUMULATE_BLOCKS_PER_CU 16 /* any time: likewise for the accumulate kernel (two loads
-                                     and a store per vector; registers allow 8 blocks).  Default 4 */
+                                     and a store per vector; registers allow 8 blocks).  Default 5 */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 

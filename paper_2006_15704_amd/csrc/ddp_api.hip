@@ -59,7 +59,7 @@ struct ddp_ctx {
     int32_t blocks_per_cu = 2;                    // reduce kernels: resident blocks per compute unit (0 = no cap)
     int64_t cap_min_bytes = int64_t(40) << 20;    // ... applied to launches of at least this many bytes
     int32_t copy_blocks_per_cu = 0;               // pack / unpack kernels: the same kind of cap (0 = none)
-    int32_t acc_blocks_per_cu = 4;                // accumulate kernel: likewise
+    int32_t acc_blocks_per_cu = 5;                // accumulate kernel: likewise
     int64_t lds_per_cu = 160 * 1024;              // read from the device at creation
 
     bool registered = false, built = false;
