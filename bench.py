@@ -89,6 +89,8 @@ def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup
                                (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * (1 << 20)))
         if args.streams is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_STREAMS, args.streams)
+        if args.tail_on_backward is not None:
+            lib.ddp_set_option(ctx, lib.DDP_OPT_TAIL_ON_BACKWARD, args.tail_on_backward)
         if args.blocks_per_cu is not None:
             lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_BLOCKS_PER_CU, args.blocks_per_cu)
         if args.copy_blocks_per_cu is not None:
@@ -156,6 +158,9 @@ def main() -> int:
                          "default: the library's, 100 MiB)")
     ap.add_argument("--streams", type=int, default=None,
                     help="reduction streams taken in turn by the bucket launches (DDP_OPT_REDUCE_STREAMS)")
+    ap.add_argument("--tail-on-backward", type=int, default=None, choices=[0, 1],
+                    help="DDP_OPT_TAIL_ON_BACKWARD: 1 (library default) = the launches of the call that "
+                         "completes an iteration go to the backward stream; 0 = always a reduction stream")
     ap.add_argument("--blocks-per-cu", type=int, default=None,
                     help="reduce kernels: resident thread blocks per compute unit "
                          "(DDP_OPT_REDUCE_BLOCKS_PER_CU; 0 = no cap)")
@@ -313,11 +318,13 @@ def main() -> int:
         }
 
     if args.pipeline == "fused" and args.coalesce_mib is None and not args.no_coalesce_leg:
-        # the same steps with one launch per bucket (DDP_OPT_COALESCE = 0), as when the ready marks
-        # arrive in separate calls during a real backward pass
+        # the same steps with one launch per bucket on the reduction stream (DDP_OPT_COALESCE = 0,
+        # DDP_OPT_TAIL_ON_BACKWARD = 0), as when the ready marks arrive in separate calls during a
+        # real backward pass
         args.coalesce_mib = 0.0
+        keep_tail, args.tail_on_backward = args.tail_on_backward, 0
         pb = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
-        args.coalesce_mib = None
+        args.coalesce_mib, args.tail_on_backward = None, keep_tail
         pb_ms, pb_launches = pb["iteration"]
         out["one_launch_per_bucket"] = {
             "ms_per_step": round(pb["ms_per_step"], 4),
@@ -333,8 +340,9 @@ def main() -> int:
         # whole has a duration
         args.streams = 2
         keep_coalesce, args.coalesce_mib = args.coalesce_mib, 0.0
+        keep_tail, args.tail_on_backward = args.tail_on_backward, 0
         rr = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
-        args.streams, args.coalesce_mib = None, keep_coalesce
+        args.streams, args.coalesce_mib, args.tail_on_backward = None, keep_coalesce, keep_tail
         rr_ms, _ = rr["iteration"]
         out["two_streams"] = {
             "ms_per_step": round(rr["ms_per_step"], 4),

@@ -126,6 +126,15 @@ typedef struct ddp_ctx ddp_ctx;
                                      rate lost at 2 or 3).  Default 0 = no cap */
 #define DDP_OPT_ACCUMULATE_BLOCKS_PER_CU 16 /* any time: likewise for the accumulate kernel (two loads
                                      and a store per vector; registers allow 8 blocks).  Default 5 */
+#define DDP_OPT_TAIL_ON_BACKWARD 17 /* any time between iterations: 1 (default) = the buckets launched by
+                                     the API call that completes an iteration (the call after which
+                                     the last bucket is launchable: every gradient exists, nothing
+                                     of the backward pass is left to overlap with) are enqueued on
+                                     backward_stream instead of a reduction stream, fused pipeline
+                                     only.  Stream order then replaces the cross-stream event, whose
+                                     hand-over takes about 0.2 ms on this system when the waiting
+                                     queue was armed long before the event fires.  0 = every bucket
+                                     goes to a reduction stream */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 
@@ -224,7 +233,8 @@ int32_t ddp_get_bucket_ptr(const ddp_ctx* ctx, int32_t b, int32_t r, void** ptr)
 /* Algorithm 1, autograd_hook(param_index), with the pending counts of
  * Section 4.2: records that all R replica gradients of `param_id` have been
  * produced by work already enqueued on backward_stream, decrements the
- * bucket's pending count, and launches on reduce_stream, in bucket order,
+ * bucket's pending count, and launches on reduce_stream (see also
+ * DDP_OPT_REDUCE_STREAMS and DDP_OPT_TAIL_ON_BACKWARD), in bucket order,
  * every bucket that is complete and whose predecessors have all been launched
  * (Section 3.2.3: no bucket i+1 before bucket i).  A launch first makes
  * reduce_stream wait for backward_stream's work enqueued so far, then copies

@@ -38,7 +38,7 @@ DDP_OPT_REDUCE_BLOCKS, DDP_OPT_NONTEMPORAL, DDP_OPT_REDUCE_UNROLL = 4, 5, 6
 DDP_OPT_PAIR_MIN_BYTES, DDP_OPT_EMIT_BUSY_BLOCKS, DDP_OPT_COPY_NT_STORE = 7, 8, 9
 DDP_OPT_COALESCE, DDP_OPT_FIND_UNUSED, DDP_OPT_REDUCE_STREAMS = 10, 11, 12
 DDP_OPT_REDUCE_BLOCKS_PER_CU, DDP_OPT_REDUCE_CAP_MIN_BYTES, DDP_OPT_COPY_BLOCKS_PER_CU = 13, 14, 15
-DDP_OPT_ACCUMULATE_BLOCKS_PER_CU = 16
+DDP_OPT_ACCUMULATE_BLOCKS_PER_CU, DDP_OPT_TAIL_ON_BACKWARD = 16, 17
 DDP_PIPELINE_STAGED, DDP_PIPELINE_FUSED = 0, 1
 DDP_K_PACK, DDP_K_REDUCE, DDP_K_UNPACK, DDP_K_ACCUMULATE, DDP_K_ITERATION = 0, 1, 2, 3, 4
 

@@ -56,6 +56,7 @@ struct ddp_ctx {
     static constexpr int64_t kPairMinTilesPerSegment = 256;   // ... if their tensors are large on average
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
     int32_t n_streams = 1;                        // reduction streams taken in turn by the launches
+    int32_t tail_on_backward = 1;                 // the call that completes an iteration launches on the backward stream
     int32_t blocks_per_cu = 2;                    // reduce kernels: resident blocks per compute unit (0 = no cap)
     int64_t cap_min_bytes = int64_t(40) << 20;    // ... applied to launches of at least this many bytes
     int32_t copy_blocks_per_cu = 0;               // pack / unpack kernels: the same kind of cap (0 = none)
@@ -198,7 +199,7 @@ void new_call(ddp_ctx* c) {
 // Enqueue on a reduction stream everything buckets [first, last] need, as one
 // launch per kernel.  The buckets are consecutive, hold one element type, and
 // their tiles and slab ranges are contiguous.
-int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
+int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) {
     const ddp::BucketInfo& bf = c->plan.buckets[first];
     const ddp::BucketInfo& bl = c->plan.buckets[last];
     const int seg_begin = bf.seg_begin;
@@ -208,10 +209,16 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last) {
     int64_t bytes = 0;
     for (int32_t b = first; b <= last; ++b) bytes += static_cast<int64_t>(c->plan.buckets[b].bytes());
     const int32_t id = first + 65536 * (last - first);
-    // the launches of an iteration take the reduction streams in turn
-    const int lane = static_cast<int>(c->launches_in_iter++ % c->n_streams);
-    const hipStream_t st = c->lane[lane];
-    c->lane_used[lane] = true;
+    // The launches of an iteration take the reduction streams in turn -- except
+    // those of the API call that completes the iteration (see flush_deferred),
+    // which go to the backward stream itself.
+    int lane = -1;
+    hipStream_t st = c->backward;
+    if (!on_backward) {
+        lane = static_cast<int>(c->launches_in_iter++ % c->n_streams);
+        st = c->lane[lane];
+        c->lane_used[lane] = true;
+    }
     if (st != c->backward && !c->lane_ordered[lane]) {
         // Order the buckets after the gradient-producing work enqueued so far.
         // If the backward stream has already drained there is nothing to wait
@@ -307,6 +314,15 @@ int32_t flush_deferred(ddp_ctx* c) {
     todo.swap(c->deferred);
     if (c->plan_only) return DDP_OK;
     HIPCHK(c, hipSetDevice(c->device));
+    // Buckets are launched in index order, so if the last bucket is among the
+    // ones this API call launches, every gradient of the iteration has been
+    // produced and the backward stream has nothing left to overlap with.  The
+    // call's launches then go to the backward stream: stream order replaces
+    // the cross-stream event, whose hand-over costs about 0.2 ms here when the
+    // waiting queue was armed long before the event fires.  (The staged
+    // pipeline keeps its flat buffers and unpack on the reduction stream.)
+    const bool closing = c->tail_on_backward != 0 && c->pipeline == DDP_PIPELINE_FUSED &&
+                         todo.back() == static_cast<int32_t>(c->plan.buckets.size()) - 1;
     size_t i = 0;
     while (i < todo.size()) {
         size_t j = i;
@@ -319,7 +335,7 @@ int32_t flush_deferred(ddp_ctx* c) {
                 ++j;
             }
         }
-        const int32_t st = launch_range(c, todo[i], todo[j]);
+        const int32_t st = launch_range(c, todo[i], todo[j], closing);
         if (st != DDP_OK) return st;
         i = j + 1;
     }
@@ -485,6 +501,9 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
         case DDP_OPT_REDUCE_CAP_MIN_BYTES:
             if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
             c->cap_min_bytes = value;
+            return DDP_OK;
+        case DDP_OPT_TAIL_ON_BACKWARD:
+            c->tail_on_backward = value != 0;
             return DDP_OK;
         case DDP_OPT_REDUCE_STREAMS:
             if (value < 1 || value > ddp_ctx::kMaxLanes)
@@ -866,20 +885,18 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     }
     if (!c->plan_only) {
         // every reduction stream that received work in this iteration joins the caller's
+        bool reduce_side_used = c->lane_used[0];
         for (int l = 1; l < ddp_ctx::kMaxLanes; ++l)
             if (c->lane_used[l]) {
                 HIPCHK(c, hipEventRecord(c->ev_join[l], c->lane[l]));
                 HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_join[l], 0));
+                reduce_side_used = true;
             }
-        if (c->open_group != static_cast<size_t>(-1)) {      // closes this iteration's bucket launches
-            HIPCHK(c, hipEventRecord(c->timed[c->open_group].stop, c->reduce));
-            c->open_group = static_cast<size_t>(-1);
-        }
+        const int par = static_cast<int>(c->iteration & 1);
         if (c->iter_zero) {
             // The bitmap step of Section 4.2: the host bitmap goes to the device
             // with a non-blocking copy and one extra reduction (an OR over the
             // replicas) yields the parameters that somebody used.
-            const int par = static_cast<int>(c->iteration & 1);
             if (c->pin_ready_iter != c->iteration) {
                 if (c->local_in_flight[par]) HIPCHK(c, hipEventSynchronize(c->ev_local[par]));
                 c->pin_ready_iter = c->iteration;
@@ -887,13 +904,12 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             const size_t flag_bytes = static_cast<size_t>(n) * c->R;
             std::memcpy(c->h_local[par], c->local_cur.data(), flag_bytes);
             HIPCHK(c, hipMemcpyAsync(c->d_local, c->h_local[par], flag_bytes, hipMemcpyHostToDevice, c->reduce));
-            HIPCHK(c, hipEventRecord(c->ev_local[par], c->reduce));
-            c->local_in_flight[par] = true;
             HIPCHK(c, ddp::launch_bitmap_or(c->d_local, c->d_global, n, c->R, c->reduce));
             if (c->global_in_flight) HIPCHK(c, hipEventSynchronize(c->ev_global));
             HIPCHK(c, hipMemcpyAsync(c->h_global, c->d_global, static_cast<size_t>(n), hipMemcpyDeviceToHost, c->reduce));
             HIPCHK(c, hipEventRecord(c->ev_global, c->reduce));
             c->global_in_flight = true;
+            reduce_side_used = true;
         }
         if (c->pipeline == DDP_PIPELINE_STAGED) {
             size_t slot;
@@ -904,10 +920,21 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
                                          c->write_all ? c->R : 1, c->iter_zero ? c->d_global : nullptr,
                                          c->find_unused != 0, c->copy_nt_store != 0, copy_lds(c), c->reduce));
             if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
+            reduce_side_used = true;
         }
-        if (c->backward != c->reduce) {
+        // the backward stream waits for whatever ran on the reduction side
+        if (c->backward != c->reduce && reduce_side_used) {
             HIPCHK(c, hipEventRecord(c->ev_done, c->reduce));
             HIPCHK(c, hipStreamWaitEvent(c->backward, c->ev_done, 0));
+        }
+        // from here on the backward stream is behind everything of this iteration
+        if (c->pin_ready_iter == c->iteration) {      // the flag staging buffer was used: free for reuse after this
+            HIPCHK(c, hipEventRecord(c->ev_local[par], c->backward));
+            c->local_in_flight[par] = true;
+        }
+        if (c->open_group != static_cast<size_t>(-1)) {      // closes this iteration's bucket launches
+            HIPCHK(c, hipEventRecord(c->timed[c->open_group].stop, c->backward));
+            c->open_group = static_cast<size_t>(-1);
         }
     }
     c->log_closed.swap(c->log_running);

@@ -14,7 +14,11 @@ For every cap and delay the script reports
     t_total      backward with ready marks + finalize, until the averaged
                  gradients are complete
 (all three are GPU times between two events on the backward stream)
-    exposed      t_total - t_backward: synchronization time not hidden
+    exposed      the part of t_total after the backward stream's own kernels have
+                 ended (an event between the backward pass and finalize):
+                 synchronization time not hidden
+    slowdown     t_total - exposed - t_backward: how much the ready marks and the
+                 concurrent reductions lengthen the backward pass itself
     overlap      1 - exposed / t_sync
 one JSON object per line.  Run:  python -m paper_2006_15704_amd.sweep
 """
@@ -52,6 +56,27 @@ def timed(fn, sync, reps, torch, stream):
         b.synchronize()
         out.append(a.elapsed_time(b))
     return statistics.median(out)
+
+
+def timed_exposed(backward, finalize, sync, reps, torch, stream):
+    """Median GPU times of backward() followed by finalize(): the whole thing,
+    and the part after the backward stream's own work has ended (an event
+    between the two calls), i.e. the synchronization time that was not hidden,
+    measured directly instead of as a difference of two long intervals."""
+    total, exposed = [], []
+    for _ in range(reps):
+        sync()
+        a, m, b = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        a.record(stream)
+        backward()
+        m.record(stream)
+        finalize()
+        b.record(stream)
+        sync()
+        b.synchronize()
+        total.append(a.elapsed_time(b))
+        exposed.append(m.elapsed_time(b))
+    return statistics.median(total), statistics.median(exposed)
 
 
 def main() -> int:
@@ -144,13 +169,15 @@ def main() -> int:
                         def backward_alone():
                             lib.ddp_synth_backward(ctx, order, dl, src_ptrs, False)
 
-                        def backward_and_sync():
+                        def backward_with_marks():
                             lib.ddp_synth_backward(ctx, order, dl, src_ptrs, True)
+
+                        def finalize():
                             lib.ddp_finalize_backward(ctx)
 
                         t_bwd = timed(backward_alone, sync, args.reps, torch, s.backward_stream) if (d_us > 0 or src_ptrs) else 0.0
-                        t_tot = timed(backward_and_sync, sync, args.reps, torch, s.backward_stream)
-                        exposed = t_tot - t_bwd
+                        t_tot, exposed = timed_exposed(backward_with_marks, finalize, sync, args.reps, torch,
+                                                       s.backward_stream)
                         print(json.dumps({
                             "workload": args.workload, "dtype": args.dtype, "R": R, "pipeline": pipe,
                             "cap_mib": cap_mib, "n_buckets": n_buckets, "streams": n_streams,
@@ -160,6 +187,7 @@ def main() -> int:
                             "backward_writes_gradients": bool(src_ptrs), "busy_blocks": args.busy_blocks,
                             "t_backward_ms": round(t_bwd, 4), "t_sync_ms": round(t_sync, 4),
                             "t_total_ms": round(t_tot, 4), "exposed_ms": round(exposed, 4),
+                            "backward_slowdown_ms": round(t_tot - exposed - t_bwd, 4),
                             "overlap": round(1.0 - exposed / t_sync, 3) if t_sync > 0 else None,
                             "sync_gbps_alg": round((R + 1) * B / t_sync / 1e6, 1),
                         }), flush=True)

@@ -321,7 +321,8 @@ def test_no_sync_accumulation_then_one_reduction(pipeline, dtype):
 
 # ---- overlap plumbing: the reduction must wait for the backward stream ------------------
 @pytest.mark.parametrize("pipeline", [STAGED, FUSED])
-def test_reduction_waits_for_gradients_produced_on_the_backward_stream(pipeline):
+@pytest.mark.parametrize("tail_on_backward", [1, 0])
+def test_reduction_waits_for_gradients_produced_on_the_backward_stream(pipeline, tail_on_backward):
     """Gradient memory starts as NaN; the synthetic backward stream writes the
     real gradients after a delay, parameter by parameter, and marks them ready.
     Any reduction that ran ahead of its inputs would average NaNs."""
@@ -335,6 +336,7 @@ def test_reduction_waits_for_gradients_produced_on_the_backward_stream(pipeline)
         src.upload_replica(r, reps[r])
     want, _, _ = oracle.synchronize(numel, [FP32] * 8, 16384, reps)
     with harness.Session(grads, 16384, pipeline) as s:
+        d.ddp_set_option(s.ctx, d.DDP_OPT_TAIL_ON_BACKWARD, tail_on_backward)
         order = list(range(7, -1, -1))
         d.ddp_synth_backward(s.ctx, order, [200_000] * 8, src.ptrs(), True)
         d.ddp_finalize_backward(s.ctx)
@@ -415,7 +417,8 @@ def test_round_robin_reduction_streams_give_the_same_results(pipeline, streams):
     numel = [int(x) for x in rng.integers(0, 6000, size=n)]
     reps = gaussian_reps(17, numel, R, 1e-2)
     order = [int(p) for p in rng.permutation(n)][: n - 5]
-    for extra in ((), ((d.DDP_OPT_COALESCE, 40000),), ((d.DDP_OPT_TIMING, 1),), ((d.DDP_OPT_TIMING, 2),)):
+    for extra in ((), ((d.DDP_OPT_COALESCE, 40000),), ((d.DDP_OPT_TIMING, 1),), ((d.DDP_OPT_TIMING, 2),),
+                  ((d.DDP_OPT_TAIL_ON_BACKWARD, 0),), ((d.DDP_OPT_TAIL_ON_BACKWARD, 0), (d.DDP_OPT_TIMING, 2))):
         run_sync(numel, [FP32] * n, reps, 12000, pipeline, order=order, one_by_one=not extra,
                  write_all=True, options=((d.DDP_OPT_REDUCE_STREAMS, streams),) + extra)
 

@@ -297,6 +297,7 @@ def test_participation_with_several_reduction_streams(pipeline):
         d.ddp_set_option(s.ctx, d.DDP_OPT_REDUCE_STREAMS, 3)
         d.ddp_set_option(s.ctx, d.DDP_OPT_FIND_UNUSED, 1)
         for it in range(4):
+            d.ddp_set_option(s.ctx, d.DDP_OPT_TAIL_ON_BACKWARD, it & 1)
             rng = np.random.default_rng(81 + it)
             order = [int(p) for p in rng.permutation(n)][: n - 3]
             marks = [(p, [int(rng.random() < 0.6) for _ in range(R)]) for p in order]
