@@ -118,6 +118,7 @@ struct ddp_ctx {
     bool lane_used[kMaxLanes] = {};               // lane received work in the running iteration
     bool lane_ordered[kMaxLanes] = {};            // lane already waits for ev_call in the running API call
     int64_t launches_in_iter = 0;
+    bool tail_used = false;                       // some launch of the running iteration went to the backward stream
     bool backward_idle_in_call = false;           // backward stream was found drained in this API call
     bool ordered_in_call = false;   // backward stream position of this API call already examined
     std::vector<int32_t> deferred;  // buckets made launchable by the running API call, not yet enqueued
@@ -218,6 +219,8 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
         lane = static_cast<int>(c->launches_in_iter++ % c->n_streams);
         st = c->lane[lane];
         c->lane_used[lane] = true;
+    } else {
+        c->tail_used = true;
     }
     if (st != c->backward && !c->lane_ordered[lane]) {
         // Order the buckets after the gradient-producing work enqueued so far.
@@ -892,6 +895,12 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
                 HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_join[l], 0));
                 reduce_side_used = true;
             }
+        // the interval of this iteration's bucket launches ends here if all of them ran on the
+        // reduction side, else on the backward stream below
+        if (c->open_group != static_cast<size_t>(-1) && !c->tail_used) {
+            HIPCHK(c, hipEventRecord(c->timed[c->open_group].stop, c->reduce));
+            c->open_group = static_cast<size_t>(-1);
+        }
         const int par = static_cast<int>(c->iteration & 1);
         if (c->iter_zero) {
             // The bitmap step of Section 4.2: the host bitmap goes to the device
@@ -956,6 +965,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     c->iter_zero = false;
     for (bool& b : c->lane_used) b = false;
     c->launches_in_iter = 0;
+    c->tail_used = false;
     ++c->iteration;
     c->tracker.new_iteration();
     return DDP_OK;

@@ -14,11 +14,10 @@ For every cap and delay the script reports
     t_total      backward with ready marks + finalize, until the averaged
                  gradients are complete
 (all three are GPU times between two events on the backward stream)
-    exposed      the part of t_total after the backward stream's own kernels have
-                 ended (an event between the backward pass and finalize):
-                 synchronization time not hidden
-    slowdown     t_total - exposed - t_backward: how much the ready marks and the
-                 concurrent reductions lengthen the backward pass itself
+    exposed      t_total - t_backward: synchronization time not hidden
+    after_marks  the part of t_total after everything ddp_synth_backward enqueued
+                 on the backward stream (an event between it and finalize); with
+                 DDP_OPT_TAIL_ON_BACKWARD that includes the last buckets
     overlap      1 - exposed / t_sync
 one JSON object per line.  Run:  python -m paper_2006_15704_amd.sweep
 """
@@ -60,9 +59,8 @@ def timed(fn, sync, reps, torch, stream):
 
 def timed_exposed(backward, finalize, sync, reps, torch, stream):
     """Median GPU times of backward() followed by finalize(): the whole thing,
-    and the part after the backward stream's own work has ended (an event
-    between the two calls), i.e. the synchronization time that was not hidden,
-    measured directly instead of as a difference of two long intervals."""
+    and the part after everything backward() enqueued on the stream (an event
+    between the two calls)."""
     total, exposed = [], []
     for _ in range(reps):
         sync()
@@ -176,8 +174,9 @@ def main() -> int:
                             lib.ddp_finalize_backward(ctx)
 
                         t_bwd = timed(backward_alone, sync, args.reps, torch, s.backward_stream) if (d_us > 0 or src_ptrs) else 0.0
-                        t_tot, exposed = timed_exposed(backward_with_marks, finalize, sync, args.reps, torch,
-                                                       s.backward_stream)
+                        t_tot, after_marks = timed_exposed(backward_with_marks, finalize, sync, args.reps, torch,
+                                                           s.backward_stream)
+                        exposed = t_tot - t_bwd
                         print(json.dumps({
                             "workload": args.workload, "dtype": args.dtype, "R": R, "pipeline": pipe,
                             "cap_mib": cap_mib, "n_buckets": n_buckets, "streams": n_streams,
@@ -187,7 +186,7 @@ def main() -> int:
                             "backward_writes_gradients": bool(src_ptrs), "busy_blocks": args.busy_blocks,
                             "t_backward_ms": round(t_bwd, 4), "t_sync_ms": round(t_sync, 4),
                             "t_total_ms": round(t_tot, 4), "exposed_ms": round(exposed, 4),
-                            "backward_slowdown_ms": round(t_tot - exposed - t_bwd, 4),
+                            "after_marks_ms": round(after_marks, 4),
                             "overlap": round(1.0 - exposed / t_sync, 3) if t_sync > 0 else None,
                             "sync_gbps_alg": round((R + 1) * B / t_sync / 1e6, 1),
                         }), flush=True)
