@@ -294,6 +294,11 @@ def main() -> int:
             "avg_launch_ms": round(avg_launch_ms, 5),
             "launches": launches,
             "timing": "HIP event pair per " + timing,
+            "interval_ms": ({"median": round(float(np.median(iter_ms)), 5), "min": round(float(iter_ms.min()), 5),
+                             "max": round(float(iter_ms.max()), 5), "what": "one iteration's launches"}
+                            if timing == "iteration" and len(iter_ms) else
+                            {"median": round(float(np.median(red_ms)), 5), "min": round(float(red_ms.min()), 5),
+                             "max": round(float(red_ms.max()), 5), "what": "one launch"} if len(red_ms) else None),
             "algorithmic_bytes_per_launch": round(total_alg / max(launches, 1)),
             "traffic": read_traffic(args.workload, args.pipeline),
         },
@@ -326,7 +331,18 @@ def main() -> int:
         pb = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
         args.coalesce_mib, args.tail_on_backward = None, keep_tail
         pb_ms, pb_launches = pb["iteration"]
+        per_bucket_gbps = None
+        if n_buckets <= 64:
+            # a few more steps with one event pair per launch: the rate of every bucket
+            args.coalesce_mib, args.tail_on_backward = 0.0, 0
+            pl = measure(lib, harness, torch, grads, cap, codes["fused"], order, max(5, args.steps // 5), 2, "launch", args)
+            args.coalesce_mib, args.tail_on_backward = None, keep_tail
+            l_ms, l_ids = pl["reduce"]
+            per_bucket_gbps = {str(b): round((R + 1) * bucket_elems[b] * es / float(np.median(l_ms[l_ids == b])) / 1e6, 1)
+                               for b in range(n_buckets) if (l_ids == b).any()}
         out["one_launch_per_bucket"] = {
+            "reduce_gbps_per_bucket": per_bucket_gbps,
+            "per_bucket_note": "median over steps, one HIP event pair per launch (the pair adds about 3 us to each)",
             "ms_per_step": round(pb["ms_per_step"], 4),
             "value_gbps": round((R + W) * B / pb["ms_per_step"] / 1e6, 1),
             "launches_per_step": int(pb_launches.sum()) // args.steps,
