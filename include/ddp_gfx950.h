@@ -20,7 +20,8 @@
  *     call returns.  Gradient memory is owned by the caller and borrowed until
  *     ddp_destroy; bucket storage is owned by the library.
  *   - Streams are hipStream_t values passed as void* (NULL = the null stream).
- *     The library creates no streams of its own and never changes priorities.
+ *     The library creates streams of its own only when DDP_OPT_REDUCE_STREAMS
+ *     asks for more than one reduction stream, at the default priority.
  *   - A context is not thread-safe (the paper's hooks fire from one autograd
  *     thread).  Different contexts may be used from different threads.
  *   - All compute calls are asynchronous with respect to the host unless
