@@ -13,6 +13,7 @@
 
 #include <mutex>
 #include <set>
+#include <utility>
 
 namespace ddp {
 namespace {
@@ -731,19 +732,25 @@ inline hipError_t after_launch() { return hipGetLastError(); }
 // dynamic LDS that no kernel touches cap the number of resident blocks
 // (a CU has 160 KiB of LDS): 0 = no cap.
 constexpr unsigned kLdsNoOptIn = 64 * 1024;
+constexpr unsigned kLdsPerUnit = 160 * 1024;     // gfx950
 
 template <typename... KArgs, typename... Args>
 static hipError_t launch(void (*kernel)(KArgs...), dim3 grid, unsigned lds, hipStream_t s, Args... args) {
     if (lds > kLdsNoOptIn) {
         // allocations above 64 KiB must be allowed per kernel; once is enough
+        // (per device: the attribute belongs to the kernel's code object on the current device)
         static std::mutex mu;
-        static std::set<const void*> raised;
+        static std::set<std::pair<int, const void*>> raised;
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const std::pair<int, const void*> key(dev, reinterpret_cast<const void*>(kernel));
         std::lock_guard<std::mutex> lock(mu);
-        if (raised.find(reinterpret_cast<const void*>(kernel)) == raised.end()) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (raised.find(key) == raised.end()) {
+            e = hipFuncSetAttribute(key.second, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    static_cast<int>(kLdsPerUnit));
             if (e != hipSuccess) return e;
-            raised.insert(reinterpret_cast<const void*>(kernel));
+            raised.insert(key);
         }
     }
     hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), lds, s, static_cast<KArgs>(args)...);
