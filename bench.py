@@ -47,6 +47,7 @@ WORKLOADS = {
     "bert_large": ("bert_large", 3, 8, 1e-3, 0, 25 << 20),
     "resnet50_fp16_r16": ("resnet50", 4, 16, 1e-2, 1, 25 << 20),      # the bucket-size sweep's configuration
     "bert_large_bf16": ("bert_large", 3, 8, 1e-3, 2, 25 << 20),        # diagnostic: 16-bit storage at BERT size
+    "bert_large_r32": ("bert_large", 5, 32, 1e-3, 0, 25 << 20),        # configuration 5's reduction (R = 32)
     "tiny": ("tiny", 1, 2, 1.0, 0, 16384),
     "uniform": ("uniform", 9, 8, 1e-2, 0, 25 << 20),     # diagnostic: 40 single-tensor 25 MiB buckets
 }
@@ -182,6 +183,8 @@ def main() -> int:
                          "launches (default for fused, where they are the only kernels)")
     ap.add_argument("--cap-mib", type=float, default=None,
                     help="override the bucket cap (MiB; negative = whole model)")
+    ap.add_argument("--replicas", type=int, default=None,
+                    help="diagnostic: override the workload's number of replicas R")
     ap.add_argument("--uniform", default=None,
                     help="diagnostic workload 'count,elems': that many equal tensors (with --workload uniform)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -200,6 +203,8 @@ def main() -> int:
     from paper_2006_15704_amd import harness
 
     shape_name, config_id, R, sigma, dtype, cap = WORKLOADS[args.workload]
+    if args.replicas is not None:
+        R = args.replicas
     if args.cap_mib is not None:
         cap = lib.DDP_CAP_WHOLE_MODEL if args.cap_mib < 0 else int(args.cap_mib * (1 << 20))
     if args.workload == "uniform" and args.uniform:

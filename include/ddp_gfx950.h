@@ -93,9 +93,11 @@ typedef struct ddp_ctx ddp_ctx;
                                      element type share ONE launch per kernel as long as the launch
                                      stays within `value` bytes of bucket data (INT64_MAX: no
                                      limit); order and results are unchanged.  0 = one launch per
-                                     bucket.  Default 100 MiB (measured: short launches pay a fixed
-                                     start-up and drain cost each, launches far beyond 100 MiB lose
-                                     throughput again) */
+                                     bucket.  Default -1 = chosen from R so that a launch runs for
+                                     roughly 150 to 300 us (400 MiB for R <= 2, 240 MiB up to 4,
+                                     100 MiB up to 8, 70 MiB up to 16, else 50 MiB; measured: short
+                                     launches pay a fixed start-up and drain cost each, much longer
+                                     ones lose throughput again) */
 #define DDP_OPT_FIND_UNUSED   11  /* any time between iterations: the paper's find_unused_parameters
                                      knob.  1 = gradients of parameters that no replica used in the
                                      iteration (the global bitmap of Section 4.2 says so) are left
@@ -116,7 +118,8 @@ typedef struct ddp_ctx ddp_ctx;
                                      16-byte loads per thread in flight, so two or three blocks per
                                      unit fill the memory system; more only interleave more request
                                      streams at the DRAM channels and throughput drops.  0 = no cap
-                                     (registers decide: 5, or 3 with paired tiles).  Default 2 */
+                                     (registers decide: 5, or 3 with paired tiles).  Default -1 =
+                                     chosen from R: no cap up to R = 4 (few loads per block), else 2 */
 #define DDP_OPT_REDUCE_CAP_MIN_BYTES 14 /* any time: the cap applies to launches of at least this many
                                      bytes of bucket data (measured: it gains 1 to 2.5 points of
                                      HBM peak from 50 MiB up and loses 1.5 to 3 on launches of 25

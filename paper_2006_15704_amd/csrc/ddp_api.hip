@@ -50,14 +50,15 @@ struct ddp_ctx {
     int32_t nontemporal = 1;
     int32_t unroll = 2;
     int32_t copy_nt_store = 0;
-    int64_t coalesce = int64_t(100) << 20;        // > 0: consecutive buckets of one API call share a
+    int64_t coalesce = -1;                        // > 0: consecutive buckets of one API call share a
                                                   // launch while it stays within this many bytes
     int64_t pair_min_bytes = int64_t(48) << 20;   // launches at least this large use paired tiles ...
     static constexpr int64_t kPairMinTilesPerSegment = 256;   // ... if their tensors are large on average
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
     int32_t n_streams = 1;                        // reduction streams taken in turn by the launches
     int32_t tail_on_backward = 1;                 // the call that completes an iteration launches on the backward stream
-    int32_t blocks_per_cu = 2;                    // reduce kernels: resident blocks per compute unit (0 = no cap)
+    int32_t blocks_per_cu = -1;                   // reduce kernels: resident blocks per compute unit (0 = no cap,
+                                                  // -1 = chosen from R, see auto_blocks_per_cu)
     int64_t cap_min_bytes = int64_t(40) << 20;    // ... applied to launches of at least this many bytes
     int32_t copy_blocks_per_cu = 0;               // pack / unpack kernels: the same kind of cap (0 = none)
     int32_t acc_blocks_per_cu = 5;                // accumulate kernel: likewise
@@ -142,9 +143,33 @@ int32_t fail(ddp_ctx* c, int32_t code, const std::string& msg) {
 
 // Bytes of unused dynamic LDS per block that leave room for exactly
 // blocks_per_cu blocks on a compute unit.
+// Measured on BERT-large-shaped lists (fp32, launches of the size coalesce_limit
+// gives): a block keeps min(R, 8) x 2 loads per thread in flight, so with few
+// replicas many blocks are needed (R = 2: 77 % of the HBM peak without a cap,
+// 67 % with two blocks; R = 3: 72 % with four, 60 % with two); from R = 5 on two
+// blocks are best or close to it (R = 8: 75.6 % against 73.5 % without a cap and
+// 71.6 % with one block; R = 12: 74.9 % against 71.9 % with one).  For R >= 16
+// one block is 1 to 1.5 points better on lists of large tensors (a block runs
+// several eight-replica phases) but 6 points worse on the ResNet-50 list in
+// fp16, whose many small tensors put slow boundary tiles on a unit that then
+// has nothing else to run -- so two it is.
+int32_t auto_blocks_per_cu(int32_t R) { return R <= 4 ? 0 : 2; }
+
+// A launch should run for roughly 150 to 300 us: shorter ones pay their start-up
+// and drain, much longer ones lose throughput again.  Bytes of bucket data per
+// launch that gave the best rate: R = 2: 400 MiB (67 -> 77 % with no cap),
+// R = 4: 240 MiB (76.5 -> 79 %), R = 8: 100 MiB, R = 16: 70 MiB, R = 32: 50 MiB.
+int64_t auto_coalesce(int32_t R) {
+    const int64_t mib = int64_t(1) << 20;
+    return (R <= 2 ? 400 : R <= 4 ? 240 : R <= 8 ? 100 : R <= 16 ? 70 : 50) * mib;
+}
+
+int64_t coalesce_limit(const ddp_ctx* c) { return c->coalesce < 0 ? auto_coalesce(c->R) : c->coalesce; }
+
 unsigned occupancy_lds(const ddp_ctx* c, int64_t launch_bytes) {
-    if (c->blocks_per_cu <= 0 || launch_bytes < c->cap_min_bytes) return 0;
-    return static_cast<unsigned>((c->lds_per_cu / c->blocks_per_cu) & ~int64_t(1023));
+    const int32_t blocks = c->blocks_per_cu < 0 ? auto_blocks_per_cu(c->R) : c->blocks_per_cu;
+    if (blocks <= 0 || launch_bytes < c->cap_min_bytes) return 0;
+    return static_cast<unsigned>((c->lds_per_cu / blocks) & ~int64_t(1023));
 }
 
 unsigned lds_for_blocks(const ddp_ctx* c, int32_t blocks) {
@@ -329,11 +354,12 @@ int32_t flush_deferred(ddp_ctx* c) {
     size_t i = 0;
     while (i < todo.size()) {
         size_t j = i;
-        if (c->coalesce > 0) {
+        const int64_t limit = coalesce_limit(c);
+        if (limit > 0) {
             uint64_t bytes = c->plan.buckets[todo[i]].bytes();
             while (j + 1 < todo.size() && todo[j + 1] == todo[j] + 1 &&
                    c->plan.buckets[todo[j + 1]].dtype == c->plan.buckets[todo[i]].dtype &&
-                   bytes + c->plan.buckets[todo[j + 1]].bytes() <= static_cast<uint64_t>(c->coalesce)) {
+                   bytes + c->plan.buckets[todo[j + 1]].bytes() <= static_cast<uint64_t>(limit)) {
                 bytes += c->plan.buckets[todo[j + 1]].bytes();
                 ++j;
             }
@@ -490,7 +516,7 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             c->find_unused = value != 0;
             return DDP_OK;
         case DDP_OPT_REDUCE_BLOCKS_PER_CU:
-            if (value < 0 || value > 16) return fail(c, DDP_ERR_ARG, "blocks per compute unit outside [0, 16]");
+            if (value < -1 || value > 16) return fail(c, DDP_ERR_ARG, "blocks per compute unit outside [-1, 16]");
             c->blocks_per_cu = static_cast<int32_t>(value);
             return DDP_OK;
         case DDP_OPT_COPY_BLOCKS_PER_CU:
@@ -525,7 +551,7 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             c->n_streams = static_cast<int32_t>(value);
             return DDP_OK;
         case DDP_OPT_COALESCE:
-            if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
+            if (value < -1) return fail(c, DDP_ERR_ARG, "bad size");
             c->coalesce = value;
             return DDP_OK;
         case DDP_OPT_COPY_NT_STORE:
@@ -823,7 +849,7 @@ static int32_t mark_one(ddp_ctx* c, int32_t param_id, const uint8_t* used) {
     c->order_running.push_back(param_id);
     if (set_participation(c, param_id, used)) c->used_running[param_id] = 1;
     for (int32_t b : launch) note_launch(c, b, c->tracker.marks() - 1);
-    if (c->coalesce <= 0) return flush_deferred(c);
+    if (coalesce_limit(c) <= 0) return flush_deferred(c);
     return DDP_OK;
 }
 

@@ -278,6 +278,24 @@ __device__ __forceinline__ void chunk_interior(BaseFn base_of, int r, const uint
         for (int u = 0; u < U; ++u) add_into<DT>(acc[u], x[i][u]);
 }
 
+// The last `left` (0..7) replicas as ONE chunk, so that all of their loads are
+// in flight together (a 4 + 2 + 1 split would run three dependent phases).
+template <int DT, bool NT, int U, typename BaseFn>
+__device__ __forceinline__ void tail_interior(BaseFn base_of, int r, int left,
+                                              const uint32_t (&lane_off)[U],
+                                              float (&acc)[U][Fmt<DT>::VEC]) {
+    switch (left) {
+        case 7: chunk_interior<DT, NT, 7, U>(base_of, r, lane_off, acc); break;
+        case 6: chunk_interior<DT, NT, 6, U>(base_of, r, lane_off, acc); break;
+        case 5: chunk_interior<DT, NT, 5, U>(base_of, r, lane_off, acc); break;
+        case 4: chunk_interior<DT, NT, 4, U>(base_of, r, lane_off, acc); break;
+        case 3: chunk_interior<DT, NT, 3, U>(base_of, r, lane_off, acc); break;
+        case 2: chunk_interior<DT, NT, 2, U>(base_of, r, lane_off, acc); break;
+        case 1: chunk_interior<DT, NT, 1, U>(base_of, r, lane_off, acc); break;
+        default: break;
+    }
+}
+
 template <int DT, bool NT, int U, typename BaseFn>
 __device__ __forceinline__ void sum_interior(BaseFn base_of, int R, const uint32_t (&lane_off)[U],
                                              float (&acc)[U][Fmt<DT>::VEC]) {
@@ -287,9 +305,7 @@ __device__ __forceinline__ void sum_interior(BaseFn base_of, int R, const uint32
         for (int i = 0; i < Fmt<DT>::VEC; ++i) acc[u][i] = -0.0f;   // -0 + x == x for every x
     int r = 0;
     for (; r + 8 <= R; r += 8) chunk_interior<DT, NT, 8, U>(base_of, r, lane_off, acc);
-    if (r + 4 <= R) { chunk_interior<DT, NT, 4, U>(base_of, r, lane_off, acc); r += 4; }
-    if (r + 2 <= R) { chunk_interior<DT, NT, 2, U>(base_of, r, lane_off, acc); r += 2; }
-    if (r < R) { chunk_interior<DT, NT, 1, U>(base_of, r, lane_off, acc); }
+    tail_interior<DT, NT, U>(base_of, r, R - r, lane_off, acc);
 }
 
 // The same with the first eight replica pointers already in registers (they are
@@ -310,9 +326,12 @@ __device__ __forceinline__ void sum_interior_pre(const char* const (&pre)[8], in
         r = 8;
     }
     for (; r + 8 <= R; r += 8) chunk_interior<DT, NT, 8, U>(base_of, r, lane_off, acc);
-    if (r + 4 <= R) { chunk_interior<DT, NT, 4, U>(base_of, r, lane_off, acc); r += 4; }
-    if (r + 2 <= R) { chunk_interior<DT, NT, 2, U>(base_of, r, lane_off, acc); r += 2; }
-    if (r < R) { chunk_interior<DT, NT, 1, U>(base_of, r, lane_off, acc); }
+    if (r == 0) {
+        // fewer than eight replicas: their pointers are the preloaded ones
+        tail_interior<DT, NT, U>([&](int k) { return pre[k] + byte0; }, 0, R, lane_off, acc);
+    } else {
+        tail_interior<DT, NT, U>(base_of, r, R - r, lane_off, acc);
+    }
 }
 
 template <int DT>

@@ -234,8 +234,8 @@ def test_participation_argument_errors(d):
 def test_reduction_stream_option_is_validated(d):
     ctx, _ = plan(d, [4, 4, 4], [0, 0, 0], 0)
     try:
-        for opt, bad in ((d.DDP_OPT_REDUCE_BLOCKS_PER_CU, -1), (d.DDP_OPT_REDUCE_BLOCKS_PER_CU, 17),
-                         (d.DDP_OPT_REDUCE_CAP_MIN_BYTES, -1), (d.DDP_OPT_COALESCE, -1), (99, 0)):
+        for opt, bad in ((d.DDP_OPT_REDUCE_BLOCKS_PER_CU, -2), (d.DDP_OPT_REDUCE_BLOCKS_PER_CU, 17),
+                         (d.DDP_OPT_REDUCE_CAP_MIN_BYTES, -1), (d.DDP_OPT_COALESCE, -2), (99, 0)):
             with pytest.raises(d.DdpError) as e:
                 d.ddp_set_option(ctx, opt, bad)
             assert e.value.code == d.DDP_ERR_ARG
