@@ -101,7 +101,10 @@ typedef struct ddp_ctx ddp_ctx;
 #define DDP_OPT_FIND_UNUSED   11  /* any time between iterations: the paper's find_unused_parameters
                                      knob.  1 = gradients of parameters that no replica used in the
                                      iteration (the global bitmap of Section 4.2 says so) are left
-                                     exactly as they are; 0 (default) = they are written as zeros */
+                                     exactly as they are (a bucket made only of such parameters is
+                                     then not launched at all in the fused pipeline: Section 6.2.2's
+                                     skipping at the bucket level); 0 (default) = they are written as
+                                     zeros */
 #define DDP_OPT_REDUCE_STREAMS 12  /* between iterations: number of reduction streams, 1 (default) to 8.
                                      The launches of an iteration take the streams in turn: the
                                      caller's reduce_stream first, then streams the library creates

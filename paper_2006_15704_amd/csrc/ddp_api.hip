@@ -333,6 +333,17 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
     return DDP_OK;
 }
 
+// True if no replica used any parameter of bucket b in the running iteration.
+bool bucket_all_unused(const ddp_ctx* c, int32_t b) {
+    if (!c->bucket_zero[b]) return false;
+    const ddp::BucketInfo& bk = c->plan.buckets[b];
+    const size_t begin = static_cast<size_t>(bk.seg_begin) * c->R;
+    const size_t end = begin + bk.params.size() * static_cast<size_t>(c->R);
+    for (size_t k = begin; k < end; ++k)
+        if (c->local_cur[k]) return false;
+    return true;
+}
+
 // Enqueue the buckets the running API call has made launchable: one launch per
 // bucket, or (DDP_OPT_COALESCE) one per run of consecutive buckets of equal
 // element type.
@@ -351,6 +362,16 @@ int32_t flush_deferred(ddp_ctx* c) {
     // pipeline keeps its flat buffers and unpack on the reduction stream.)
     const bool closing = c->tail_on_backward != 0 && c->pipeline == DDP_PIPELINE_FUSED &&
                          todo.back() == static_cast<int32_t>(c->plan.buckets.size()) - 1;
+    if (c->find_unused != 0 && c->pipeline == DDP_PIPELINE_FUSED && c->iter_zero) {
+        // Skipping at the bucket level (Section 6.2.2): a bucket none of whose
+        // parameters was used by any replica has nothing to reduce and, with
+        // find_unused, nothing to write -- it needs no launch at all.
+        size_t kept = 0;
+        for (int32_t b : todo)
+            if (!bucket_all_unused(c, b)) todo[kept++] = b;
+        todo.resize(kept);
+        if (todo.empty()) return DDP_OK;
+    }
     size_t i = 0;
     while (i < todo.size()) {
         size_t j = i;

@@ -311,3 +311,45 @@ def test_participation_with_several_reduction_streams(pipeline):
         for r in range(R):
             for p in range(n):
                 assert grads.download(r, p).tobytes() == state[r][p].tobytes(), f"r{r} p{p}"
+
+
+def test_wholly_unused_buckets_are_not_launched():
+    """Section 6.2.2, skipping at the bucket level: with find_unused a bucket
+    whose parameters nobody used keeps its gradients and needs no kernel; the
+    launch log (the schedule) still lists it, the timed launches do not."""
+    d, harness = lib()
+    n, R, cap = 12, 3, 8000                       # 1000 fp32 elements each: two parameters per bucket
+    numel = [1000] * n
+    dtypes = [FP32] * n
+    reps = [[workloads.gaussian_grad(90, r, 0, p, numel[p], 1.0, FP32) for p in range(n)] for r in range(R)]
+    asg = oracle.assign_buckets(numel, dtypes, cap)
+    assert [bk.params for bk in asg.buckets] == [[11, 10], [9, 8], [7, 6], [5, 4], [3, 2], [1, 0]]
+    dead = {9, 8, 3, 2}                           # buckets 1 and 4; parameter 5 alone does not empty bucket 3
+    marks = []
+    for p in range(n - 1, -1, -1):
+        used = [0] * R if (p in dead or p == 5) else [1, int(p % 2), 1]
+        marks.append((p, used))
+        for r in range(R):
+            if not used[r]:
+                poison(reps[r][p], FP32)
+    want, _, wlog, glob = oracle.synchronize_local(numel, dtypes, cap, reps, marks, find_unused=True)
+    grads = harness.DeviceGrads(numel, dtypes, R)
+    for r in range(R):
+        grads.upload_replica(r, reps[r])
+    for find_unused, expect in ((1, [0, 2, 3, 5]), (0, [0, 1, 2, 3, 4, 5])):
+        with harness.Session(grads, cap, FUSED, True) as s:
+            d.ddp_set_option(s.ctx, d.DDP_OPT_FIND_UNUSED, find_unused)
+            d.ddp_set_option(s.ctx, d.DDP_OPT_COALESCE, 0)
+            d.ddp_set_option(s.ctx, d.DDP_OPT_TIMING, 1)
+            for p, used in marks:
+                d.ddp_mark_ready_local(s.ctx, p, used)
+            d.ddp_finalize_backward(s.ctx)
+            d.ddp_synchronize(s.ctx)
+            assert d.ddp_get_launch_log(s.ctx, 1) == wlog
+            assert d.ddp_get_global_used(s.ctx, n).tolist() == glob.tolist()
+            _, ids = d.ddp_get_kernel_times(s.ctx, d.DDP_K_REDUCE)
+            assert [int(x) for x in ids] == expect
+            if find_unused:
+                for r in range(R):
+                    for p in range(n):
+                        assert grads.download(r, p).tobytes() == want[r][p].tobytes(), f"r{r} p{p}"
