@@ -26,6 +26,14 @@
  *     thread).  Different contexts may be used from different threads.
  *   - All compute calls are asynchronous with respect to the host unless
  *     stated otherwise.
+ *   - Graph capture: the ready marks and ddp_finalize_backward of an iteration
+ *     may be captured into a HIP graph on backward_stream (the capture forks
+ *     to the reduction streams and joins again by itself) if every replica
+ *     takes part in every parameter (no participation flags: their staging
+ *     copies read host memory that later iterations rewrite), DDP_OPT_TIMING is
+ *     0 and the staged pipeline is not used.  The host state (launch log,
+ *     iteration count) advances at capture time only; a replay repeats the same
+ *     launches on whatever the gradient tensors hold then.
  */
 #ifndef DDP_GFX950_H
 #define DDP_GFX950_H

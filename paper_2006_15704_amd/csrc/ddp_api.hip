@@ -255,7 +255,11 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
         // (and at most one event on it) serves every bucket the call launches;
         // each reduction stream waits for that event once.
         if (!c->ordered_in_call) {
-            const hipError_t q = hipStreamQuery(c->backward);
+            // (a stream that is being captured into a graph cannot be queried: treat it as busy)
+            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+            const bool capturing = hipStreamIsCapturing(c->backward, &cap) == hipSuccess &&
+                                   cap != hipStreamCaptureStatusNone;
+            const hipError_t q = capturing ? hipErrorNotReady : hipStreamQuery(c->backward);
             if (q == hipErrorNotReady) {
                 HIPCHK(c, hipEventRecord(c->ev_ready[first], c->backward));
                 c->call_event = c->ev_ready[first];

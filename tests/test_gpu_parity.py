@@ -457,3 +457,46 @@ def test_round_robin_streams_wait_for_the_backward_stream(pipeline, same_stream)
         for it in range(3):
             for i in range(n):
                 assert keep.download(it, i).tobytes() == wants[it][i].tobytes(), f"iteration {it} parameter {i}"
+
+
+# ---- graph capture ------------------------------------------------------------------------------
+@pytest.mark.parametrize("two_streams", [False, True])
+def test_a_captured_step_replays_correctly(two_streams):
+    """One whole step (ready marks + finalize, fused pipeline) captured into a
+    HIP graph on the backward stream and replayed on new gradients several
+    times, with eager work and synchronizations between the replays; every
+    replay is compared with the oracle.  With two_streams the buckets are
+    launched one call at a time, so all but the last go to the reduction
+    stream and the capture forks and joins across streams."""
+    import torch
+    d, harness = lib()
+    numel = workloads.numel_of(workloads.tiny_shapes()) + [9000, 2048, 77]
+    n, R, cap = len(numel), 3, 16384
+    grads = harness.DeviceGrads(numel, [FP32] * n, R)
+    order = list(range(n - 1, -1, -1))
+    with harness.Session(grads, cap, FUSED) as s:
+        reps = gaussian_reps(95, numel, R, 1.0)
+        for r in range(R):
+            grads.upload_replica(r, reps[r])
+        s.sync()                                   # an eager step first (also builds every lazy resource)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s.backward_stream):
+            if two_streams:
+                for p in order:
+                    d.ddp_mark_ready(s.ctx, p)
+            else:
+                d.ddp_mark_ready_many(s.ctx, order)
+            d.ddp_finalize_backward(s.ctx)
+        torch.cuda.synchronize()
+        for it in range(4):
+            reps = gaussian_reps(96 + it, numel, R, 1.0)
+            for r in range(R):
+                grads.upload_replica(r, reps[r])
+            torch.cuda.synchronize()
+            want, _, _ = oracle.synchronize(numel, [FP32] * n, cap, reps)
+            g.replay()
+            torch.cuda.synchronize()
+            for i in range(n):
+                assert grads.download(0, i).tobytes() == want[i].tobytes(), f"replay {it} parameter {i}"
+        del g
