@@ -7,10 +7,9 @@ namespace ddp {
 
 // Work is cut into tiles of TILE_BYTES of gradient data: one thread block of
 // BLOCK threads moves TILE_VECS 16-byte vectors per replica.  8 KiB tiles (two
-// vectors per thread and replica) measured best on the ResNet-50-shaped list,
-// whose buckets are small enough for block granularity to show; 16 KiB tiles
-// with four vectors per thread are about 1.5 % faster on BERT-large and 8 %
-// slower on ResNet-50.
+// vectors per thread and replica) measured best: 16 KiB tiles with two or four
+// vectors per thread were 1 to 4 points of HBM peak slower on the ResNet-50-
+// and BERT-large-shaped lists under every cap on resident blocks.
 constexpr int BLOCK = 256;
 #ifndef DDP_TILE_VECS
 #define DDP_TILE_VECS 512

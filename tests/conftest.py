@@ -52,9 +52,8 @@ def read_golden(name):
 
 def progress(msg: str) -> None:
     """A progress line for long GPU tests: goes to the real stderr (not
-    captured by pytest) and, when the folder exists, to
-    gpurun_out/test_progress.log, so that a long test is not mistaken for a
-    hung one."""
+    captured by pytest) and, when the results folder of a remote run exists,
+    to a log file in it, so that a long test is not mistaken for a hung one."""
     line = f"[progress] {msg}\n"
     try:
         sys.__stderr__.write(line)
