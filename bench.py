@@ -20,8 +20,9 @@ Prints ONE JSON line.
             one synchronization divided by the measured step time.
   roofline  the reduce kernel (the dominant one) against the 8 TB/s HBM peak:
             algorithmic bytes per launch = (R + 1) * bytes of the buckets the
-            launch covers, divided by the average launch duration, measured
-            with HIP events on the reduction stream inside the timed region.
+            launch covers, divided by the average launch duration: the time
+            between two HIP events around the timed region (on the stream the
+            launches run on or are waited for by) divided by the launches.
   cpu_baseline  the CPU oracle on the same workload.
 """
 from __future__ import annotations
@@ -110,18 +111,35 @@ def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup
         lib.ddp_synchronize(ctx)
         torch.cuda.synchronize()
 
-        # timed region: `steps` steps with HIP events on the reduction stream
-        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 1 if timing_mode == "launch" else 2)
+        launches_per_step = None
+        if timing_mode == "region":
+            # one more untimed step with the library's per-iteration events, to count the launches
+            lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 2)
+            step()
+            lib.ddp_synchronize(ctx)
+            launches_per_step = int(lib.ddp_get_kernel_times(ctx, lib.DDP_K_ITERATION)[1].sum())
+            lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 0)
+
+        # timed region: `steps` steps.  "launch" / "iteration": the library's HIP events, one pair
+        # per launch / per iteration, on the stream the kernels run on.  "region": one pair of HIP
+        # events around all the steps on the backward stream -- every launch either runs on that
+        # stream or is waited for by it in ddp_finalize_backward -- and no events in between.
+        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, {"launch": 1, "iteration": 2, "region": 0}[timing_mode])
         torch.cuda.synchronize()
+        ev_a = torch.cuda.Event(enable_timing=True)
+        ev_b = torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
+        ev_a.record(s.backward_stream)
         for _ in range(steps):
             step()
+        ev_b.record(s.backward_stream)
         t_enq = time.perf_counter()
         lib.ddp_synchronize(ctx)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         res = {"ms_per_step": (t1 - t0) * 1e3 / steps,
-               "host_enqueue_ms_per_step": (t_enq - t0) * 1e3 / steps}
+               "host_enqueue_ms_per_step": (t_enq - t0) * 1e3 / steps,
+               "region_ms": ev_a.elapsed_time(ev_b), "launches_per_step": launches_per_step}
         res["reduce"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_REDUCE)
         res["pack"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_PACK)
         res["unpack"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_UNPACK)
@@ -177,10 +195,11 @@ def main() -> int:
                     help="staged pipeline: pack/unpack store with the non-temporal hint")
     ap.add_argument("--same-stream", action="store_true",
                     help="use one stream for backward and reduction (no event plumbing)")
-    ap.add_argument("--timing", default=None, choices=["launch", "iteration"],
+    ap.add_argument("--timing", default=None, choices=["launch", "iteration", "region"],
                     help="HIP-event granularity in the timed region: one pair per kernel launch "
-                         "(default for staged), or one pair around each iteration's bucket "
-                         "launches (default for fused, where they are the only kernels)")
+                         "(default for staged), one pair around each iteration's bucket launches, or "
+                         "one pair around all the steps (default for fused, where the reduce launches "
+                         "are the only kernels: no event between them)")
     ap.add_argument("--cap-mib", type=float, default=None,
                     help="override the bucket cap (MiB; negative = whole model)")
     ap.add_argument("--replicas", type=int, default=None,
@@ -217,7 +236,7 @@ def main() -> int:
     B = sum(numel) * es
     W = 1
     codes = {"staged": lib.DDP_PIPELINE_STAGED, "fused": lib.DDP_PIPELINE_FUSED}
-    timing = args.timing or ("iteration" if args.pipeline == "fused" else "launch")
+    timing = args.timing or ("region" if args.pipeline == "fused" else "launch")
 
     reps = generate_replicas(config_id, numel, R, sigma, dtype)
     grads = harness.DeviceGrads(numel, [dtype] * n, R)
@@ -256,12 +275,18 @@ def main() -> int:
             sel = red_ms[red_ids == b]
             if len(sel):
                 per_bucket[str(b)] = round((R + 1) * bucket_elems[b] * es / float(np.median(sel)) / 1e6, 1)
-    else:
+    elif timing == "iteration":
         # one interval per iteration holding all its bucket launches; in the
         # fused pipeline they are the only kernels inside it
         launches = int(iter_launches.sum())
         total_alg = float((R + 1) * B * len(iter_ms))
         total_ms = float(iter_ms.sum())
+    else:
+        # one interval around all the steps (fused pipeline: the reduce launches are its only
+        # kernels); the gaps between consecutive launches are part of it
+        launches = m["launches_per_step"] * args.steps
+        total_alg = float((R + 1) * B * args.steps)
+        total_ms = float(m["region_ms"])
     avg_launch_ms = total_ms / max(launches, 1)
     achieved = total_alg / max(total_ms, 1e-12) / 1e6          # bytes / ms -> GB/s
 
@@ -298,18 +323,31 @@ def main() -> int:
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "avg_launch_ms": round(avg_launch_ms, 5),
             "launches": launches,
-            "timing": "HIP event pair per " + timing,
+            "timing": ("one HIP event pair around the timed region" if timing == "region"
+                       else "HIP event pair per " + timing),
             "interval_ms": ({"median": round(float(np.median(iter_ms)), 5), "min": round(float(iter_ms.min()), 5),
                              "max": round(float(iter_ms.max()), 5), "what": "one iteration's launches"}
                             if timing == "iteration" and len(iter_ms) else
                             {"median": round(float(np.median(red_ms)), 5), "min": round(float(red_ms.min()), 5),
-                             "max": round(float(red_ms.max()), 5), "what": "one launch"} if len(red_ms) else None),
+                             "max": round(float(red_ms.max()), 5), "what": "one launch"}
+                            if timing == "launch" and len(red_ms) else None),
             "algorithmic_bytes_per_launch": round(total_alg / max(launches, 1)),
             "traffic": read_traffic(args.workload, args.pipeline),
         },
     }
     if per_bucket:
         out["reduce_gbps_per_bucket"] = per_bucket
+    if timing == "region":
+        # a short second pass with one event pair per iteration, for the spread
+        it = measure(lib, harness, torch, grads, cap, codes[args.pipeline], order, max(10, args.steps // 5), 2,
+                     "iteration", args)
+        it_ms, it_launches = it["iteration"]
+        out["roofline"]["per_iteration_pass"] = {
+            "interval_ms": {"median": round(float(np.median(it_ms)), 5), "min": round(float(it_ms.min()), 5),
+                            "max": round(float(it_ms.max()), 5)},
+            "reduce_gbps": round((R + 1) * B * len(it_ms) / float(it_ms.sum()) / 1e6, 1),
+            "what": "one HIP event pair per iteration around its launches (the pairs cost a few us each)",
+        }
 
     if args.pipeline == "fused" and not args.no_staged_leg:
         # the literal three-kernel pipeline on the same data, one event pair per launch
