@@ -91,10 +91,13 @@ class Session:
     """A context with its two streams.  Thin convenience over the binding."""
 
     def __init__(self, grads: DeviceGrads, cap_bytes: int, pipeline: int = B.DDP_PIPELINE_STAGED,
-                 write_all: bool = False, same_stream: bool = False):
+                 write_all: bool = False, same_stream: bool = False, streams=None):
         self.grads = grads
-        self.reduce_stream = torch.cuda.Stream(device=grads.device)
-        self.backward_stream = self.reduce_stream if same_stream else torch.cuda.Stream(device=grads.device)
+        if streams is not None:          # (reduce, backward) of another session: contexts that share them
+            self.reduce_stream, self.backward_stream = streams
+        else:
+            self.reduce_stream = torch.cuda.Stream(device=grads.device)
+            self.backward_stream = self.reduce_stream if same_stream else torch.cuda.Stream(device=grads.device)
         torch.cuda.synchronize()
         self.ctx = B.ddp_create(grads.R, 0, self.reduce_stream.cuda_stream,
                                 self.backward_stream.cuda_stream)
