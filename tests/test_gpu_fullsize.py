@@ -61,10 +61,11 @@ def test_model_shapes_r8_fp32(name, config_id, sigma, nb):
     grads = harness.DeviceGrads(numel, [FP32] * n, R)
     for r in range(1, R):
         grads.upload_replica(r, reps[r])
-    # the library's defaults (what bench.py's headline line times), then one launch per bucket,
-    # then one launch per bucket on two reduction streams (the benchmark's other legs)
-    configs = [(STAGED, ()), (FUSED, ()), (FUSED, ((d.DDP_OPT_COALESCE, 0),)),
-               (FUSED, ((d.DDP_OPT_COALESCE, 0), (d.DDP_OPT_REDUCE_STREAMS, 2)))]
+    # the library's defaults (what bench.py's headline line times), one launch per bucket, and the
+    # benchmark's other legs: one launch per bucket on the reduction stream, and on two of them
+    per_bucket = ((d.DDP_OPT_COALESCE, 0), (d.DDP_OPT_TAIL_ON_BACKWARD, 0))
+    configs = [(STAGED, ()), (FUSED, ()), (FUSED, ((d.DDP_OPT_COALESCE, 0),)), (FUSED, per_bucket),
+               (FUSED, per_bucket + ((d.DDP_OPT_REDUCE_STREAMS, 2),))]
     for pipeline, options in configs:
         progress(f"{name}: pipeline {pipeline} options {options}")
         grads.upload_replica(0, reps[0])
