@@ -67,6 +67,23 @@ if not os.path.exists(LIB_PATH):
 
 _lib = C.CDLL(LIB_PATH)
 
+
+def _refuse_stale_library() -> None:
+    """The library carries a digest of the sources it was compiled from; if the
+    sources next to it have changed since, results would silently describe old
+    code."""
+    from . import build as _build
+    _lib.ddp_version.restype = C.c_char_p
+    have = _lib.ddp_version().decode().rsplit("ddp-src-hash:", 1)[-1]
+    want = _build.source_hash()
+    if have != want:
+        raise ImportError(
+            f"{LIB_PATH} was built from other sources (digest {have}, sources on disk {want}): "
+            "rebuild it with `python paper_2006_15704_amd/build.py`")
+
+
+_refuse_stale_library()
+
 _vp, _i32, _i64, _u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
 _lib.ddp_version.restype = C.c_char_p
 _lib.ddp_last_error.restype = C.c_char_p

@@ -18,6 +18,35 @@ FLAGS = [
 ]
 
 
+def source_hash() -> str:
+    """Digest of everything the library is compiled from.  It is baked into the
+    library (ddp_version() reports it), so that a library built from other
+    sources than the ones on disk is recognised and never measured or tested
+    by mistake."""
+    import hashlib
+    h = hashlib.sha256()
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC))
+             if f.endswith((".hip", ".cpp", ".h"))]
+    files.append(os.path.join(os.path.dirname(HERE), "include", "ddp_gfx950.h"))
+    for path in files:
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as fh:
+            h.update(fh.read())
+    h.update(" ".join(FLAGS).encode())
+    return h.hexdigest()[:16]
+
+
+def built_hash() -> str:
+    """The digest baked into the library on disk ('' if there is none)."""
+    import re
+    try:
+        with open(LIB, "rb") as fh:
+            m = re.search(rb"ddp-src-hash:([0-9a-f]{16})", fh.read())
+        return m.group(1).decode() if m else ""
+    except OSError:
+        return ""
+
+
 def hipcc() -> str:
     exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     if not os.path.exists(exe):
@@ -26,7 +55,8 @@ def hipcc() -> str:
 
 
 def build(verbose: bool = False) -> str:
-    cmd = [hipcc()] + FLAGS + ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    cmd = ([hipcc()] + FLAGS + [f'-DDDP_SOURCE_HASH="{source_hash()}"', "-o", LIB]
+           + [os.path.join(CSRC, s) for s in SOURCES])
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

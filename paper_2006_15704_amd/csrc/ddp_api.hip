@@ -453,7 +453,12 @@ inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 extern "C" {
 
-const char* ddp_version(void) { return "ddp_gfx950 0.1"; }
+#ifndef DDP_SOURCE_HASH
+#define DDP_SOURCE_HASH "0000000000000000"
+#endif
+// The build passes a digest of the sources; the Python binding compares it with
+// the sources on disk so that a stale library is never tested or measured.
+const char* ddp_version(void) { return "ddp_gfx950 0.2 ddp-src-hash:" DDP_SOURCE_HASH; }
 
 const char* ddp_last_error(const ddp_ctx* ctx) {
     return ctx ? ctx->err.c_str() : g_create_error.c_str();
@@ -1063,6 +1068,10 @@ int32_t ddp_get_launch_log(const ddp_ctx* c, int32_t which, int32_t* bucket_ids,
 int32_t ddp_no_sync_accumulate(ddp_ctx* c, void* const* micro) {
     if (!c) return DDP_ERR_ARG;
     if (!c->built) return fail(c, DDP_ERR_STATE, "ddp_no_sync_accumulate before ddp_build_buckets");
+    // Section 3.2.4's no_sync covers whole iterations: once a ready mark has been taken, buckets
+    // may already be reducing these very tensors in place on another stream.
+    if (c->tracker.marks() != 0 || !c->deferred.empty())
+        return fail(c, DDP_ERR_STATE, "ddp_no_sync_accumulate in the middle of a synchronizing iteration");
     if (c->plan_only) return fail(c, DDP_ERR_NO_DEVICE, "plan-only context cannot accumulate");
     if (!micro) return fail(c, DDP_ERR_ARG, "ddp_no_sync_accumulate: null pointer array");
     const int32_t n = static_cast<int32_t>(c->plan.params.size());

@@ -100,11 +100,11 @@ hipError_t launch_bitmap_or(const uint8_t* local, uint8_t* global, int G, int R,
 hipError_t launch_accumulate(const SegTables& t, int64_t ntiles, int R, int n, void* const* micro,
                              unsigned lds, hipStream_t s);
 
-// K6: wait `ticks` of the device wall clock (bounded), then copy
-// src_r -> dst_r (nelem elements of es bytes) for r < R, where
-// ptrs = [dst_0..dst_{R-1}, src_0..src_{R-1}] is a device array (null = delay
-// only).  busy_blocks = 0: one block that sleeps between polls; > 0: that many
-// blocks (delay-only launches) doing arithmetic between polls.
+// K6: a kernel that waits `ticks` of the device wall clock (bounded; skipped for
+// ticks <= 0), followed by a kernel that copies src_r -> dst_r (nelem elements
+// of es bytes) for r < R, where ptrs = [dst_0..dst_{R-1}, src_0..src_{R-1}] is a
+// device array (null = delay only).  busy_blocks = 0: the delay is one block that
+// sleeps between polls; > 0: that many blocks doing arithmetic between polls.
 hipError_t launch_emit(int64_t ticks, void* const* ptrs, int R, int64_t nelem, int es,
                        int busy_blocks, float* sink, hipStream_t s);
 

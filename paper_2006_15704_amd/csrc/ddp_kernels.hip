@@ -707,9 +707,10 @@ __global__ __launch_bounds__(BLOCK) void bitmap_or_kernel(const uint8_t* __restr
 }
 
 // ---- K6: synthetic backward emitter -----------------------------------------
-// Every wave waits until `ticks` of the constant-rate wall clock have passed
-// (at most MAX_SPINS polls, so the kernel always ends), then replica
-// blockIdx.y's gradient is copied from its source.
+// With ticks > 0 every wave waits until `ticks` of the constant-rate wall clock
+// have passed (at most MAX_SPINS polls, so the kernel always ends); with a
+// pointer row replica blockIdx.y's gradient is copied from its source.  The
+// host launches the two roles separately (launch_emit).
 constexpr uint32_t MAX_SPINS = 1u << 20;
 
 __global__ __launch_bounds__(BLOCK) void emit_kernel(int64_t ticks, void* const* __restrict__ ptrs,
@@ -880,18 +881,23 @@ hipError_t launch_bitmap_or(const uint8_t* local, uint8_t* global, int G, int R,
 
 hipError_t launch_emit(int64_t ticks, void* const* ptrs, int R, int64_t nelem, int es,
                        int busy_blocks, float* sink, hipStream_t s) {
-    unsigned bx = 1, by = 1;
-    if (ptrs != nullptr) {
-        int64_t want = (nelem + BLOCK * 8 - 1) / (BLOCK * 8);
-        if (want < 1) want = 1;
-        if (want > 1024) want = 1024;
-        bx = static_cast<unsigned>(want);
-        by = static_cast<unsigned>(R);
-    } else if (busy_blocks > 1) {
-        bx = static_cast<unsigned>(busy_blocks);
+    // The delay and the copy are separate launches: a wait inside the copy's
+    // blocks would start per block, and a grid with more blocks than fit on
+    // the GPU at once would then wait several times the nominal delay.
+    if (ticks > 0) {
+        const unsigned bx = busy_blocks > 1 ? static_cast<unsigned>(busy_blocks) : 1u;
+        hipLaunchKernelGGL(emit_kernel, dim3(bx, 1), dim3(BLOCK), 0, s, ticks,
+                           static_cast<void* const*>(nullptr), R, int64_t(0), es,
+                           busy_blocks > 0 ? 1 : 0, sink);
+        const hipError_t e = after_launch();
+        if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(emit_kernel, dim3(bx, by), dim3(BLOCK), 0, s, ticks, ptrs, R, nelem, es,
-                       busy_blocks > 0 ? 1 : 0, sink);
+    if (ptrs == nullptr) return hipSuccess;
+    int64_t want = (nelem + BLOCK * 8 - 1) / (BLOCK * 8);
+    if (want < 1) want = 1;
+    if (want > 1024) want = 1024;
+    hipLaunchKernelGGL(emit_kernel, dim3(static_cast<unsigned>(want), static_cast<unsigned>(R)),
+                       dim3(BLOCK), 0, s, int64_t(0), ptrs, R, nelem, es, 0, sink);
     return after_launch();
 }
 

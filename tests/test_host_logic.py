@@ -156,14 +156,23 @@ def test_error_codes(d):
         assert d.ddp_get_launch_log(ctx, 0) == []
         d.ddp_mark_ready(ctx, 1)
         assert d.ddp_get_launch_log(ctx, 0) == [(0, 1)]
-        for call in (lambda: d.ddp_synchronize(ctx), lambda: d.ddp_no_sync_accumulate(ctx, [None] * 6),
+        for call in (lambda: d.ddp_synchronize(ctx),
                      lambda: d.ddp_synth_backward(ctx, [0]), lambda: d.ddp_get_bucket_ptr(ctx, 0, 0),
                      lambda: d.ddp_get_kernel_times(ctx, 1)):
             with pytest.raises(d.DdpError) as e:
                 call()
             assert e.value.code == d.DDP_ERR_NO_DEVICE
+        # no_sync covers whole iterations: refused once the running one has taken a ready mark
+        # (its buckets may already be reducing the gradient tensors in place)
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_no_sync_accumulate(ctx, [None] * 6)
+        assert e.value.code == d.DDP_ERR_STATE
+        assert "middle of a synchronizing iteration" in d.ddp_last_error(ctx)
         d.ddp_finalize_backward(ctx)      # parameter 0 never marked: no hang, launched by finalize
         assert d.ddp_get_launch_log(ctx, 1) == [(0, 1), (1, 2)]
+        with pytest.raises(d.DdpError) as e:      # between iterations the call is in order again
+            d.ddp_no_sync_accumulate(ctx, [None] * 6)
+        assert e.value.code == d.DDP_ERR_NO_DEVICE
     finally:
         d.ddp_destroy(ctx)
 
