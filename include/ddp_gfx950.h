@@ -349,6 +349,34 @@ int32_t ddp_synth_backward(ddp_ctx* ctx, const int32_t* order, int32_t count,
 int32_t ddp_get_kernel_times(ddp_ctx* ctx, int32_t kind, float* ms, int32_t* ids,
                              int32_t cap, int32_t* n);
 
+/* For callers that cannot allocate device memory: code that runs under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  One
+ * whole synchronization in one call, with no context: the same result as, on a
+ * fresh DDP_PIPELINE_STAGED context, ddp_register_params + ddp_build_buckets
+ * (cap_bytes) + ddp_mark_ready_many(n-1 ... 0) + ddp_finalize_backward -- every
+ * replica takes part in every parameter, the average goes to replica 0's
+ * gradient tensors, the other replicas' tensors are inputs only.  Arguments as
+ * for ddp_create (R, device, one stream for everything) and ddp_register_params
+ * (n, numel, dtype, grad_ptrs: host arrays, copied before the call returns;
+ * gradient memory stays the caller's).  Returns the number of buckets.
+ *
+ * The device tables and the R + 1 flat bucket buffers live in a static device
+ * array of DDP_STATIC_SCRATCH_BYTES that every GPU used through this call holds
+ * until the process ends; host tables travel inside kernel arguments.  The call
+ * makes no hipMalloc / hipFree / hipHostMalloc and no copy from host memory; all
+ * its work is kernels enqueued on `stream`, in order, so it is asynchronous and
+ * may be captured.  Limits: tables (32 bytes + 8 R bytes per parameter, 4 bytes
+ * per 8 KiB of a gradient) plus (R + 1) x the padded gradient bytes must fit the
+ * array, else DDP_ERR_UNSUPPORTED and nothing is enqueued (text in
+ * ddp_last_error(NULL)).  All calls on one GPU share the array, which keeps the
+ * previous call's contents (the call clears what it needs cleared): calls whose
+ * work overlaps in time on one GPU -- different streams, different threads --
+ * race; serialize them.  Other errors as for ddp_create / ddp_register_params. */
+#define DDP_STATIC_SCRATCH_BYTES (32u << 20)
+int32_t ddp_sync_static(int32_t R, int32_t device, void* stream, int32_t n,
+                        const int64_t* numel, const int32_t* dtype,
+                        void* const* grad_ptrs, uint64_t cap_bytes);
+
 /* Library version string. */
 const char* ddp_version(void);
 

@@ -40,6 +40,7 @@ DDP_OPT_COALESCE, DDP_OPT_FIND_UNUSED, DDP_OPT_REDUCE_STREAMS = 10, 11, 12
 DDP_OPT_REDUCE_BLOCKS_PER_CU, DDP_OPT_REDUCE_CAP_MIN_BYTES, DDP_OPT_COPY_BLOCKS_PER_CU = 13, 14, 15
 DDP_OPT_ACCUMULATE_BLOCKS_PER_CU, DDP_OPT_TAIL_ON_BACKWARD = 16, 17
 DDP_PIPELINE_STAGED, DDP_PIPELINE_FUSED = 0, 1
+DDP_STATIC_SCRATCH_BYTES = 32 << 20
 DDP_K_PACK, DDP_K_REDUCE, DDP_K_UNPACK, DDP_K_ACCUMULATE, DDP_K_ITERATION = 0, 1, 2, 3, 4
 
 EXPORTS = [
@@ -50,7 +51,7 @@ EXPORTS = [
     "ddp_get_global_used",
     "ddp_mark_ready_many", "ddp_finalize_backward", "ddp_synchronize",
     "ddp_get_launch_log", "ddp_no_sync_accumulate", "ddp_get_used_map",
-    "ddp_synth_backward", "ddp_get_kernel_times",
+    "ddp_synth_backward", "ddp_get_kernel_times", "ddp_sync_static",
 ]
 
 
@@ -109,6 +110,7 @@ _lib.ddp_no_sync_accumulate.argtypes = [_vp, C.POINTER(_vp)]
 _lib.ddp_get_used_map.argtypes = [_vp, _i32, C.POINTER(C.c_uint8)]
 _lib.ddp_synth_backward.argtypes = [_vp, C.POINTER(_i32), _i32, C.POINTER(_i64), C.POINTER(_vp), _i32]
 _lib.ddp_get_kernel_times.argtypes = [_vp, _i32, C.POINTER(C.c_float), C.POINTER(_i32), _i32, C.POINTER(_i32)]
+_lib.ddp_sync_static.argtypes = [_i32, _i32, _vp, _i32, C.POINTER(_i64), C.POINTER(_i32), C.POINTER(_vp), _u64]
 for _name in EXPORTS:
     if _name not in ("ddp_version", "ddp_last_error"):
         getattr(_lib, _name).restype = _i32
@@ -287,3 +289,14 @@ def ddp_get_kernel_times(ctx, kind: int):
     ids = np.zeros(max(n.value, 1), dtype=np.int32)
     _check(ctx, _lib.ddp_get_kernel_times(ctx, kind, _as(ms, C.c_float), _as(ids, _i32), n.value, C.byref(n)))
     return ms[:n.value].copy(), ids[:n.value].copy()
+
+
+def ddp_sync_static(R: int, device: int, stream: int, numel: Sequence[int], dtype: Sequence[int],
+                    grad_ptrs: Sequence[int], cap_bytes: int) -> int:
+    """One whole synchronization without a context and without device-memory
+    allocation; returns the number of buckets."""
+    ne, dt, gp = _i64_array(numel), _i32_array(dtype), _ptr_array(grad_ptrs)
+    if len(gp) != R * len(ne):
+        raise ValueError(f"grad_ptrs has {len(gp)} entries, expected R*n = {R * len(ne)}")
+    return _check(None, _lib.ddp_sync_static(R, device, _vp(stream or None), len(ne), _as(ne, _i64),
+                                             _as(dt, _i32), _as(gp, _vp), cap_bytes))

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libddp_gfx950.so")
-SOURCES = ["bucket_plan.cpp", "ddp_api.hip", "ddp_kernels.hip"]
+SOURCES = ["bucket_plan.cpp", "ddp_api.hip", "ddp_kernels.hip", "ddp_static.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                     # no fused multiply-add may change a rounding

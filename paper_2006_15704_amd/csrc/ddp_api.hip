@@ -13,6 +13,7 @@
 
 #include "bucket_plan.h"
 #include "ddp_kernels.h"
+#include "seg_layout.h"
 
 namespace {
 
@@ -25,7 +26,7 @@ constexpr unsigned kOrderEvent = hipEventDisableTiming | hipEventReleaseToDevice
 // not add cache maintenance to the interval it measures.
 constexpr unsigned kTimingEvent = hipEventReleaseToDevice;
 
-thread_local std::string g_create_error;
+thread_local std::string g_create_error;   // failures of calls that have no context
 
 struct TimedLaunch {
     int32_t kind;
@@ -178,13 +179,7 @@ unsigned lds_for_blocks(const ddp_ctx* c, int32_t blocks) {
 }
 unsigned copy_lds(const ddp_ctx* c) { return lds_for_blocks(c, c->copy_blocks_per_cu); }
 
-ddp::Scale make_scale(int R) {
-    ddp::Scale sc;
-    sc.div = static_cast<float>(R);
-    sc.mul = 1.0f / static_cast<float>(R);
-    sc.use_mul = (R & (R - 1)) == 0;   // power of two: the reciprocal is exact, same bits as dividing
-    return sc;
-}
+using ddp::make_scale;
 
 int32_t timed_begin(ddp_ctx* c, int32_t kind, int32_t bucket, hipStream_t s, size_t* slot) {
     *slot = static_cast<size_t>(-1);
@@ -447,9 +442,13 @@ void release_device(ddp_ctx* c) {
     c->d_emit = nullptr; c->h_emit = nullptr;
 }
 
-inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+inline int64_t round_up(int64_t x, int64_t a) { return ddp::round_up_to(x, a); }
 
 }  // namespace
+
+namespace ddp {
+int32_t fail_without_context(int32_t code, const std::string& msg) { return fail(nullptr, code, msg); }
+}  // namespace ddp
 
 extern "C" {
 
@@ -653,42 +652,14 @@ static int32_t build_internal(ddp_ctx* c, uint64_t cap_bytes, const std::vector<
     c->global_closed.assign(n, 0);
 
     if (!c->plan_only) {
-        // slab layout: bucket bases aligned to 256 bytes, lengths padded to 16
-        c->bucket_slab_off.resize(nb);
-        c->bucket_vecs.resize(nb);
-        int64_t off = 0;
-        for (int32_t b = 0; b < nb; ++b) {
-            c->bucket_slab_off[b] = off;
-            const int64_t bytes = static_cast<int64_t>(c->plan.buckets[b].bytes());
-            c->bucket_vecs[b] = (bytes + 15) / 16;
-            off = round_up(off + c->bucket_vecs[b] * 16, 256);
-        }
-        c->slab_stride = round_up(off > 0 ? off : 256, 4096);
-
-        // segment tables in bucket-major fill order
-        std::vector<int64_t> numel(n), flat_byte(n);
-        std::vector<int32_t> param(n), dtype(n);
-        c->h_tile0.assign(n + 1, 0);
-        for (int32_t b = 0; b < nb; ++b) {
-            const ddp::BucketInfo& bk = c->plan.buckets[b];
-            for (size_t k = 0; k < bk.params.size(); ++k) {
-                const int32_t i = bk.params[k];
-                const int32_t g = bk.seg_begin + static_cast<int32_t>(k);
-                const ddp::ParamInfo& p = c->plan.params[i];
-                numel[g] = p.numel;
-                flat_byte[g] = c->bucket_slab_off[b] + p.offset * ddp::elem_size(p.dtype);
-                param[g] = i;
-                dtype[g] = p.dtype;
-                // largest lead-in over every destination this segment can have:
-                // its slot in the flat slab and each replica's gradient tensor
-                int lead = static_cast<int>(flat_byte[g] & 15);
-                for (int64_t r = 0; r < c->R; ++r) {
-                    const int a = static_cast<int>(reinterpret_cast<uintptr_t>(c->grad_ptrs[r * n + i]) & 15u);
-                    if (a > lead) lead = a;
-                }
-                c->h_tile0[g + 1] = c->h_tile0[g] + ddp::tiles_for(p.numel, ddp::elem_size(p.dtype), lead);
-            }
-        }
+        // slab layout (bucket bases aligned to 256 bytes, lengths padded to 16) and segment
+        // tables in bucket-major fill order
+        ddp::HostTables ht;
+        ddp::build_host_tables(c->plan, c->grad_ptrs.data(), c->R, ht);
+        c->bucket_slab_off = ht.bucket_slab_off;
+        c->bucket_vecs = ht.bucket_vecs;
+        c->slab_stride = ht.slab_stride;
+        c->h_tile0 = ht.tile0;
         if (c->h_tile0[n] >= (int64_t(1) << 31)) {
             c->built = false;
             return fail(c, DDP_ERR_UNSUPPORTED, "model too large for one launch grid");
@@ -697,27 +668,11 @@ static int32_t build_internal(ddp_ctx* c, uint64_t cap_bytes, const std::vector<
         release_build(c);   // leftovers of an earlier attempt that failed
         // one allocation for the segment records and the pointer rows
         const int64_t R = c->R;
-        std::vector<ddp::SegInfo> seg(n);
-        std::vector<void*> grad(static_cast<size_t>(R) * n + 8, nullptr);   // + 8: see SegTables::grad
-        for (int32_t g = 0; g < n; ++g) {
-            bool cong = true;
-            for (int64_t r = 0; r < R; ++r) {
-                void* ptr = c->grad_ptrs[r * n + param[g]];
-                grad[g * R + r] = ptr;
-                cong = cong && ((reinterpret_cast<uintptr_t>(ptr) ^ reinterpret_cast<uintptr_t>(c->grad_ptrs[param[g]])) & 15u) == 0;
-            }
-            seg[g].numel = numel[g];
-            seg[g].tile0 = c->h_tile0[g];
-            seg[g].flat_byte = flat_byte[g];
-            seg[g].param = param[g];
-            const int lead0 = static_cast<int>(reinterpret_cast<uintptr_t>(c->grad_ptrs[param[g]]) & 15u);
-            seg[g].flags = dtype[g] | (cong ? 0x100 : 0) | (lead0 << 16);
-        }
         const size_t seg_bytes = sizeof(ddp::SegInfo) * n;
-        const size_t bytes = seg_bytes + sizeof(void*) * grad.size();
+        const size_t bytes = seg_bytes + sizeof(void*) * ht.grad.size();
         std::vector<char> host(bytes);
-        std::memcpy(host.data(), seg.data(), seg_bytes);
-        std::memcpy(host.data() + seg_bytes, grad.data(), sizeof(void*) * grad.size());
+        std::memcpy(host.data(), ht.seg.data(), seg_bytes);
+        std::memcpy(host.data() + seg_bytes, ht.grad.data(), sizeof(void*) * ht.grad.size());
         HIPCHK(c, hipMalloc(&c->d_tables, bytes));
         HIPCHK(c, hipMemcpy(c->d_tables, host.data(), bytes, hipMemcpyHostToDevice));
         char* d = static_cast<char*>(c->d_tables);
@@ -726,9 +681,7 @@ static int32_t build_internal(ddp_ctx* c, uint64_t cap_bytes, const std::vector<
         c->tables.G = n;
         c->tables.R = c->R;
         {
-            std::vector<int32_t> tile_seg(static_cast<size_t>(c->h_tile0[n]));
-            for (int32_t g = 0; g < n; ++g)
-                for (int64_t tl = c->h_tile0[g]; tl < c->h_tile0[g + 1]; ++tl) tile_seg[tl] = g;
+            const std::vector<int32_t>& tile_seg = ht.tile_seg;
             const size_t tb = sizeof(int32_t) * (tile_seg.empty() ? 1 : tile_seg.size());
             HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_tile_seg), tb));
             if (!tile_seg.empty())

@@ -56,6 +56,15 @@ struct Scale {       // y = use_mul ? s * mul : s / div
     int32_t use_mul;
 };
 
+// The division by R that turns the sum into DDP's average (Section 3.2.1).
+inline Scale make_scale(int R) {
+    Scale sc;
+    sc.div = static_cast<float>(R);
+    sc.mul = 1.0f / static_cast<float>(R);
+    sc.use_mul = (R & (R - 1)) == 0;   // power of two: the reciprocal is exact, same bits as dividing
+    return sc;
+}
+
 // All segment launches cover the tiles [tile_base, tile_base + ntiles) of the
 // global tile numbering (tile0 / tile_seg).  `lds` in K1-K4: bytes of dynamic
 // LDS per block that the kernels do not use; they cap the number of blocks
