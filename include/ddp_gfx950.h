@@ -150,6 +150,24 @@ typedef struct ddp_ctx ddp_ctx;
                                      hand-over takes about 0.2 ms on this system when the waiting
                                      queue was armed long before the event fires.  0 = every bucket
                                      goes to a reduction stream */
+#define DDP_OPT_FLAG_ORDER    18  /* between iterations: how a bucket launch on a reduction stream is ordered
+                                     after the work on backward_stream that produces its gradients
+                                     (fused pipeline).  -1 (default): through device flags where the
+                                     streams allow it -- ddp_mark_ready enqueues a one-block kernel on
+                                     backward_stream that announces a sequence number, and a one-wave
+                                     gate kernel in front of the bucket kernel waits for it; no event
+                                     record stalls backward_stream and the bucket kernel starts as soon
+                                     as the number is there.  The gate's wait is bounded
+                                     (DDP_OPT_GATE_WAIT_US); a launch whose gate gave up does nothing and
+                                     is redone by a repair launch that ddp_finalize_backward enqueues on
+                                     backward_stream once every gradient exists, so results never depend
+                                     on a wait succeeding.  Streams that share a hardware queue cannot
+                                     run a gate and its announcement concurrently; ddp_create (and
+                                     DDP_OPT_REDUCE_STREAMS) probe for that with a bounded test and such
+                                     streams keep events.  0: events always */
+#define DDP_OPT_GATE_WAIT_US  19  /* any time: upper bound, in microseconds, on a gate's wait (0 = look
+                                     once).  Default 100000.  A backward pass that lags further behind
+                                     the host only loses overlap for that iteration, never correctness */
 #define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
                                      kernels: 1, 2 (default) or 4 */
 
@@ -186,6 +204,21 @@ int32_t ddp_destroy(ddp_ctx* ctx);
 const char* ddp_last_error(const ddp_ctx* ctx);
 
 int32_t ddp_set_option(ddp_ctx* ctx, int32_t option, int64_t value);
+
+/* Reads back what is in effect for DDP_OPT_PIPELINE, _WRITE_ALL, _TIMING,
+ * _FIND_UNUSED, _REDUCE_STREAMS, _TAIL_ON_BACKWARD, _GATE_WAIT_US, _COALESCE (the
+ * byte limit in effect, also when it was chosen from R) and _FLAG_ORDER (1 if
+ * the launches of the next iteration would be ordered through device flags: the
+ * option allows it, the pipeline is the fused one, the buckets are built and
+ * every reduction stream in use passed the concurrency probe; else 0), and for
+ * DDP_STAT_REPAIRED_LAUNCHES below.  Other options -> DDP_ERR_ARG. */
+int32_t ddp_get_option(ddp_ctx* ctx, int32_t option, int64_t* value);
+
+/* Read-only through ddp_get_option: the number of bucket launches whose gate
+ * gave up and that a repair launch redid, since ddp_create (the call waits for
+ * the context's outstanding work first).  A number that keeps growing says that
+ * DDP_OPT_GATE_WAIT_US is too short for this backward pass. */
+#define DDP_STAT_REPAIRED_LAUNCHES 100
 
 /* Algorithm 1, constructor loop over net.parameters(): registers n parameters
  * in registration order (index = position in net.parameters()).

@@ -39,12 +39,14 @@ DDP_OPT_PAIR_MIN_BYTES, DDP_OPT_EMIT_BUSY_BLOCKS, DDP_OPT_COPY_NT_STORE = 7, 8, 
 DDP_OPT_COALESCE, DDP_OPT_FIND_UNUSED, DDP_OPT_REDUCE_STREAMS = 10, 11, 12
 DDP_OPT_REDUCE_BLOCKS_PER_CU, DDP_OPT_REDUCE_CAP_MIN_BYTES, DDP_OPT_COPY_BLOCKS_PER_CU = 13, 14, 15
 DDP_OPT_ACCUMULATE_BLOCKS_PER_CU, DDP_OPT_TAIL_ON_BACKWARD = 16, 17
+DDP_OPT_FLAG_ORDER, DDP_OPT_GATE_WAIT_US = 18, 19
+DDP_STAT_REPAIRED_LAUNCHES = 100
 DDP_PIPELINE_STAGED, DDP_PIPELINE_FUSED = 0, 1
 DDP_STATIC_SCRATCH_BYTES = 32 << 20
 DDP_K_PACK, DDP_K_REDUCE, DDP_K_UNPACK, DDP_K_ACCUMULATE, DDP_K_ITERATION = 0, 1, 2, 3, 4
 
 EXPORTS = [
-    "ddp_version", "ddp_last_error", "ddp_create", "ddp_destroy", "ddp_set_option",
+    "ddp_version", "ddp_last_error", "ddp_create", "ddp_destroy", "ddp_set_option", "ddp_get_option",
     "ddp_register_params", "ddp_build_buckets", "ddp_rebuild_buckets", "ddp_get_ready_order",
     "ddp_get_assignment",
     "ddp_get_bucket_info", "ddp_get_bucket_ptr", "ddp_mark_ready", "ddp_mark_ready_local",
@@ -92,6 +94,7 @@ _lib.ddp_last_error.argtypes = [_vp]
 _lib.ddp_create.argtypes = [C.POINTER(_vp), _i32, _i32, _vp, _vp]
 _lib.ddp_destroy.argtypes = [_vp]
 _lib.ddp_set_option.argtypes = [_vp, _i32, _i64]
+_lib.ddp_get_option.argtypes = [_vp, _i32, C.POINTER(_i64)]
 _lib.ddp_register_params.argtypes = [_vp, _i32, C.POINTER(_i64), C.POINTER(_i32), C.POINTER(_vp)]
 _lib.ddp_build_buckets.argtypes = [_vp, _u64]
 _lib.ddp_rebuild_buckets.argtypes = [_vp, _u64]
@@ -169,6 +172,12 @@ def ddp_destroy(ctx) -> None:
 
 def ddp_set_option(ctx, option: int, value: int) -> None:
     _check(ctx, _lib.ddp_set_option(ctx, option, value))
+
+
+def ddp_get_option(ctx, option: int) -> int:
+    value = _i64()
+    _check(ctx, _lib.ddp_get_option(ctx, option, C.byref(value)))
+    return value.value
 
 
 def ddp_register_params(ctx, numel: Sequence[int], dtype: Sequence[int],

@@ -124,6 +124,28 @@ struct ddp_ctx {
     bool backward_idle_in_call = false;           // backward stream was found drained in this API call
     bool ordered_in_call = false;   // backward stream position of this API call already examined
     std::vector<int32_t> deferred;  // buckets made launchable by the running API call, not yet enqueued
+
+    // Stream ordering through device flags (DDP_OPT_FLAG_ORDER): the backward stream announces a
+    // sequence number, a one-wave gate kernel in front of each bucket launch waits for it.
+    int32_t flag_order = -1;                      // -1 = where the streams allow it, 0 = never (events)
+    int64_t gate_wait_us = 100000;                // bound on one gate's wait
+    int32_t num_cus = 256;                        // read from the device at creation
+    char* d_order_mem = nullptr;                  // OrderState followed by the two probe words
+    ddp::OrderState* d_order = nullptr;
+    unsigned long long* d_probe = nullptr;
+    // Gate records: kGateRows rows of one record per bucket; iteration i uses row i % kGateRows.
+    // Several iterations may be enqueued before the first one's repair launch has run, and a
+    // gate of a later iteration that gives up early must not overwrite a record that an
+    // earlier iteration's repair launch has yet to read.
+    static constexpr int64_t kGateRows = 8;
+    ddp::GateRecord* d_gate = nullptr;            // [kGateRows][buckets], allocated with the buckets
+    int64_t safe_iteration = 0;                   // everything enqueued before this iteration is known to be done
+    uint64_t seq_issued = 0;                      // sequence numbers announced so far
+    uint64_t probe_value = 0;
+    uint64_t call_seq = 0;                        // the number announced for the running API call
+    bool call_by_flag = false;                    // the running API call orders its launches by flag
+    bool lane_concurrent[kMaxLanes] = {};         // probed: the lane runs concurrently with the backward stream
+    int64_t gates_in_iter = 0;                    // gate kernels enqueued in the running iteration
     std::string err;
 };
 
@@ -211,10 +233,39 @@ void drop_timed(ddp_ctx* c) {
 // A new API call begins: whatever the caller enqueued on the backward stream
 // since the last call has to be ordered before the launches of this one.
 void new_call(ddp_ctx* c) {
+    c->call_by_flag = false;
     c->ordered_in_call = false;
     c->backward_idle_in_call = false;
     c->call_event = nullptr;
     for (bool& b : c->lane_ordered) b = false;
+}
+
+// Whether lane `l` makes progress while the backward stream is busy and vice versa.  HIP
+// streams that share a hardware queue run one after the other; a gate kernel on such a lane
+// would keep the announcement it waits for from running, so those pairs keep events.  The
+// probe is a bounded wait on the lane for a value written from the backward stream.
+int32_t probe_lane(ddp_ctx* c, int l) {
+    c->lane_concurrent[l] = false;
+    if (c->lane[l] == c->backward) return DDP_OK;
+    HIPCHK(c, hipStreamSynchronize(c->lane[l]));
+    HIPCHK(c, hipStreamSynchronize(c->backward));
+    ++c->probe_value;
+    HIPCHK(c, ddp::launch_probe(c->d_probe, c->probe_value, 300 * c->wall_clock_khz / 1000, c->lane[l], c->backward));
+    HIPCHK(c, hipStreamSynchronize(c->lane[l]));
+    HIPCHK(c, hipStreamSynchronize(c->backward));
+    unsigned long long seen = 0;
+    HIPCHK(c, hipMemcpy(&seen, c->d_probe + 1, sizeof(seen), hipMemcpyDeviceToHost));
+    c->lane_concurrent[l] = seen == 1;
+    return DDP_OK;
+}
+
+// Flags order the launches of the running API call if every reduction stream in use passed
+// the probe (fused pipeline only: its kernels carry the gate check).
+bool flags_usable(const ddp_ctx* c) {
+    if (c->flag_order == 0 || c->pipeline != DDP_PIPELINE_FUSED || c->d_gate == nullptr) return false;
+    for (int l = 0; l < c->n_streams; ++l)
+        if (!c->lane_concurrent[l]) return false;
+    return true;
 }
 
 // Enqueue on a reduction stream everything buckets [first, last] need, as one
@@ -242,13 +293,14 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
     } else {
         c->tail_used = true;
     }
-    if (st != c->backward && !c->lane_ordered[lane]) {
+    const ddp::GateRecord* gate = nullptr;
+    if (st != c->backward && (!c->lane_ordered[lane] || c->call_by_flag)) {
         // Order the buckets after the gradient-producing work enqueued so far.
         // If the backward stream has already drained there is nothing to wait
         // for, and the queue packets are saved.  Within one API call the caller
         // cannot enqueue anything in between, so one look at the backward stream
-        // (and at most one event on it) serves every bucket the call launches;
-        // each reduction stream waits for that event once.
+        // (and at most one event or announcement on it) serves every bucket the
+        // call launches.
         if (!c->ordered_in_call) {
             // (a stream that is being captured into a graph cannot be queried: treat it as busy)
             hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
@@ -256,16 +308,42 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
                                    cap != hipStreamCaptureStatusNone;
             const hipError_t q = capturing ? hipErrorNotReady : hipStreamQuery(c->backward);
             if (q == hipErrorNotReady) {
-                HIPCHK(c, hipEventRecord(c->ev_ready[first], c->backward));
-                c->call_event = c->ev_ready[first];
+                if (!capturing && flags_usable(c)) {
+                    // a one-block kernel instead of an event record (which stalls the stream
+                    // for about 12 us here)
+                    c->call_seq = ++c->seq_issued;
+                    HIPCHK(c, ddp::launch_announce(c->d_order, c->call_seq, c->backward));
+                    c->call_by_flag = true;
+                } else {
+                    HIPCHK(c, hipEventRecord(c->ev_ready[first], c->backward));
+                    c->call_event = c->ev_ready[first];
+                }
             } else if (q == hipSuccess) {
                 c->backward_idle_in_call = true;
+                c->safe_iteration = c->iteration;     // every earlier iteration has finished
             } else {
                 return fail(c, DDP_ERR_HIP, std::string("hipStreamQuery: ") + hipGetErrorString(q));
             }
             c->ordered_in_call = true;
         }
-        if (!c->backward_idle_in_call) HIPCHK(c, hipStreamWaitEvent(st, c->call_event, 0));
+        if (c->call_by_flag) {
+            // every launch gets a gate of its own: if the gate gives up, exactly this launch
+            // is skipped and redone by the repair launch of the finalizing step
+            if (c->gates_in_iter == 0 && c->iteration - c->safe_iteration >= ddp_ctx::kGateRows - 1) {
+                // this iteration's row of gate records was last used kGateRows iterations ago:
+                // that iteration's repair launch must have read it
+                HIPCHK(c, hipStreamSynchronize(c->backward));
+                c->safe_iteration = c->iteration;
+            }
+            ddp::GateRecord* rec = c->d_gate + (c->iteration % ddp_ctx::kGateRows) * static_cast<int64_t>(c->plan.buckets.size()) + first;
+            HIPCHK(c, ddp::launch_gate(c->d_order, c->call_seq, c->gate_wait_us * c->wall_clock_khz / 1000, rec,
+                                       static_cast<int32_t>(tile_base), static_cast<int32_t>(ntiles), bf.dtype,
+                                       static_cast<uint32_t>(c->iteration + 1), st));
+            gate = rec;
+            ++c->gates_in_iter;
+        } else if (!c->backward_idle_in_call) {
+            HIPCHK(c, hipStreamWaitEvent(st, c->call_event, 0));
+        }
         c->lane_ordered[lane] = true;
     }
     // Participation flags travel to the device only for launches that hold a
@@ -326,7 +404,8 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_fused_reduce(bf.dtype, c->tables, tile_base, ntiles, c->R,
                                            c->write_all ? c->R : 1, d_flags, c->find_unused != 0, sc,
-                                           c->unroll, pair, c->nontemporal != 0, occupancy_lds(c, bytes), st));
+                                           c->unroll, pair, c->nontemporal != 0, occupancy_lds(c, bytes),
+                                           gate, static_cast<uint32_t>(c->iteration + 1), st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     }
     return DDP_OK;
@@ -409,6 +488,8 @@ void release_build(ddp_ctx* c) {
     if (c->d_local) (void)hipFree(c->d_local);
     if (c->d_global) (void)hipFree(c->d_global);
     if (c->d_micro) (void)hipFree(c->d_micro);
+    if (c->d_gate) (void)hipFree(c->d_gate);
+    c->d_gate = nullptr;
     for (int k = 0; k < 2; ++k) {
         if (c->h_local[k]) (void)hipHostFree(c->h_local[k]);
         c->h_local[k] = nullptr;
@@ -437,6 +518,8 @@ void release_device(ddp_ctx* c) {
     release_build(c);
     for (hipEvent_t* e : {&c->ev_done, &c->ev_micro, &c->ev_emit, &c->ev_local[0], &c->ev_local[1], &c->ev_global})
         if (*e) { (void)hipEventDestroy(*e); *e = nullptr; }
+    if (c->d_order_mem) (void)hipFree(c->d_order_mem);
+    c->d_order_mem = nullptr; c->d_order = nullptr; c->d_probe = nullptr;
     if (c->d_emit) (void)hipFree(c->d_emit);
     if (c->h_emit) (void)hipHostFree(c->h_emit);
     c->d_emit = nullptr; c->h_emit = nullptr;
@@ -498,8 +581,23 @@ int32_t ddp_create(ddp_ctx** out, int32_t R, int32_t device, void* reduce_stream
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_global, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_micro, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_emit, hipEventDisableTiming);
+        int cus = 0;
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+        if (e == hipSuccess && cus > 0) c->num_cus = cus;
+        const size_t order_bytes = sizeof(ddp::OrderState) + 2 * sizeof(unsigned long long);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_order_mem), order_bytes);
+        if (e == hipSuccess) e = hipMemset(c->d_order_mem, 0, order_bytes);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) {
             std::string msg = std::string("ddp_create: ") + hipGetErrorString(e);
+            release_device(c);
+            delete c;
+            return fail(nullptr, DDP_ERR_HIP, msg);
+        }
+        c->d_order = reinterpret_cast<ddp::OrderState*>(c->d_order_mem);
+        c->d_probe = reinterpret_cast<unsigned long long*>(c->d_order_mem + sizeof(ddp::OrderState));
+        if (probe_lane(c, 0) != DDP_OK) {
+            std::string msg = "ddp_create: stream probe: " + c->err;
             release_device(c);
             delete c;
             return fail(nullptr, DDP_ERR_HIP, msg);
@@ -572,12 +670,34 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
                 HIPCHK(c, hipSetDevice(c->device));
                 for (int l = 1; l < value; ++l) {
                     if (c->lane[l]) continue;
-                    // default priority, and no implicit ordering with the legacy default stream
-                    HIPCHK(c, hipStreamCreateWithFlags(&c->lane[l], hipStreamNonBlocking));
+                    // default priority, and no implicit ordering with the legacy default stream.
+                    // A new stream may land on the hardware queue of the backward stream; a few
+                    // more are tried then (the misfits are destroyed once one fits, so that the
+                    // next try does not get the same queue again).
+                    hipStream_t misfit[6];
+                    int misfits = 0;
+                    for (;;) {
+                        HIPCHK(c, hipStreamCreateWithFlags(&c->lane[l], hipStreamNonBlocking));
+                        const int32_t rc = probe_lane(c, l);
+                        if (rc != DDP_OK) return rc;
+                        if (c->lane_concurrent[l] || misfits == 6) break;
+                        misfit[misfits++] = c->lane[l];
+                    }
+                    for (int k = 0; k < misfits; ++k) (void)hipStreamDestroy(misfit[k]);
                     HIPCHK(c, hipEventCreateWithFlags(&c->ev_join[l], kOrderEvent));
                 }
             }
             c->n_streams = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_FLAG_ORDER:
+            if (value != -1 && value != 0) return fail(c, DDP_ERR_ARG, "flag ordering must be -1 (where possible) or 0 (never)");
+            if (c->tracker.marks() != 0 || !c->log_running.empty())
+                return fail(c, DDP_ERR_STATE, "the ordering mode can only change between iterations");
+            c->flag_order = static_cast<int32_t>(value);
+            return DDP_OK;
+        case DDP_OPT_GATE_WAIT_US:
+            if (value < 0 || value > 10000000) return fail(c, DDP_ERR_ARG, "gate wait outside [0, 10 s]");
+            c->gate_wait_us = value;
             return DDP_OK;
         case DDP_OPT_COALESCE:
             if (value < -1) return fail(c, DDP_ERR_ARG, "bad size");
@@ -603,6 +723,33 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             return DDP_OK;
         default:
             return fail(c, DDP_ERR_ARG, "unknown option");
+    }
+}
+
+int32_t ddp_get_option(ddp_ctx* c, int32_t option, int64_t* value) {
+    if (!c || !value) return DDP_ERR_ARG;
+    switch (option) {
+        case DDP_STAT_REPAIRED_LAUNCHES: {
+            *value = 0;
+            if (c->plan_only) return DDP_OK;
+            HIPCHK(c, hipSetDevice(c->device));
+            const int32_t rc = ddp_synchronize(c);
+            if (rc != DDP_OK) return rc;
+            uint32_t n = 0;
+            HIPCHK(c, hipMemcpy(&n, &c->d_order->repaired, sizeof(n), hipMemcpyDeviceToHost));
+            *value = n;
+            return DDP_OK;
+        }
+        case DDP_OPT_PIPELINE: *value = c->pipeline; return DDP_OK;
+        case DDP_OPT_WRITE_ALL: *value = c->write_all; return DDP_OK;
+        case DDP_OPT_TIMING: *value = c->timing; return DDP_OK;
+        case DDP_OPT_FIND_UNUSED: *value = c->find_unused; return DDP_OK;
+        case DDP_OPT_REDUCE_STREAMS: *value = c->n_streams; return DDP_OK;
+        case DDP_OPT_COALESCE: *value = coalesce_limit(c); return DDP_OK;
+        case DDP_OPT_TAIL_ON_BACKWARD: *value = c->tail_on_backward; return DDP_OK;
+        case DDP_OPT_GATE_WAIT_US: *value = c->gate_wait_us; return DDP_OK;
+        case DDP_OPT_FLAG_ORDER: *value = flags_usable(c) ? 1 : 0; return DDP_OK;
+        default: return DDP_ERR_ARG;
     }
 }
 
@@ -697,6 +844,10 @@ static int32_t build_internal(ddp_ctx* c, uint64_t cap_bytes, const std::vector<
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_global), static_cast<size_t>(n), hipHostMallocDefault));
         HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_micro), sizeof(void*) * R * n));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_micro), sizeof(void*) * R * n, hipHostMallocDefault));
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_gate), sizeof(ddp::GateRecord) * nb * ddp_ctx::kGateRows));
+        HIPCHK(c, hipMemset(c->d_gate, 0, sizeof(ddp::GateRecord) * nb * ddp_ctx::kGateRows));
+        c->gates_in_iter = 0;
+        c->safe_iteration = c->iteration;
         c->ev_ready.resize(nb, nullptr);
         for (int32_t b = 0; b < nb; ++b)
             HIPCHK(c, hipEventCreateWithFlags(&c->ev_ready[b], kOrderEvent));
@@ -906,6 +1057,8 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             }
         // the interval of this iteration's bucket launches ends here if all of them ran on the
         // reduction side, else on the backward stream below
+        // an iteration that used gates ends with the repair launch on the backward stream
+        if (c->gates_in_iter > 0) c->tail_used = true;
         if (c->open_group != static_cast<size_t>(-1) && !c->tail_used) {
             HIPCHK(c, hipEventRecord(c->timed[c->open_group].stop, c->reduce));
             c->open_group = static_cast<size_t>(-1);
@@ -945,6 +1098,23 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             HIPCHK(c, hipEventRecord(c->ev_done, c->reduce));
             HIPCHK(c, hipStreamWaitEvent(c->backward, c->ev_done, 0));
         }
+        if (c->gates_in_iter > 0) {
+            // Gates wait a bounded time.  Launches whose gate gave up did nothing; they are
+            // redone now that every gradient exists (normally there is none and the launch
+            // ends at once).  With a zero participation flag in the iteration the whole
+            // bitmap is on the device by now (copied above on the reduction stream).
+            uint32_t dtypes_seen = 0;
+            for (const ddp::BucketInfo& bk : c->plan.buckets) dtypes_seen |= 1u << bk.dtype;
+            for (int dt = 0; dt < 3; ++dt)
+                if (dtypes_seen & (1u << dt))
+                    HIPCHK(c, ddp::launch_repair(dt, c->tables, c->d_order,
+                                                 c->d_gate + (c->iteration % ddp_ctx::kGateRows) * static_cast<int64_t>(c->plan.buckets.size()),
+                                                 static_cast<int>(c->plan.buckets.size()),
+                                                 static_cast<uint32_t>(c->iteration + 1), c->R,
+                                                 c->write_all ? c->R : 1, c->iter_zero ? c->d_local : nullptr,
+                                                 c->find_unused != 0, make_scale(c->R), 2 * c->num_cus,
+                                                 c->nontemporal != 0, c->backward));
+        }
         // from here on the backward stream is behind everything of this iteration
         if (c->pin_ready_iter == c->iteration) {      // the flag staging buffer was used: free for reuse after this
             HIPCHK(c, hipEventRecord(c->ev_local[par], c->backward));
@@ -975,6 +1145,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     for (bool& b : c->lane_used) b = false;
     c->launches_in_iter = 0;
     c->tail_used = false;
+    c->gates_in_iter = 0;
     ++c->iteration;
     c->tracker.new_iteration();
     return DDP_OK;
@@ -1003,6 +1174,7 @@ int32_t ddp_synchronize(ddp_ctx* c) {
     for (int l = 1; l < ddp_ctx::kMaxLanes; ++l)
         if (c->lane[l]) HIPCHK(c, hipStreamSynchronize(c->lane[l]));
     HIPCHK(c, hipStreamSynchronize(c->reduce));
+    c->safe_iteration = c->iteration;
     return DDP_OK;
 }
 

@@ -97,9 +97,61 @@ hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* 
 // (a replica with flag 0 contributes +0 and is not read; a parameter nobody
 // used is skipped with keep_unused, else written as zeros).  pair = blocks
 // take two tiles each (for large launches).
+struct GateRecord;   // below, with the flag-ordering kernels
+
+// gate (may be null): the record of the gate kernel enqueued in front of this
+// launch; if gate->failed_tag == tag the launch does nothing.
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
-                               int unroll, bool pair, bool nontemporal, unsigned lds, hipStream_t s);
+                               int unroll, bool pair, bool nontemporal, unsigned lds,
+                               const GateRecord* gate, uint32_t tag, hipStream_t s);
+
+// ---- stream ordering through device flags -------------------------------------
+// A bucket launch on a reduction stream must come after the backward-stream work
+// that produces its gradients (Section 3.2.3).  Instead of an event pair per
+// launch, the backward stream announces its position with a one-block kernel
+// that stores a sequence number, and the reduction stream runs a one-wave gate
+// kernel in front of the bucket kernel that polls for it.  The gate's wait is
+// bounded; a gate that gives up marks its launch as failed, the bucket kernel
+// that follows sees the mark and does nothing, and the repair launch enqueued by
+// the finalizing step (when every gradient exists) redoes exactly those launches.
+struct OrderState {
+    unsigned long long ready_seq;   // latest announced sequence number (monotonic)
+    unsigned long long pad0[15];    // the polled word has a cache line of its own
+    uint32_t abort_tag;             // == iteration tag: a gate of this iteration has given up,
+                                    //    later gates of the iteration give up at once
+    uint32_t repaired;              // launches redone by repair launches since the context was created
+    uint32_t pad1[30];
+};
+
+struct GateRecord {                 // one per bucket, used by the launch whose first bucket it is
+    int32_t tile_base;              // tile range of the launch
+    int32_t ntiles;
+    uint32_t failed_tag;            // == iteration tag: the gate gave up, the launch did nothing
+    int32_t dtype;
+};
+
+// backward stream: ready_seq = seq (release: everything enqueued before is visible
+// to whoever observes the number).
+hipError_t launch_announce(OrderState* st, unsigned long long seq, hipStream_t s);
+
+// reduction stream: wait (at most wait_ticks of the device wall clock) until
+// ready_seq >= need; on failure fill *rec and raise abort_tag.
+hipError_t launch_gate(OrderState* st, unsigned long long need, long long wait_ticks, GateRecord* rec,
+                       int32_t tile_base, int32_t ntiles, int32_t dtype, uint32_t tag, hipStream_t s);
+
+// Redo the launches of element type `dtype` whose gate gave up in iteration `tag`
+// (rec[0..nb)).  `blocks` persistent blocks; normally there is nothing to do.
+hipError_t launch_repair(int dtype, const SegTables& t, OrderState* st, const GateRecord* rec, int nb, uint32_t tag,
+                         int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
+                         int blocks, bool nontemporal, hipStream_t s);
+
+// Bounded probe: one wave on stream `waiter` polls word[0] for `value` (at most
+// wait_ticks), then a one-thread kernel on stream `writer` stores it.
+// word[1] = 1 if the waiter saw the value, i.e. if the two streams make progress
+// independently (streams that share a hardware queue run one after the other).
+hipError_t launch_probe(unsigned long long* word, unsigned long long value, long long wait_ticks,
+                        hipStream_t waiter, hipStream_t writer);
 
 // global[g] = OR_r local[g*R + r]  (the bitmap AllReduce of Section 4.2).
 hipError_t launch_bitmap_or(const uint8_t* local, uint8_t* global, int G, int R, hipStream_t s);

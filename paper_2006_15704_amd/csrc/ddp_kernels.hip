@@ -568,11 +568,20 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
     }
 }
 
+// gate / tag: see GateRecord.  A launch whose gate gave up must not touch
+// gradients that may still be incomplete; the repair launch redoes it.
+__device__ __forceinline__ bool gate_failed(const GateRecord* __restrict__ gate, uint32_t tag) {
+    return gate != nullptr && gate->failed_tag == tag;
+}
+
 template <int DT, bool NT, int U>
 __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int64_t tile_base, int R,
                                                              int nwrite,
                                                              const uint8_t* __restrict__ local,
-                                                             int keep_unused, Scale sc) {
+                                                             int keep_unused, Scale sc,
+                                                             const GateRecord* __restrict__ gate,
+                                                             uint32_t tag) {
+    if (gate_failed(gate, tag)) return;
     fused_tile<DT, NT, U>(t, tile_base + blockIdx.x, R, nwrite, local, keep_unused, sc);
 }
 
@@ -583,10 +592,13 @@ template <int DT, bool NT, int U>
 __global__ __launch_bounds__(BLOCK) void fused_reduce_pair_kernel(SegTables t, int64_t tile_base,
                                                                   int64_t tile_end, int R, int nwrite,
                                                                   const uint8_t* __restrict__ local,
-                                                                  int keep_unused, Scale sc) {
+                                                                  int keep_unused, Scale sc,
+                                                                  const GateRecord* __restrict__ gate,
+                                                                  uint32_t tag) {
     constexpr int ES = Fmt<DT>::ES;
     constexpr int VEC = Fmt<DT>::VEC;
     constexpr int U2 = 2 * U;
+    if (gate_failed(gate, tag)) return;
     static_assert(TILE_VECS == BLOCK * U, "pairing assumes one step per tile");
     const int64_t tile_a = tile_base + 2 * static_cast<int64_t>(blockIdx.x);
     const int64_t tile_b = tile_a + 1;
@@ -627,6 +639,80 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_pair_kernel(SegTables t, i
         return;
     }
     fused_tile<DT, NT, U>(t, tile_a, R, nwrite, local, keep_unused, sc);
+}
+
+// ---- stream ordering through device flags ------------------------------------
+constexpr uint32_t MAX_GATE_POLLS = 1u << 22;
+
+__global__ __launch_bounds__(64) void announce_kernel(OrderState* st, unsigned long long seq) {
+    if (threadIdx.x == 0)
+        __hip_atomic_store(&st->ready_seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One wave; lane 0 polls.  Both bounds (wall-clock ticks and the poll count) end
+// the loop whatever the other stream does.
+__global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long long need,
+                                                  long long wait_ticks, GateRecord* rec,
+                                                  int32_t tile_base, int32_t ntiles, int32_t dtype,
+                                                  uint32_t tag) {
+    if (threadIdx.x != 0) return;
+    bool ok = false;
+    if (__hip_atomic_load(&st->abort_tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tag) {
+        const uint64_t t0 = wall_clock64();
+        for (uint32_t poll = 0; poll < MAX_GATE_POLLS; ++poll) {
+            if (__hip_atomic_load(&st->ready_seq, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= need) {
+                ok = true;
+                break;
+            }
+            if (static_cast<long long>(wall_clock64() - t0) >= wait_ticks) break;
+            __builtin_amdgcn_s_sleep(16);
+        }
+    }
+    if (!ok) {
+        rec->tile_base = tile_base;
+        rec->ntiles = ntiles;
+        rec->dtype = dtype;
+        rec->failed_tag = tag;
+        __hip_atomic_store(&st->abort_tag, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Launches whose gate gave up, redone once every gradient exists.  Block j takes
+// the tiles j, j + G, ... of each failed launch.
+template <int DT, bool NT, int U>
+__global__ __launch_bounds__(BLOCK) void repair_kernel(SegTables t, OrderState* st,
+                                                       const GateRecord* __restrict__ rec,
+                                                       int nb, uint32_t tag, int R, int nwrite,
+                                                       const uint8_t* __restrict__ local,
+                                                       int keep_unused, Scale sc) {
+    for (int b = 0; b < nb; ++b) {
+        const GateRecord r = rec[b];
+        if (r.failed_tag != tag || r.dtype != DT) continue;
+        if (blockIdx.x == 0 && threadIdx.x == 0) st->repaired += 1;   // (repair launches run one after the other)
+        for (int64_t i = blockIdx.x; i < r.ntiles; i += gridDim.x)
+            fused_tile<DT, NT, U>(t, r.tile_base + i, R, nwrite, local, keep_unused, sc);
+    }
+}
+
+__global__ __launch_bounds__(64) void probe_wait_kernel(unsigned long long* word, unsigned long long value,
+                                                        long long wait_ticks) {
+    if (threadIdx.x != 0) return;
+    const uint64_t t0 = wall_clock64();
+    unsigned long long seen = 0;
+    for (uint32_t poll = 0; poll < MAX_GATE_POLLS; ++poll) {
+        if (__hip_atomic_load(&word[0], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == value) {
+            seen = 1;
+            break;
+        }
+        if (static_cast<long long>(wall_clock64() - t0) >= wait_ticks) break;
+        __builtin_amdgcn_s_sleep(16);
+    }
+    word[1] = seen;
+}
+
+__global__ __launch_bounds__(64) void probe_write_kernel(unsigned long long* word, unsigned long long value) {
+    if (threadIdx.x == 0)
+        __hip_atomic_store(&word[0], value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- K4: no_sync accumulation ---------------------------------------------
@@ -832,38 +918,79 @@ hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* 
 
 template <int DT, int U>
 static hipError_t fused_dispatch(bool nt, dim3 grid, unsigned lds, hipStream_t s, const SegTables& t,
-                                 int64_t tile_base, int R, int nwrite, const uint8_t* local, int keep, Scale sc) {
-    if (nt) return launch(fused_reduce_kernel<DT, true, U>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
-    return launch(fused_reduce_kernel<DT, false, U>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
+                                 int64_t tile_base, int R, int nwrite, const uint8_t* local, int keep, Scale sc,
+                                 const GateRecord* gate, uint32_t tag) {
+    if (nt) return launch(fused_reduce_kernel<DT, true, U>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+    return launch(fused_reduce_kernel<DT, false, U>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
 }
 
 template <int DT>
 static hipError_t fused_unroll(int unroll, bool pair, bool nt, int64_t ntiles, unsigned lds, hipStream_t s,
                                const SegTables& t, int64_t tile_base, int R, int nwrite,
-                               const uint8_t* local, int keep, Scale sc) {
+                               const uint8_t* local, int keep, Scale sc, const GateRecord* gate, uint32_t tag) {
     constexpr int UMAX = TILE_VECS / BLOCK;      // a tile holds at most this many vectors per thread
     if (pair) {
         dim3 grid(static_cast<unsigned>((ntiles + 1) / 2));
-        if (nt) return launch(fused_reduce_pair_kernel<DT, true, UMAX>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc);
-        return launch(fused_reduce_pair_kernel<DT, false, UMAX>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc);
+        if (nt) return launch(fused_reduce_pair_kernel<DT, true, UMAX>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc, gate, tag);
+        return launch(fused_reduce_pair_kernel<DT, false, UMAX>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc, gate, tag);
     }
     dim3 grid(static_cast<unsigned>(ntiles));
-    if (unroll >= 4 && UMAX >= 4) return fused_dispatch<DT, (UMAX >= 4 ? 4 : 1)>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
-    if (unroll >= 2 && UMAX >= 2) return fused_dispatch<DT, (UMAX >= 2 ? 2 : 1)>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
-    return fused_dispatch<DT, 1>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc);
+    if (unroll >= 4 && UMAX >= 4) return fused_dispatch<DT, (UMAX >= 4 ? 4 : 1)>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+    if (unroll >= 2 && UMAX >= 2) return fused_dispatch<DT, (UMAX >= 2 ? 2 : 1)>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+    return fused_dispatch<DT, 1>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
 }
 
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
-                               int unroll, bool pair, bool nontemporal, unsigned lds, hipStream_t s) {
+                               int unroll, bool pair, bool nontemporal, unsigned lds,
+                               const GateRecord* gate, uint32_t tag, hipStream_t s) {
     if (ntiles <= 0) return hipSuccess;
     const int keep = keep_unused ? 1 : 0;
     switch (dtype) {
-        case 0: return fused_unroll<0>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc);
-        case 1: return fused_unroll<1>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc);
-        case 2: return fused_unroll<2>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc);
+        case 0: return fused_unroll<0>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        case 1: return fused_unroll<1>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        case 2: return fused_unroll<2>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_announce(OrderState* st, unsigned long long seq, hipStream_t s) {
+    hipLaunchKernelGGL(announce_kernel, dim3(1), dim3(64), 0, s, st, seq);
+    return after_launch();
+}
+
+hipError_t launch_gate(OrderState* st, unsigned long long need, long long wait_ticks, GateRecord* rec,
+                       int32_t tile_base, int32_t ntiles, int32_t dtype, uint32_t tag, hipStream_t s) {
+    hipLaunchKernelGGL(gate_kernel, dim3(1), dim3(64), 0, s, st, need, wait_ticks, rec, tile_base, ntiles,
+                       dtype, tag);
+    return after_launch();
+}
+
+hipError_t launch_repair(int dtype, const SegTables& t, OrderState* st, const GateRecord* rec, int nb, uint32_t tag,
+                         int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
+                         int blocks, bool nt, hipStream_t s) {
+    if (blocks <= 0 || nb <= 0) return hipSuccess;
+    constexpr int U = TILE_VECS / BLOCK >= 2 ? 2 : 1;
+    const dim3 grid(static_cast<unsigned>(blocks));
+    const int keep = keep_unused ? 1 : 0;
+    switch (dtype) {
+        case 0: return nt ? launch(repair_kernel<0, true, U>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc)
+                          : launch(repair_kernel<0, false, U>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc);
+        case 1: return nt ? launch(repair_kernel<1, true, U>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc)
+                          : launch(repair_kernel<1, false, U>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc);
+        case 2: return nt ? launch(repair_kernel<2, true, U>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc)
+                          : launch(repair_kernel<2, false, U>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_probe(unsigned long long* word, unsigned long long value, long long wait_ticks,
+                        hipStream_t waiter, hipStream_t writer) {
+    hipLaunchKernelGGL(probe_wait_kernel, dim3(1), dim3(64), 0, waiter, word, value, wait_ticks);
+    hipError_t e = after_launch();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(probe_write_kernel, dim3(1), dim3(64), 0, writer, word, value);
+    return after_launch();
 }
 
 hipError_t launch_accumulate(const SegTables& t, int64_t ntiles, int R, int n, void* const* micro,

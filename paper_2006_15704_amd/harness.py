@@ -93,19 +93,31 @@ class Session:
     def __init__(self, grads: DeviceGrads, cap_bytes: int, pipeline: int = B.DDP_PIPELINE_STAGED,
                  write_all: bool = False, same_stream: bool = False, streams=None):
         self.grads = grads
-        if streams is not None:          # (reduce, backward) of another session: contexts that share them
-            self.reduce_stream, self.backward_stream = streams
-        else:
-            self.reduce_stream = torch.cuda.Stream(device=grads.device)
-            self.backward_stream = self.reduce_stream if same_stream else torch.cuda.Stream(device=grads.device)
-        torch.cuda.synchronize()
-        self.ctx = B.ddp_create(grads.R, 0, self.reduce_stream.cuda_stream,
-                                self.backward_stream.cuda_stream)
-        B.ddp_set_option(self.ctx, B.DDP_OPT_PIPELINE, pipeline)
-        B.ddp_set_option(self.ctx, B.DDP_OPT_WRITE_ALL, 1 if write_all else 0)
-        B.ddp_register_params(self.ctx, grads.numel, grads.dtype, grads.ptrs())
-        self.n_buckets = B.ddp_build_buckets(self.ctx, cap_bytes)
         self.pipeline = pipeline
+        self.ctx = None
+        # HIP streams that share a hardware queue run one after the other: a reduction stream
+        # like that overlaps nothing.  The library probes the pair it is given
+        # (DDP_OPT_FLAG_ORDER reads 1 if the streams run concurrently); new streams are tried
+        # until a pair passes, the last pair is used as it is.
+        for attempt in range(8):
+            if streams is not None:      # (reduce, backward) of another session: contexts that share them
+                self.reduce_stream, self.backward_stream = streams
+            elif attempt == 0 or not same_stream:
+                self.reduce_stream = torch.cuda.Stream(device=grads.device)
+                self.backward_stream = self.reduce_stream if same_stream else torch.cuda.Stream(device=grads.device)
+            torch.cuda.synchronize()
+            self.ctx = B.ddp_create(grads.R, 0, self.reduce_stream.cuda_stream,
+                                    self.backward_stream.cuda_stream)
+            B.ddp_set_option(self.ctx, B.DDP_OPT_PIPELINE, pipeline)
+            B.ddp_set_option(self.ctx, B.DDP_OPT_WRITE_ALL, 1 if write_all else 0)
+            B.ddp_register_params(self.ctx, grads.numel, grads.dtype, grads.ptrs())
+            self.n_buckets = B.ddp_build_buckets(self.ctx, cap_bytes)
+            self.streams_concurrent = bool(B.ddp_get_option(self.ctx, B.DDP_OPT_FLAG_ORDER))
+            if (self.streams_concurrent or streams is not None or same_stream
+                    or pipeline != B.DDP_PIPELINE_FUSED or attempt == 7):
+                break
+            B.ddp_destroy(self.ctx)
+            self.ctx = None
 
     def sync(self, ready_order: Optional[Sequence[int]] = None, one_by_one: bool = False) -> None:
         """mark every parameter of ready_order (default: reverse registration

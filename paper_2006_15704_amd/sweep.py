@@ -99,6 +99,9 @@ def main() -> int:
                          "parameters, the blocks shuffled (0 = plain reverse order).  Every "
                          "configuration is then measured twice: with the default mapping and after "
                          "ddp_rebuild_buckets has followed the traced order (Section 6.2.1)")
+    ap.add_argument("--flag-order", type=int, default=-1, choices=[-1, 0],
+                    help="DDP_OPT_FLAG_ORDER: -1 = bucket launches are ordered after the backward stream "
+                         "through device flags where the streams allow it, 0 = through events")
     ap.add_argument("--produce", action="store_true",
                     help="the synthetic backward also writes every gradient (copies it from a "
                          "source buffer after the delay), which keeps the memory system busy "
@@ -141,6 +144,8 @@ def main() -> int:
                 ctx = s.ctx
                 lib.ddp_set_option(ctx, lib.DDP_OPT_EMIT_BUSY_BLOCKS, args.busy_blocks)
                 lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_STREAMS, n_streams)
+                lib.ddp_set_option(ctx, lib.DDP_OPT_FLAG_ORDER, args.flag_order)
+                by_flags = bool(lib.ddp_get_option(ctx, lib.DDP_OPT_FLAG_ORDER))
                 lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE,
                                    (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * MIB))
 
@@ -182,7 +187,7 @@ def main() -> int:
                             "cap_mib": cap_mib, "n_buckets": n_buckets, "streams": n_streams,
                             "coalesce_mib": args.coalesce_mib, "delay_us_per_param": d_us,
                             "order": f"blocks of {args.shuffle_blocks} shuffled" if args.shuffle_blocks else "reverse",
-                            "mapping": mapping,
+                            "mapping": mapping, "ordered_by": "flags" if by_flags else "events",
                             "backward_writes_gradients": bool(src_ptrs), "busy_blocks": args.busy_blocks,
                             "t_backward_ms": round(t_bwd, 4), "t_sync_ms": round(t_sync, 4),
                             "t_total_ms": round(t_tot, 4), "exposed_ms": round(exposed, 4),

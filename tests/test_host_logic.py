@@ -347,3 +347,25 @@ def test_compute_context_without_gpu_fails_loudly(d):
     with pytest.raises(d.DdpError) as e:
         d.ddp_create(2, 0)
     assert e.value.code == d.DDP_ERR_HIP
+
+
+def test_options_read_back_on_a_plan_only_context(d):
+    ctx, nb = plan(d, [100, 200, 300], [0, 0, 0], 1 << 20)
+    try:
+        assert d.ddp_get_option(ctx, d.DDP_OPT_REDUCE_STREAMS) == 1
+        assert d.ddp_get_option(ctx, d.DDP_OPT_GATE_WAIT_US) == 100000
+        d.ddp_set_option(ctx, d.DDP_OPT_GATE_WAIT_US, 5)
+        assert d.ddp_get_option(ctx, d.DDP_OPT_GATE_WAIT_US) == 5
+        # nothing can be ordered through device flags without a device
+        assert d.ddp_get_option(ctx, d.DDP_OPT_FLAG_ORDER) == 0
+        assert d.ddp_get_option(ctx, d.DDP_STAT_REPAIRED_LAUNCHES) == 0
+        assert d.ddp_get_option(ctx, d.DDP_OPT_COALESCE) > 0          # the limit chosen from R
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_get_option(ctx, 9999)
+        assert e.value.code == d.DDP_ERR_ARG
+        for bad in (1, -2):
+            with pytest.raises(d.DdpError) as e:
+                d.ddp_set_option(ctx, d.DDP_OPT_FLAG_ORDER, bad)
+            assert e.value.code == d.DDP_ERR_ARG
+    finally:
+        d.ddp_destroy(ctx)
