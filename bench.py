@@ -2,34 +2,41 @@
 """Benchmark of bucketed gradient synchronization on one MI355X.
 
 One "step" is one pass of the whole hot path over one batch of synthetic
-gradients, through the C ABI: ready marks for every parameter in reverse
-registration order (each bucket is launched as soon as it is complete and its
-predecessors have been launched), then the finalizing step.  The marks of a
-step arrive in one call, so with the library's defaults consecutive buckets
-share a kernel launch up to 100 MiB (DDP_OPT_COALESCE); the
-`one_launch_per_bucket` and `two_streams` sub-objects report the same steps
-with a launch per bucket.  Inputs are resident in HBM before the timed region
-starts.  The default pipeline is the
-one-pass (fused) one; `--pipeline staged` times the literal pack / reduce /
-unpack pipeline instead, and the default run also reports the staged
-pipeline's per-kernel rates in a `staged` sub-object.
+gradients, through the C ABI, the way a backward pass drives it (Algorithm 1):
+one ddp_mark_ready call per parameter, in reverse registration order -- every
+bucket is launched by the call that completes it, on the reduction streams --
+and then ddp_finalize_backward.  Library defaults throughout.  Inputs are
+resident in HBM before the timed region starts, and consecutive steps work on
+different sets of replica gradients (four sets, several GB), so that the
+256 MB Infinity Cache cannot serve a step from what the previous one left.
 
 Prints ONE JSON line.
-  value     (R + W) * B / ms_per_step: every replica gradient read once, the
-            average written W = 1 times -- the algorithmic end-to-end bytes of
-            one synchronization divided by the measured step time.
-  roofline  the reduce kernel (the dominant one) against the 8 TB/s HBM peak:
-            algorithmic bytes per launch = (R + 1) * bytes of the buckets the
-            launch covers, divided by the average launch duration: the time
-            between two HIP events around the timed region (on the stream the
-            launches run on or are waited for by) divided by the launches.
-  cpu_baseline  the CPU oracle on the same workload.
+  value     (R + W) * B / ms_per_step for the ResNet-50-shaped list (R = 8):
+            every replica gradient read once, the average written W = 1 times,
+            divided by the wall-clock time of a step.
+  roofline  the reduce kernel (fused_reduce_kernel, the dominant one) against
+            the 8 TB/s HBM peak: algorithmic bytes per launch = (R + 1) * bytes
+            of the bucket(s) a launch covers; average launch duration = the time
+            between two HIP events around the timed region (on the backward
+            stream, which every launch runs on or is joined to by finalize)
+            divided by the number of launches.
+  bert_large    the same measurement on the BERT-large-shaped list (the metric
+            is quoted on both shapes).
+  marks_in_one_call   both shapes again with all marks of a step in ONE
+            ddp_mark_ready_many call (consecutive buckets then share launches).
+  overlap   configuration 4 in short: ResNet-50 shape in fp16, R = 16, a synthetic
+            backward stream of one 10 us kernel per parameter; exposed time of
+            the synchronization per bucket cap.
+  bert_large_r32   configuration 5's reduction (R = 32) and no_sync accumulation.
+  cpu_baseline  the CPU oracle on a bounded sample of the headline workload,
+            one thread and all host cores.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 from concurrent.futures import ThreadPoolExecutor
@@ -41,32 +48,44 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0     # MI355X published HBM3E bandwidth
+MIB = 1 << 20
 
 WORKLOADS = {
     # name: (shape list, config id, R, sigma, dtype code, cap bytes)
-    "resnet50": ("resnet50", 2, 8, 1e-2, 0, 25 << 20),
-    "bert_large": ("bert_large", 3, 8, 1e-3, 0, 25 << 20),
-    "resnet50_fp16_r16": ("resnet50", 4, 16, 1e-2, 1, 25 << 20),      # the bucket-size sweep's configuration
-    "bert_large_bf16": ("bert_large", 3, 8, 1e-3, 2, 25 << 20),        # diagnostic: 16-bit storage at BERT size
-    "bert_large_r32": ("bert_large", 5, 32, 1e-3, 0, 25 << 20),        # configuration 5's reduction (R = 32)
-    "tiny": ("tiny", 1, 2, 1.0, 0, 16384),
-    "uniform": ("uniform", 9, 8, 1e-2, 0, 25 << 20),     # diagnostic: 40 single-tensor 25 MiB buckets
+    "resnet50": ("resnet50", 2, 8, 1e-2, 0, 25 * MIB),
+    "bert_large": ("bert_large", 3, 8, 1e-3, 0, 25 * MIB),
+    "resnet50_fp16_r16": ("resnet50", 4, 16, 1e-2, 1, 25 * MIB),      # the bucket-size sweep's configuration
+    "bert_large_r32": ("bert_large", 5, 32, 1e-3, 0, 25 * MIB),        # configuration 5's reduction (R = 32)
 }
+ALL_LEGS = ["headline", "bert_large", "one_call", "single_set", "per_bucket", "overlap", "r32", "staged",
+            "accumulate", "cpu"]
+DT_NAME = {0: "f32", 1: "f16", 2: "bf16"}
 
 
-def generate_replicas(config_id, numel, R, sigma, dtype, threads=16):
-    import workloads
-    jobs = [(r, p) for r in range(R) for p in range(len(numel))]
-    with ThreadPoolExecutor(max_workers=threads) as pool:
-        flat = list(pool.map(
-            lambda rp: workloads.gaussian_grad(config_id, rp[0], 0, rp[1], numel[rp[1]], sigma, dtype), jobs))
+def device_grads(harness, torch, numel, dtype, R, sigma, seed, fill_noise=True):
+    """R replica buffers with seeded Gaussian gradients generated on the device
+    (the same distribution as the host recipe of the parity tests; the bits
+    differ, which no throughput figure depends on)."""
     n = len(numel)
-    return [flat[r * n:(r + 1) * n] for r in range(R)]
+    g = harness.DeviceGrads(numel, [dtype] * n, R)
+    if fill_noise:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed)
+        for r in range(R):
+            buf = g.bufs[r]
+            usable = buf.numel() // 4 * 4
+            if dtype == 0:
+                buf[:usable].view(torch.float32).normal_(0.0, sigma, generator=gen)
+            elif dtype == 1:
+                buf[:usable].view(torch.float16).normal_(0.0, sigma, generator=gen)
+            else:
+                buf[:usable].view(torch.bfloat16).normal_(0.0, sigma, generator=gen)
+    return g
 
 
-def read_traffic(workload, pipeline):
+def read_traffic(workload, mode):
     """HBM bytes per reduce launch from the committed counter summary, if any."""
-    path = os.path.join(ROOT, "profiles", f"reduce_traffic_{workload}_{pipeline}.json")
+    path = os.path.join(ROOT, "profiles", f"reduce_traffic_{workload}_{mode}.json")
     try:
         with open(path) as fh:
             return json.load(fh).get("traffic_bytes_per_launch")
@@ -74,138 +93,395 @@ def read_traffic(workload, pipeline):
         return None
 
 
-def measure(lib, harness, torch, grads, cap, pipeline_code, order, steps, warmup, timing_mode, args):
-    """Runs warmup + `steps` timed steps on a fresh context; returns a dict."""
-    with harness.Session(grads, cap, pipeline_code, same_stream=args.same_stream) as s:
-        ctx = s.ctx
-        if args.reduce_blocks is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_BLOCKS, args.reduce_blocks)
-        if args.plain_loads:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_NONTEMPORAL, 0)
-        if args.unroll is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_UNROLL, args.unroll)
-        if args.copy_nt_store:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_COPY_NT_STORE, 1)
-        if args.coalesce_mib is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE,
-                               (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * (1 << 20)))
-        if args.streams is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_STREAMS, args.streams)
-        if args.tail_on_backward is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_TAIL_ON_BACKWARD, args.tail_on_backward)
-        if args.blocks_per_cu is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_BLOCKS_PER_CU, args.blocks_per_cu)
-        if args.copy_blocks_per_cu is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_COPY_BLOCKS_PER_CU, args.copy_blocks_per_cu)
-        if args.cap_min_mib is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_REDUCE_CAP_MIN_BYTES, int(args.cap_min_mib * (1 << 20)))
-        if args.pair_min_mib is not None:
-            lib.ddp_set_option(ctx, lib.DDP_OPT_PAIR_MIN_BYTES, int(args.pair_min_mib * (1 << 20)))
+def spread(values):
+    v = [float(x) for x in values]
+    return {"median": round(statistics.median(v), 5), "min": round(min(v), 5), "max": round(max(v), 5), "n": len(v)}
 
-        def step():
-            lib.ddp_mark_ready_many(ctx, order)
-            lib.ddp_finalize_backward(ctx)
 
-        for _ in range(warmup):
-            step()
-        lib.ddp_synchronize(ctx)
-        torch.cuda.synchronize()
+class Rig:
+    """`sets` independent sets of replica gradients of one workload, one context
+    per set, all contexts on the same pair of streams."""
 
-        launches_per_step = None
-        if timing_mode == "region":
-            # one more untimed step with the library's per-iteration events, to count the launches
-            lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 2)
-            step()
-            lib.ddp_synchronize(ctx)
-            launches_per_step = int(lib.ddp_get_kernel_times(ctx, lib.DDP_K_ITERATION)[1].sum())
-            lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 0)
+    def __init__(self, lib, harness, torch, workload, sets, pipeline, options=(), same_stream=False):
+        self.lib, self.torch = lib, torch
+        shape_name, self.config_id, self.R, self.sigma, self.dtype, self.cap = WORKLOADS[workload]
+        import workloads
+        self.numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[shape_name]())
+        self.n = len(self.numel)
+        self.es = harness.ESIZE[self.dtype]
+        self.B = sum(self.numel) * self.es
+        self.order = list(range(self.n - 1, -1, -1))
+        self.grads = [device_grads(harness, torch, self.numel, self.dtype, self.R, self.sigma, 1000 * self.config_id + k)
+                      for k in range(sets)]
+        self.sessions = []
+        streams = None
+        for g in self.grads:
+            s = harness.Session(g, self.cap, pipeline, same_stream=same_stream, streams=streams)
+            streams = (s.reduce_stream, s.backward_stream)
+            for opt, val in options:
+                lib.ddp_set_option(s.ctx, opt, val)
+            self.sessions.append(s)
+        self.backward_stream = self.sessions[0].backward_stream
+        self.n_buckets = self.sessions[0].n_buckets
+        self.bucket_elems = [lib.ddp_get_bucket_info(self.sessions[0].ctx, b)[0] for b in range(self.n_buckets)]
+        self.flag_order = bool(lib.ddp_get_option(self.sessions[0].ctx, lib.DDP_OPT_FLAG_ORDER))
 
-        # timed region: `steps` steps.  "launch" / "iteration": the library's HIP events, one pair
-        # per launch / per iteration, on the stream the kernels run on.  "region": one pair of HIP
-        # events around all the steps on the backward stream -- every launch either runs on that
-        # stream or is waited for by it in ddp_finalize_backward -- and no events in between.
-        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, {"launch": 1, "iteration": 2, "region": 0}[timing_mode])
-        torch.cuda.synchronize()
+    def close(self):
+        for s in self.sessions:
+            s.close()
+        self.sessions, self.grads = [], []
+
+    def step(self, k, per_call):
+        ctx = self.sessions[k % len(self.sessions)].ctx
+        lib = self.lib
+        if per_call:
+            mark = lib.ddp_mark_ready
+            for p in self.order:
+                mark(ctx, p)
+        else:
+            lib.ddp_mark_ready_many(ctx, self.order)
+        lib.ddp_finalize_backward(ctx)
+
+    def sync(self):
+        for s in self.sessions:
+            self.lib.ddp_synchronize(s.ctx)
+        self.torch.cuda.synchronize()
+
+    def measure(self, steps, warmup, per_call, spread_iters=20):
+        """warmup + `steps` timed steps; then a pass with one HIP event pair per
+        iteration for the spread.  Returns a dict."""
+        lib, torch = self.lib, self.torch
+        S = len(self.sessions)
+        for k in range(max(warmup, S)):
+            self.step(k, per_call)
+        self.sync()
+        # launches per step, counted by the library's per-iteration events on one untimed step
+        ctx0 = self.sessions[0].ctx
+        lib.ddp_set_option(ctx0, lib.DDP_OPT_TIMING, 2)
+        self.step(0, per_call)
+        self.sync()
+        launches_per_step = int(lib.ddp_get_kernel_times(ctx0, lib.DDP_K_ITERATION)[1].sum())
+        lib.ddp_set_option(ctx0, lib.DDP_OPT_TIMING, 0)
+        # the timed region: no event between the steps
         ev_a = torch.cuda.Event(enable_timing=True)
         ev_b = torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        ev_a.record(s.backward_stream)
-        for _ in range(steps):
-            step()
-        ev_b.record(s.backward_stream)
-        t_enq = time.perf_counter()
-        lib.ddp_synchronize(ctx)
         torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev_a.record(self.backward_stream)
+        for k in range(steps):
+            self.step(k, per_call)
+        ev_b.record(self.backward_stream)
+        t_enq = time.perf_counter()
+        self.sync()
         t1 = time.perf_counter()
-        res = {"ms_per_step": (t1 - t0) * 1e3 / steps,
-               "host_enqueue_ms_per_step": (t_enq - t0) * 1e3 / steps,
-               "region_ms": ev_a.elapsed_time(ev_b), "launches_per_step": launches_per_step}
-        res["reduce"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_REDUCE)
-        res["pack"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_PACK)
-        res["unpack"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_UNPACK)
-        res["iteration"] = lib.ddp_get_kernel_times(ctx, lib.DDP_K_ITERATION)
-        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 0)
-        res["bucket_elems"] = [lib.ddp_get_bucket_info(ctx, b)[0] for b in range(s.n_buckets)]
-        res["n_buckets"] = s.n_buckets
+        region_ms = ev_a.elapsed_time(ev_b)
+        # spread: one event pair per iteration (each pair costs a few microseconds)
+        for s in self.sessions:
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 2)
+        for k in range(spread_iters):
+            self.step(k, per_call)
+        self.sync()
+        it_ms = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_ITERATION)[0] for s in self.sessions])
+        for s in self.sessions:
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 0)
+        R, B = self.R, self.B
+        ms_per_step = (t1 - t0) * 1e3 / steps
+        launches = launches_per_step * steps
+        achieved = (R + 1) * B * steps / region_ms / 1e6
+        return {
+            "ms_per_step": round(ms_per_step, 4),
+            "value_gbps": round((R + 1) * B / ms_per_step / 1e6, 1),
+            "pct_hbm_peak_end_to_end": round(100.0 * (R + 1) * B / ms_per_step / 1e6 / HBM_PEAK_GBPS, 2),
+            "host_enqueue_ms_per_step": round((t_enq - t0) * 1e3 / steps, 4),
+            "launches_per_step": launches_per_step,
+            "roofline": {
+                "kernel": "fused_reduce_kernel",
+                "bound": "hbm",
+                "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "avg_launch_ms": round(region_ms / max(launches, 1), 5),
+                "launches": launches,
+                "algorithmic_bytes_per_launch": round((R + 1) * B / max(launches_per_step, 1)),
+                "timing": "one HIP event pair around the timed region on the backward stream; "
+                          "launches on the two reduction streams may overlap, the average is region / launches",
+                "iteration_ms": spread(it_ms),
+                "iteration_what": "first bucket launch to the end of the iteration, one HIP event pair per "
+                                  "iteration (second pass; the pairs cost a few us each)",
+            },
+        }
+
+    def per_bucket(self, steps):
+        """One reduction stream, one HIP event pair per launch: the rate of every bucket."""
+        lib = self.lib
+        for s in self.sessions:
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_REDUCE_STREAMS, 1)
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 1)
+        for k in range(steps):
+            self.step(k, True)
+        self.sync()
+        ms = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_REDUCE)[0] for s in self.sessions])
+        ids = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_REDUCE)[1] for s in self.sessions])
+        for s in self.sessions:
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 0)
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_REDUCE_STREAMS, -1)
+        out = {}
+        for b in range(self.n_buckets):
+            sel = ms[ids == b]
+            if len(sel):
+                out[str(b)] = round((self.R + 1) * self.bucket_elems[b] * self.es / float(np.median(sel)) / 1e6, 1)
+        total = (self.R + 1) * self.B * steps / float(ms.sum()) / 1e6
+        return {"reduce_gbps_per_bucket": out, "reduce_gbps": round(total, 1),
+                "frac_of_hbm_peak": round(total / HBM_PEAK_GBPS, 4),
+                "bucket_mib": [round(e * self.es / MIB, 2) for e in self.bucket_elems],
+                "note": "one reduction stream, median over steps of one HIP event pair per launch "
+                        "(the pair adds about 3 us to each launch)"}
+
+
+def shape_leg(lib, harness, torch, workload, sets, steps, warmup, legs, traffic_mode):
+    """The per-call measurement of one workload plus its optional sub-legs."""
+    rig = Rig(lib, harness, torch, workload, sets, lib.DDP_PIPELINE_FUSED)
+    try:
+        res = rig.measure(steps, warmup, per_call=True)
+        res["roofline"]["traffic"] = read_traffic(workload, traffic_mode)
+        res["config"] = {"workload": f"{workload}: {rig.n} tensors, {sum(rig.numel)} elements, R={rig.R}, "
+                                     f"cap={rig.cap} B, {rig.n_buckets} buckets, ready order = reverse registration, "
+                                     f"one ddp_mark_ready call per parameter",
+                         "pipeline": "fused", "R": rig.R, "W": 1, "bucket_cap_bytes": rig.cap,
+                         "replica_sets_rotated": sets,
+                         "working_set_gb": round(sets * rig.R * rig.B / 1e9, 2),
+                         "launch_ordering": "device flags" if rig.flag_order else "events"}
+        if "one_call" in legs:
+            one = rig.measure(steps, warmup, per_call=False)
+            one["what"] = "all marks of a step in one ddp_mark_ready_many call: consecutive buckets share launches"
+            res["marks_in_one_call"] = one
+        if "per_bucket" in legs and rig.n_buckets <= 64:
+            res["one_launch_per_bucket"] = rig.per_bucket(max(5, steps // 2))
+    finally:
+        rig.close()
+    if "single_set" in legs:
+        rig = Rig(lib, harness, torch, workload, 1, lib.DDP_PIPELINE_FUSED)
+        try:
+            one = rig.measure(steps, warmup, per_call=True)
+            res["single_replica_set"] = {k: one[k] for k in ("ms_per_step", "value_gbps")}
+            res["single_replica_set"]["reduce_frac"] = one["roofline"]["frac"]
+            res["single_replica_set"]["what"] = ("every step works on the same addresses: part of a step is served "
+                                                 "from the Infinity Cache")
+        finally:
+            rig.close()
     return res
+
+
+def overlap_leg(lib, harness, torch, reps=10, delay_us=10):
+    """Configuration 4 in short (Section 5.1 / 5.2 in one-GPU form): exposed time of the synchronization
+    under a synthetic backward pass of one `delay_us` kernel per parameter."""
+    import workloads
+    shape_name, config_id, R, sigma, dtype, _ = WORKLOADS["resnet50_fp16_r16"]
+    numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[shape_name]())
+    n = len(numel)
+    B = sum(numel) * harness.ESIZE[dtype]
+    grads = device_grads(harness, torch, numel, dtype, R, sigma, 4000)
+    order = list(range(n - 1, -1, -1))
+    delays = [delay_us * 1000] * n
+    rows = []
+    for cap_mib in (1, 5, 10, 25, -1):
+        cap = lib.DDP_CAP_WHOLE_MODEL if cap_mib < 0 else cap_mib * MIB
+        with harness.Session(grads, cap, lib.DDP_PIPELINE_FUSED) as s:
+            ctx, stream = s.ctx, s.backward_stream
+            lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE, 0)          # one launch per bucket
+
+            def timed(fn):
+                out = []
+                for _ in range(reps):
+                    lib.ddp_synchronize(ctx)
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(stream)
+                    fn()
+                    b.record(stream)
+                    lib.ddp_synchronize(ctx)
+                    b.synchronize()
+                    out.append(a.elapsed_time(b))
+                return statistics.median(out)
+
+            def sync_alone():
+                lib.ddp_synth_backward(ctx, order, None, None, True)
+                lib.ddp_finalize_backward(ctx)
+
+            def backward_alone():
+                lib.ddp_synth_backward(ctx, order, delays, None, False)
+
+            def backward_and_sync():
+                lib.ddp_synth_backward(ctx, order, delays, None, True)
+                lib.ddp_finalize_backward(ctx)
+
+            for _ in range(3):
+                sync_alone()
+            t_sync, t_bwd, t_tot = timed(sync_alone), timed(backward_alone), timed(backward_and_sync)
+            rows.append({"cap_mib": cap_mib, "buckets": s.n_buckets, "sync_alone_ms": round(t_sync, 4),
+                         "backward_alone_ms": round(t_bwd, 4), "exposed_ms": round(t_tot - t_bwd, 4),
+                         "overlap": round(1.0 - (t_tot - t_bwd) / t_sync, 3),
+                         "ordered_by": "flags" if lib.ddp_get_option(ctx, lib.DDP_OPT_FLAG_ORDER) else "events"})
+    return {"workload": f"resnet50 shape, fp16, R={R}, {n} parameters, {delay_us} us of synthetic backward per parameter",
+            "algorithmic_bytes": (R + 1) * B, "reps": reps,
+            "what": "GPU time between two events on the backward stream, median; exposed = t(backward + sync) - "
+                    "t(backward alone); overlap = 1 - exposed / sync_alone; one launch per bucket",
+            "per_cap": rows}
+
+
+def r32_leg(lib, harness, torch, steps=8):
+    """Configuration 5's two kernels at full size: the R = 32 reduction and one no_sync micro-step."""
+    rig = Rig(lib, harness, torch, "bert_large_r32", 1, lib.DDP_PIPELINE_FUSED)
+    try:
+        res = rig.measure(steps, 2, per_call=True, spread_iters=20)
+        out = {"reduce": {"ms_per_sync": res["ms_per_step"], "gbps": res["roofline"]["achieved"],
+                          "frac_of_hbm_peak": res["roofline"]["frac"], "bytes_per_sync": (rig.R + 1) * rig.B,
+                          "launches_per_step": res["launches_per_step"], "iteration_ms": res["roofline"]["iteration_ms"]}}
+        micro = device_grads(harness, torch, rig.numel, rig.dtype, rig.R, rig.sigma, 5001)
+        ptrs = micro.ptrs()
+        ctx = rig.sessions[0].ctx
+        for _ in range(2):
+            lib.ddp_no_sync_accumulate(ctx, ptrs)
+        lib.ddp_synchronize(ctx)
+        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 1)
+        for _ in range(max(steps, 20)):
+            lib.ddp_no_sync_accumulate(ctx, ptrs)
+        lib.ddp_synchronize(ctx)
+        acc_ms, _ = lib.ddp_get_kernel_times(ctx, lib.DDP_K_ACCUMULATE)
+        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 0)
+        out["no_sync_accumulate"] = {"ms_per_micro_step": spread(acc_ms),
+                                     "gbps": round(3.0 * rig.R * rig.B / float(np.median(acc_ms)) / 1e6, 1),
+                                     "frac_of_hbm_peak": round(3.0 * rig.R * rig.B / float(np.median(acc_ms)) / 1e6 / HBM_PEAK_GBPS, 4),
+                                     "bytes_per_micro_step": 3 * rig.R * rig.B}
+        out["workload"] = (f"bert_large shape, fp32, R={rig.R}: {rig.R * rig.B / 1e9:.1f} GB of replica gradients "
+                           f"and as much of micro-step gradients resident")
+        del micro
+    finally:
+        rig.close()
+    return out
+
+
+def staged_leg(lib, harness, torch, steps):
+    """The literal three-kernel pipeline (pack, reduce, unpack) on the headline workload."""
+    rig = Rig(lib, harness, torch, "resnet50", 1, lib.DDP_PIPELINE_STAGED)
+    try:
+        ctx = rig.sessions[0].ctx
+        for k in range(2):
+            rig.step(k, False)
+        rig.sync()
+        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 1)
+        t0 = time.perf_counter()
+        for k in range(steps):
+            rig.step(k, False)
+        rig.sync()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+        R, B = rig.R, rig.B
+        pack, red, unpack = (lib.ddp_get_kernel_times(ctx, k)[0] for k in (lib.DDP_K_PACK, lib.DDP_K_REDUCE, lib.DDP_K_UNPACK))
+        return {"ms_per_step": round(ms_per_step, 4),
+                "value_gbps": round((R + 1) * B / ms_per_step / 1e6, 1),
+                "pack_gbps": round(2.0 * R * B * steps / float(pack.sum()) / 1e6, 1),
+                "reduce_gbps": round((R + 1) * B * steps / float(red.sum()) / 1e6, 1),
+                "unpack_gbps": round(2.0 * B * steps / float(unpack.sum()) / 1e6, 1),
+                "bytes": "pack 2RB, reduce (R+1)B, unpack (1+W)B per step", "steps": steps}
+    finally:
+        rig.close()
+
+
+def accumulate_leg(lib, harness, torch, iters=20):
+    rig = Rig(lib, harness, torch, "resnet50", 1, lib.DDP_PIPELINE_FUSED)
+    try:
+        micro = device_grads(harness, torch, rig.numel, rig.dtype, rig.R, rig.sigma, 2001)
+        ptrs, ctx = micro.ptrs(), rig.sessions[0].ctx
+        for _ in range(2):
+            lib.ddp_no_sync_accumulate(ctx, ptrs)
+        lib.ddp_synchronize(ctx)
+        lib.ddp_set_option(ctx, lib.DDP_OPT_TIMING, 1)
+        for _ in range(iters):
+            lib.ddp_no_sync_accumulate(ctx, ptrs)
+        lib.ddp_synchronize(ctx)
+        acc_ms, _ = lib.ddp_get_kernel_times(ctx, lib.DDP_K_ACCUMULATE)
+        return {"ms_per_micro_step": spread(acc_ms),
+                "gbps": round(3.0 * rig.R * rig.B / float(np.median(acc_ms)) / 1e6, 1),
+                "bytes": "3*R*B per micro-step (read gradient and micro-gradient, write gradient)"}
+    finally:
+        rig.close()
+
+
+def cpu_baseline_leg(workload="resnet50", budget_s=12.0):
+    """The CPU oracle as it stands, on the headline workload: whole synchronizations on one thread,
+    then with every bucket's element range split over all host cores (the same oracle functions
+    on slices: identical bits)."""
+    import oracle
+    import workloads
+    shape_name, config_id, R, sigma, dtype, cap = WORKLOADS[workload]
+    numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[shape_name]())
+    n = len(numel)
+    B = sum(numel) * workloads.ESIZE[dtype]
+    cores = os.cpu_count() or 1
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        flat = list(pool.map(lambda rp: workloads.gaussian_grad(config_id, rp[0], 0, rp[1], numel[rp[1]], sigma, dtype),
+                             [(r, p) for r in range(R) for p in range(n)]))
+    reps = [flat[r * n:(r + 1) * n] for r in range(R)]
+    dtypes = [dtype] * n
+
+    t0 = time.perf_counter()
+    done = 0
+    while True:
+        ref, asg, _ = oracle.synchronize(numel, dtypes, cap, reps)
+        done += 1
+        if time.perf_counter() - t0 > budget_s or done >= 40:
+            break
+    single_ms = (time.perf_counter() - t0) * 1e3 / done
+
+    def one_sync_all_cores(pool):
+        outs = [None] * n
+        for b in range(len(asg.buckets)):
+            flats = [oracle.pack_bucket(asg, b, reps[r]) for r in range(R)]
+            elems = len(flats[0])
+            cuts = [elems * k // cores for k in range(cores + 1)]
+            parts = list(pool.map(lambda k: oracle.reduce_average([f[cuts[k]:cuts[k + 1]] for f in flats], asg.buckets[b].dtype),
+                                  range(cores)))
+            oracle.unpack_bucket(asg, b, np.concatenate(parts), outs)
+        return outs
+
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        outs = one_sync_all_cores(pool)
+        same = all(outs[i].tobytes() == ref[i].tobytes() for i in range(n))
+        t0 = time.perf_counter()
+        done_mt = 0
+        while True:
+            one_sync_all_cores(pool)
+            done_mt += 1
+            if time.perf_counter() - t0 > budget_s or done_mt >= 40:
+                break
+        multi_ms = (time.perf_counter() - t0) * 1e3 / done_mt
+    return {
+        "value": round((R + 1) * B / multi_ms / 1e6, 3),
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle",
+        "ms_per_step": round(multi_ms, 2),
+        "sample": f"{done_mt} whole synchronizations of the {workload} workload (all {len(asg.buckets)} buckets, R={R}, "
+                  f"host-generated gradients of the parity tests' recipe) by the numpy oracle, every bucket's "
+                  f"element range split over {cores} threads calling the unchanged oracle functions "
+                  f"(bit-identical to the single-thread result: {same})",
+        "single_thread": {"value": round((R + 1) * B / single_ms / 1e6, 3), "unit": "GB/s", "cores": 1,
+                          "ms_per_step": round(single_ms, 2), "sample": f"{done} whole synchronizations, one thread"},
+        "host_cores_visible": os.cpu_count(),
+        "numpy": np.__version__,
+    }
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet50", choices=sorted(WORKLOADS))
-    ap.add_argument("--pipeline", default="fused", choices=["staged", "fused"])
+    ap.add_argument("--legs", default=",".join(ALL_LEGS),
+                    help="comma list of " + ", ".join(ALL_LEGS) + " (headline is always run)")
+    ap.add_argument("--sets", type=int, default=4,
+                    help="independent sets of replica gradients taken in turn by consecutive steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-staged-leg", action="store_true",
-                    help="skip the extra measurement of the staged pipeline's kernels")
-    ap.add_argument("--no-coalesce-leg", action="store_true",
-                    help="skip the extra measurement with one launch per bucket")
-    ap.add_argument("--no-streams-leg", action="store_true",
-                    help="skip the extra measurement with two reduction streams")
-    ap.add_argument("--no-accumulate-leg", action="store_true",
-                    help="skip the extra measurement of the no_sync accumulation kernel")
-    ap.add_argument("--reduce-blocks", type=int, default=None)
-    ap.add_argument("--plain-loads", action="store_true")
-    ap.add_argument("--unroll", type=int, default=None, choices=[1, 2, 4])
-    ap.add_argument("--pair-min-mib", type=float, default=None,
-                    help="fused pipeline: bucket size from which blocks take two tiles")
-    ap.add_argument("--coalesce-mib", type=float, default=None,
-                    help="buckets completed by one call share a launch up to this many MiB "
-                         "(DDP_OPT_COALESCE; 0 = one launch per bucket, negative = no limit; "
-                         "default: the library's, 100 MiB)")
-    ap.add_argument("--streams", type=int, default=None,
-                    help="reduction streams taken in turn by the bucket launches (DDP_OPT_REDUCE_STREAMS)")
-    ap.add_argument("--tail-on-backward", type=int, default=None, choices=[0, 1],
-                    help="DDP_OPT_TAIL_ON_BACKWARD: 1 (library default) = the launches of the call that "
-                         "completes an iteration go to the backward stream; 0 = always a reduction stream")
-    ap.add_argument("--blocks-per-cu", type=int, default=None,
-                    help="reduce kernels: resident thread blocks per compute unit "
-                         "(DDP_OPT_REDUCE_BLOCKS_PER_CU; 0 = no cap)")
-    ap.add_argument("--copy-blocks-per-cu", type=int, default=None,
-                    help="pack / unpack / accumulate kernels: resident blocks per compute unit "
-                         "(DDP_OPT_COPY_BLOCKS_PER_CU; 0 = no cap)")
-    ap.add_argument("--acc-blocks-per-cu", type=int, default=None,
-                    help="accumulate kernel: resident blocks per compute unit "
-                         "(DDP_OPT_ACCUMULATE_BLOCKS_PER_CU; 0 = no cap)")
-    ap.add_argument("--cap-min-mib", type=float, default=None,
-                    help="launch size from which that cap applies (DDP_OPT_REDUCE_CAP_MIN_BYTES)")
-    ap.add_argument("--copy-nt-store", action="store_true",
-                    help="staged pipeline: pack/unpack store with the non-temporal hint")
-    ap.add_argument("--same-stream", action="store_true",
-                    help="use one stream for backward and reduction (no event plumbing)")
-    ap.add_argument("--timing", default=None, choices=["launch", "iteration", "region"],
-                    help="HIP-event granularity in the timed region: one pair per kernel launch "
-                         "(default for staged), one pair around each iteration's bucket launches, or "
-                         "one pair around all the steps (default for fused, where the reduce launches "
-                         "are the only kernels: no event between them)")
-    ap.add_argument("--cap-mib", type=float, default=None,
-                    help="override the bucket cap (MiB; negative = whole model)")
-    ap.add_argument("--replicas", type=int, default=None,
-                    help="diagnostic: override the workload's number of replicas R")
-    ap.add_argument("--uniform", default=None,
-                    help="diagnostic workload 'count,elems': that many equal tensors (with --workload uniform)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling profiler counters)")
     args = ap.parse_args()
@@ -213,36 +489,19 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU (the R replicas are R buffers in one GPU's "
               "HBM); --gpus above 1 is not supported and nothing was measured", file=sys.stderr)
         return 2
+    legs = set(x for x in args.legs.split(",") if x)
+    unknown = legs - set(ALL_LEGS)
+    if unknown:
+        print(f"bench.py: unknown legs {sorted(unknown)}", file=sys.stderr)
+        return 2
+    if args.no_cpu_baseline:
+        legs.discard("cpu")
 
     import torch
-    import workloads
     import __graft_entry__
     __graft_entry__.ensure_built()          # a fresh checkout has no library yet
     import paper_2006_15704_amd as lib
     from paper_2006_15704_amd import harness
-
-    shape_name, config_id, R, sigma, dtype, cap = WORKLOADS[args.workload]
-    if args.replicas is not None:
-        R = args.replicas
-    if args.cap_mib is not None:
-        cap = lib.DDP_CAP_WHOLE_MODEL if args.cap_mib < 0 else int(args.cap_mib * (1 << 20))
-    if args.workload == "uniform" and args.uniform:
-        count, elems = (int(x) for x in args.uniform.split(","))
-        numel = workloads.numel_of(workloads.uniform_shapes(count, elems))
-    else:
-        numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[shape_name]())
-    n = len(numel)
-    es = harness.ESIZE[dtype]
-    B = sum(numel) * es
-    W = 1
-    codes = {"staged": lib.DDP_PIPELINE_STAGED, "fused": lib.DDP_PIPELINE_FUSED}
-    timing = args.timing or ("region" if args.pipeline == "fused" else "launch")
-
-    reps = generate_replicas(config_id, numel, R, sigma, dtype)
-    grads = harness.DeviceGrads(numel, [dtype] * n, R)
-    for r in range(R):
-        grads.upload_replica(r, reps[r])
-    torch.cuda.synchronize()
 
     if args.calibration_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
@@ -252,209 +511,48 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    order = list(range(n - 1, -1, -1))
-    m = measure(lib, harness, torch, grads, cap, codes[args.pipeline], order, args.steps, args.warmup,
-                timing, args)
-    ms_per_step = m["ms_per_step"]
-    bucket_elems, n_buckets = m["bucket_elems"], m["n_buckets"]
-    red_ms, red_ids = m["reduce"]
-    iter_ms, iter_launches = m["iteration"]
-
-    def launch_elems(ident):
-        """elements covered by a launch id (first bucket + 65536 * further buckets)"""
-        first, extra = int(ident) % 65536, int(ident) // 65536
-        return sum(bucket_elems[first:first + extra + 1])
-
-    # reduce kernel: algorithmic bytes per launch = (R + 1) * bucket bytes
-    per_bucket = {}
-    if timing == "launch":
-        launches = len(red_ms)
-        total_alg = float(sum((R + 1) * launch_elems(b) * es for b in red_ids))
-        total_ms = float(red_ms.sum())
-        for b in range(n_buckets):
-            sel = red_ms[red_ids == b]
-            if len(sel):
-                per_bucket[str(b)] = round((R + 1) * bucket_elems[b] * es / float(np.median(sel)) / 1e6, 1)
-    elif timing == "iteration":
-        # one interval per iteration holding all its bucket launches; in the
-        # fused pipeline they are the only kernels inside it
-        launches = int(iter_launches.sum())
-        total_alg = float((R + 1) * B * len(iter_ms))
-        total_ms = float(iter_ms.sum())
-    else:
-        # one interval around all the steps (fused pipeline: the reduce launches are its only
-        # kernels); the gaps between consecutive launches are part of it
-        launches = m["launches_per_step"] * args.steps
-        total_alg = float((R + 1) * B * args.steps)
-        total_ms = float(m["region_ms"])
-    avg_launch_ms = total_ms / max(launches, 1)
-    achieved = total_alg / max(total_ms, 1e-12) / 1e6          # bytes / ms -> GB/s
-
-    value = (R + W) * B / ms_per_step / 1e6
+    head = shape_leg(lib, harness, torch, "resnet50", args.sets, args.steps, args.warmup, legs, "per_bucket")
+    _, _, R, _, dtype, _ = WORKLOADS["resnet50"]
     out = {
         "metric": "bucketed grad-sync throughput ((R+W)*B per synchronization)",
-        "value": round(value, 2),
+        "value": head["value_gbps"],
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": {0: "f32", 1: "f16", 2: "bf16"}[dtype],
+        "dtype": DT_NAME[dtype],
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {n} tensors, {sum(numel)} elements, R={R}, "
-                               f"cap={cap} B, {n_buckets} buckets, ready order = reverse registration",
-                   "pipeline": args.pipeline, "R": R, "W": W, "bucket_cap_bytes": cap},
-        "pct_hbm_peak_end_to_end": round(100.0 * value / HBM_PEAK_GBPS, 2),
-        "host_enqueue_ms_per_step": round(m["host_enqueue_ms_per_step"], 4),
-        "kernel_ms_per_step": {
-            "pack": round(float(m["pack"][0].sum()) / args.steps, 4),
-            "reduce": round(total_ms / args.steps, 4),
-            "unpack": round(float(m["unpack"][0].sum()) / args.steps, 4),
-        },
-        "roofline": {
-            "kernel": "flat_reduce_kernel" if args.pipeline == "staged" else "fused_reduce_kernel",
-            "bound": "hbm",
-            "achieved": round(achieved, 1),
-            "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "avg_launch_ms": round(avg_launch_ms, 5),
-            "launches": launches,
-            "timing": ("one HIP event pair around the timed region" if timing == "region"
-                       else "HIP event pair per " + timing),
-            "interval_ms": ({"median": round(float(np.median(iter_ms)), 5), "min": round(float(iter_ms.min()), 5),
-                             "max": round(float(iter_ms.max()), 5), "what": "one iteration's launches"}
-                            if timing == "iteration" and len(iter_ms) else
-                            {"median": round(float(np.median(red_ms)), 5), "min": round(float(red_ms.min()), 5),
-                             "max": round(float(red_ms.max()), 5), "what": "one launch"}
-                            if timing == "launch" and len(red_ms) else None),
-            "algorithmic_bytes_per_launch": round(total_alg / max(launches, 1)),
-            "traffic": read_traffic(args.workload, args.pipeline),
-        },
+        "config": head.pop("config"),
+        "pct_hbm_peak_end_to_end": head["pct_hbm_peak_end_to_end"],
+        "host_enqueue_ms_per_step": head["host_enqueue_ms_per_step"],
+        "launches_per_step": head["launches_per_step"],
+        "roofline": head["roofline"],
     }
-    if per_bucket:
-        out["reduce_gbps_per_bucket"] = per_bucket
-    if timing == "region":
-        # a short second pass with one event pair per iteration, for the spread
-        it = measure(lib, harness, torch, grads, cap, codes[args.pipeline], order, max(10, args.steps // 5), 2,
-                     "iteration", args)
-        it_ms, it_launches = it["iteration"]
-        out["roofline"]["per_iteration_pass"] = {
-            "interval_ms": {"median": round(float(np.median(it_ms)), 5), "min": round(float(it_ms.min()), 5),
-                            "max": round(float(it_ms.max()), 5)},
-            "reduce_gbps": round((R + 1) * B * len(it_ms) / float(it_ms.sum()) / 1e6, 1),
-            "what": "one HIP event pair per iteration around its launches (the pairs cost a few us each)",
-        }
-
-    if args.pipeline == "fused" and not args.no_staged_leg:
-        # the literal three-kernel pipeline on the same data, one event pair per launch
-        steps2 = max(5, args.steps // 2)
-        st = measure(lib, harness, torch, grads, cap, codes["staged"], order, steps2, 2, "launch", args)
-        s_red_ms, s_red_ids = st["reduce"]
-        red_alg = float(sum((R + 1) * launch_elems(b) * es for b in s_red_ids))
-        out["staged"] = {
-            "ms_per_step": round(st["ms_per_step"], 4),
-            "value_gbps": round((R + W) * B / st["ms_per_step"] / 1e6, 1),
-            "pack_gbps": round(2.0 * R * B * steps2 / float(st["pack"][0].sum()) / 1e6, 1),
-            "reduce_gbps": round(red_alg / float(s_red_ms.sum()) / 1e6, 1),
-            "unpack_gbps": round((1.0 + W) * B * steps2 / float(st["unpack"][0].sum()) / 1e6, 1),
-            "bytes": "pack 2RB, reduce (R+1)B, unpack (1+W)B per step",
-            "steps": steps2,
-        }
-
-    if args.pipeline == "fused" and args.coalesce_mib is None and not args.no_coalesce_leg:
-        # the same steps with one launch per bucket on the reduction stream (DDP_OPT_COALESCE = 0,
-        # DDP_OPT_TAIL_ON_BACKWARD = 0), as when the ready marks arrive in separate calls during a
-        # real backward pass
-        args.coalesce_mib = 0.0
-        keep_tail, args.tail_on_backward = args.tail_on_backward, 0
-        pb = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
-        args.coalesce_mib, args.tail_on_backward = None, keep_tail
-        pb_ms, pb_launches = pb["iteration"]
-        per_bucket_gbps = None
-        if n_buckets <= 64:
-            # a few more steps with one event pair per launch: the rate of every bucket
-            args.coalesce_mib, args.tail_on_backward = 0.0, 0
-            pl = measure(lib, harness, torch, grads, cap, codes["fused"], order, max(5, args.steps // 5), 2, "launch", args)
-            args.coalesce_mib, args.tail_on_backward = None, keep_tail
-            l_ms, l_ids = pl["reduce"]
-            per_bucket_gbps = {str(b): round((R + 1) * bucket_elems[b] * es / float(np.median(l_ms[l_ids == b])) / 1e6, 1)
-                               for b in range(n_buckets) if (l_ids == b).any()}
-        out["one_launch_per_bucket"] = {
-            "reduce_gbps_per_bucket": per_bucket_gbps,
-            "per_bucket_note": "median over steps, one HIP event pair per launch (the pair adds about 3 us to each)",
-            "ms_per_step": round(pb["ms_per_step"], 4),
-            "value_gbps": round((R + W) * B / pb["ms_per_step"] / 1e6, 1),
-            "launches_per_step": int(pb_launches.sum()) // args.steps,
-            "reduce_gbps": round((R + 1) * B * len(pb_ms) / float(pb_ms.sum()) / 1e6, 1),
-            "frac_of_hbm_peak": round((R + 1) * B * len(pb_ms) / float(pb_ms.sum()) / 1e6 / HBM_PEAK_GBPS, 4),
-        }
-
-    if args.pipeline == "fused" and args.streams is None and not args.no_streams_leg:
-        # one launch per bucket, the launches alternating between two reduction streams
-        # (DDP_OPT_REDUCE_STREAMS): neighbouring buckets overlap, so only the iteration as a
-        # whole has a duration
-        args.streams = 2
-        keep_coalesce, args.coalesce_mib = args.coalesce_mib, 0.0
-        keep_tail, args.tail_on_backward = args.tail_on_backward, 0
-        rr = measure(lib, harness, torch, grads, cap, codes["fused"], order, args.steps, 2, "iteration", args)
-        args.streams, args.coalesce_mib, args.tail_on_backward = None, keep_coalesce, keep_tail
-        rr_ms, _ = rr["iteration"]
-        out["two_streams"] = {
-            "ms_per_step": round(rr["ms_per_step"], 4),
-            "value_gbps": round((R + W) * B / rr["ms_per_step"] / 1e6, 1),
-            "reduce_gbps": round((R + 1) * B * len(rr_ms) / float(rr_ms.sum()) / 1e6, 1),
-            "frac_of_hbm_peak": round((R + 1) * B * len(rr_ms) / float(rr_ms.sum()) / 1e6 / HBM_PEAK_GBPS, 4),
-            "note": "one launch per bucket; (R+1)*B per iteration / time from the first launch to the join of both streams",
-        }
-
-    if not args.no_accumulate_leg:
-        # no_sync micro-step: grad[r][i] += micro[r][i] for all replicas, 3*R*B bytes
-        micro = harness.DeviceGrads(numel, [dtype] * n, R, fill=0)
-        ptrs = micro.ptrs()
-        with harness.Session(grads, cap, codes[args.pipeline]) as s:
-            if args.acc_blocks_per_cu is not None:
-                lib.ddp_set_option(s.ctx, lib.DDP_OPT_ACCUMULATE_BLOCKS_PER_CU, args.acc_blocks_per_cu)
-            for _ in range(2):
-                lib.ddp_no_sync_accumulate(s.ctx, ptrs)
-            lib.ddp_synchronize(s.ctx)
-            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 1)
-            reps_acc = 10
-            for _ in range(reps_acc):
-                lib.ddp_no_sync_accumulate(s.ctx, ptrs)
-            lib.ddp_synchronize(s.ctx)
-            acc_ms, _ = lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_ACCUMULATE)
-        out["no_sync_accumulate"] = {
-            "ms_per_micro_step": round(float(acc_ms.mean()), 4),
-            "gbps": round(3.0 * R * B / float(acc_ms.mean()) / 1e6, 1),
-            "bytes": "3*R*B per micro-step (read gradient and micro-gradient, write gradient)",
-        }
-        del micro
-
-    if not args.no_cpu_baseline:
-        import oracle
-        t0 = time.perf_counter()
-        done = 0
-        while True:
-            oracle.synchronize(numel, [dtype] * n, cap, reps)
-            done += 1
-            if time.perf_counter() - t0 > 10.0 or done >= 20:
-                break
-        cpu_ms = (time.perf_counter() - t0) * 1e3 / done
-        out["cpu_baseline"] = {
-            "value": round((R + W) * B / cpu_ms / 1e6, 3),
-            "unit": "GB/s",
-            "cores": 1,
-            "kind": "oracle",
-            "ms_per_step": round(cpu_ms, 2),
-            "sample": f"{done} full synchronizations of the same {args.workload} workload "
-                      f"(all {n_buckets} buckets, R={R}) by the numpy oracle, single thread",
-            "host_cores_visible": os.cpu_count(),
-            "numpy": np.__version__,
-        }
+    for key in ("marks_in_one_call", "one_launch_per_bucket", "single_replica_set"):
+        if key in head:
+            out[key] = head[key]
+    if "bert_large" in legs:
+        # 12 GB per step already: two sets are far beyond any cache
+        bert = shape_leg(lib, harness, torch, "bert_large", 2, max(10, args.steps // 2), 2,
+                         legs - {"single_set"}, "per_bucket")
+        bert["value"] = bert.pop("value_gbps")
+        bert["unit"] = "GB/s"
+        out["bert_large"] = bert
+    if "overlap" in legs:
+        out["overlap"] = overlap_leg(lib, harness, torch)
+    if "r32" in legs:
+        out["bert_large_r32"] = r32_leg(lib, harness, torch)
+    if "staged" in legs:
+        out["staged"] = staged_leg(lib, harness, torch, max(5, args.steps // 4))
+    if "accumulate" in legs:
+        out["no_sync_accumulate"] = accumulate_leg(lib, harness, torch)
+    torch.cuda.synchronize()
+    if "cpu" in legs:
+        out["cpu_baseline"] = cpu_baseline_leg()
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

@@ -113,7 +113,12 @@ typedef struct ddp_ctx ddp_ctx;
                                      then not launched at all in the fused pipeline: Section 6.2.2's
                                      skipping at the bucket level); 0 (default) = they are written as
                                      zeros */
-#define DDP_OPT_REDUCE_STREAMS 12  /* between iterations: number of reduction streams, 1 (default) to 8.
+#define DDP_OPT_REDUCE_STREAMS 12  /* between iterations: number of reduction streams, 1 to 8, or -1
+                                     (default): two for launches of less than DDP_OPT_REDUCE_CAP_MIN_BYTES
+                                     (start-up and drain of a short launch then overlap with its
+                                     neighbour: +2 to 3 points of HBM peak with one launch per 25 MiB
+                                     bucket), one for larger launches (two long launches at a time share
+                                     the memory system and lose).
                                      The launches of an iteration take the streams in turn: the
                                      caller's reduce_stream first, then streams the library creates
                                      (default priority).  This is the one-GPU form of Section 3.3's

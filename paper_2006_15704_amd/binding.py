@@ -215,8 +215,25 @@ def ddp_get_bucket_ptr(ctx, b: int, r: int) -> int:
     return p.value or 0
 
 
+# The calls made once per parameter go through a small CPython module (plain
+# argument passing, a tenth of the interpreter time of a ctypes call); it is
+# built together with the library.
+import importlib.util as _ilu
+
+_fast_path = os.path.join(_HERE, "_ddp_fastcall.so")
+if not os.path.exists(_fast_path):
+    raise ImportError(f"{_fast_path} is missing: build it with `python paper_2006_15704_amd/build.py`")
+_spec = _ilu.spec_from_file_location("_ddp_fastcall", _fast_path)
+_fast = _ilu.module_from_spec(_spec)
+_spec.loader.exec_module(_fast)
+_fast.bind(C.cast(_lib.ddp_mark_ready, _vp).value, C.cast(_lib.ddp_finalize_backward, _vp).value)
+_fast_mark, _fast_finalize = _fast.mark_ready, _fast.finalize_backward
+
+
 def ddp_mark_ready(ctx, param_id: int) -> None:
-    _check(ctx, _lib.ddp_mark_ready(ctx, param_id))
+    status = _fast_mark(ctx.value, param_id)
+    if status < 0:
+        _check(ctx, status)
 
 
 def ddp_mark_ready_local(ctx, param_id: int, used) -> None:
@@ -239,7 +256,9 @@ def ddp_mark_ready_many(ctx, ids) -> None:
 
 
 def ddp_finalize_backward(ctx) -> None:
-    _check(ctx, _lib.ddp_finalize_backward(ctx))
+    status = _fast_finalize(ctx.value)
+    if status < 0:
+        _check(ctx, status)
 
 
 def ddp_synchronize(ctx) -> None:

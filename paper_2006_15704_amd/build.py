@@ -26,7 +26,7 @@ def source_hash() -> str:
     import hashlib
     h = hashlib.sha256()
     files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC))
-             if f.endswith((".hip", ".cpp", ".h"))]
+             if f.endswith((".hip", ".cpp", ".h", ".c"))]
     files.append(os.path.join(os.path.dirname(HERE), "include", "ddp_gfx950.h"))
     for path in files:
         h.update(os.path.basename(path).encode() + b"\0")
@@ -45,6 +45,25 @@ def built_hash() -> str:
         return m.group(1).decode() if m else ""
     except OSError:
         return ""
+
+
+FAST = os.path.join(HERE, "_ddp_fastcall.so")
+
+
+def build_fastcall(verbose: bool = False) -> str:
+    """The CPython marshalling module for the per-parameter calls (plain C, host only)."""
+    import sysconfig
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        raise RuntimeError("no C compiler found for the marshalling module")
+    cmd = [cc, "-O2", "-shared", "-fPIC", "-Wall", "-I" + sysconfig.get_paths()["include"],
+           "-o", FAST, os.path.join(CSRC, "fastcall.c")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("building the marshalling module failed:\n" + res.stdout)
+    return FAST
 
 
 def hipcc() -> str:
@@ -66,6 +85,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stdout)
     if verbose and out.strip():
         print(out)
+    build_fastcall(verbose)
     return LIB
 
 

@@ -56,7 +56,8 @@ struct ddp_ctx {
     int64_t pair_min_bytes = int64_t(48) << 20;   // launches at least this large use paired tiles ...
     static constexpr int64_t kPairMinTilesPerSegment = 256;   // ... if their tensors are large on average
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
-    int32_t n_streams = 1;                        // reduction streams taken in turn by the launches
+    int32_t n_streams = -1;                       // reduction streams taken in turn by the launches; -1 = two
+                                                  // for launches below cap_min_bytes, one for larger ones
     int32_t tail_on_backward = 1;                 // the call that completes an iteration launches on the backward stream
     int32_t blocks_per_cu = -1;                   // reduce kernels: resident blocks per compute unit (0 = no cap,
                                                   // -1 = chosen from R, see auto_blocks_per_cu)
@@ -259,11 +260,33 @@ int32_t probe_lane(ddp_ctx* c, int l) {
     return DDP_OK;
 }
 
+// Creates reduction stream l (default priority, no implicit ordering with the legacy
+// default stream).  A new stream may land on the hardware queue of the backward stream; a
+// few more are tried then (the misfits are destroyed once one fits, so that the next try
+// does not get the same queue again).
+int32_t create_lane(ddp_ctx* c, int l) {
+    if (c->lane[l]) return DDP_OK;
+    hipStream_t misfit[6];
+    int misfits = 0;
+    for (;;) {
+        HIPCHK(c, hipStreamCreateWithFlags(&c->lane[l], hipStreamNonBlocking));
+        const int32_t rc = probe_lane(c, l);
+        if (rc != DDP_OK) return rc;
+        if (c->lane_concurrent[l] || misfits == 6) break;
+        misfit[misfits++] = c->lane[l];
+    }
+    for (int k = 0; k < misfits; ++k) (void)hipStreamDestroy(misfit[k]);
+    HIPCHK(c, hipEventCreateWithFlags(&c->ev_join[l], kOrderEvent));
+    return DDP_OK;
+}
+
 // Flags order the launches of the running API call if every reduction stream in use passed
 // the probe (fused pipeline only: its kernels carry the gate check).
 bool flags_usable(const ddp_ctx* c) {
     if (c->flag_order == 0 || c->pipeline != DDP_PIPELINE_FUSED || c->d_gate == nullptr) return false;
-    for (int l = 0; l < c->n_streams; ++l)
+    // (by default the second stream is only used if it passed the probe, see launch_range)
+    const int lanes = c->n_streams < 0 ? 1 : c->n_streams;
+    for (int l = 0; l < lanes; ++l)
         if (!c->lane_concurrent[l]) return false;
     return true;
 }
@@ -287,7 +310,11 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
     int lane = -1;
     hipStream_t st = c->backward;
     if (!on_backward) {
-        lane = static_cast<int>(c->launches_in_iter++ % c->n_streams);
+        // Short launches gain from a neighbour on a second stream (start-up and drain of one
+        // overlap with the other); launches long enough for the cap on resident blocks lose
+        // when two of them share the memory system, so by default those stay on one stream.
+        const int lanes = c->n_streams < 0 ? (bytes < c->cap_min_bytes && c->lane[1] && c->lane_concurrent[1] ? 2 : 1) : c->n_streams;
+        lane = static_cast<int>(c->launches_in_iter++ % lanes);
         st = c->lane[lane];
         c->lane_used[lane] = true;
     } else {
@@ -596,7 +623,9 @@ int32_t ddp_create(ddp_ctx** out, int32_t R, int32_t device, void* reduce_stream
         }
         c->d_order = reinterpret_cast<ddp::OrderState*>(c->d_order_mem);
         c->d_probe = reinterpret_cast<unsigned long long*>(c->d_order_mem + sizeof(ddp::OrderState));
-        if (probe_lane(c, 0) != DDP_OK) {
+        // the second reduction stream of the default configuration (not when both roles share
+        // one stream: then nothing can overlap anyway)
+        if (probe_lane(c, 0) != DDP_OK || (c->reduce != c->backward && create_lane(c, 1) != DDP_OK)) {
             std::string msg = "ddp_create: stream probe: " + c->err;
             release_device(c);
             delete c;
@@ -662,29 +691,15 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             c->tail_on_backward = value != 0;
             return DDP_OK;
         case DDP_OPT_REDUCE_STREAMS:
-            if (value < 1 || value > ddp_ctx::kMaxLanes)
-                return fail(c, DDP_ERR_ARG, "number of reduction streams outside [1, 8]");
+            if (value != -1 && (value < 1 || value > ddp_ctx::kMaxLanes))
+                return fail(c, DDP_ERR_ARG, "number of reduction streams outside [1, 8] and not -1");
             if (c->tracker.marks() != 0 || !c->log_running.empty())
                 return fail(c, DDP_ERR_STATE, "reduction streams can only change between iterations");
             if (!c->plan_only) {
                 HIPCHK(c, hipSetDevice(c->device));
                 for (int l = 1; l < value; ++l) {
-                    if (c->lane[l]) continue;
-                    // default priority, and no implicit ordering with the legacy default stream.
-                    // A new stream may land on the hardware queue of the backward stream; a few
-                    // more are tried then (the misfits are destroyed once one fits, so that the
-                    // next try does not get the same queue again).
-                    hipStream_t misfit[6];
-                    int misfits = 0;
-                    for (;;) {
-                        HIPCHK(c, hipStreamCreateWithFlags(&c->lane[l], hipStreamNonBlocking));
-                        const int32_t rc = probe_lane(c, l);
-                        if (rc != DDP_OK) return rc;
-                        if (c->lane_concurrent[l] || misfits == 6) break;
-                        misfit[misfits++] = c->lane[l];
-                    }
-                    for (int k = 0; k < misfits; ++k) (void)hipStreamDestroy(misfit[k]);
-                    HIPCHK(c, hipEventCreateWithFlags(&c->ev_join[l], kOrderEvent));
+                    const int32_t rc = create_lane(c, l);
+                    if (rc != DDP_OK) return rc;
                 }
             }
             c->n_streams = static_cast<int32_t>(value);

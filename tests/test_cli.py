@@ -28,9 +28,14 @@ def test_product_does_not_import_the_oracle():
             assert not re.search(r"^\s*(import|from)\s+oracle\b", text, re.M), name
             assert "ddp_oracle" not in text, name
     bench = open(os.path.join(ROOT, "bench.py")).read()
-    uses = [m.start() for m in re.finditer(r"\boracle\.", bench)]
-    guard = bench.index("if not args.no_cpu_baseline:")
-    assert uses and all(u > guard for u in uses)      # every call sits inside the cpu_baseline leg
+    # every use of the oracle sits inside the function of the cpu_baseline leg
+    begin = bench.index("def cpu_baseline_leg(")
+    end = bench.index("\ndef ", begin + 1)
+    uses = [m.start() for m in re.finditer(r"\boracle\.|import oracle", bench)]
+    assert uses and all(begin < u < end for u in uses)
+    calls = [m.start() for m in re.finditer(r"cpu_baseline_leg\(", bench)]
+    guard = bench.index('if "cpu" in legs:')
+    assert len(calls) == 2 and max(calls) > guard     # the definition and one guarded call
 
 
 def test_oracle_does_not_import_the_product():
