@@ -1,11 +1,12 @@
 """GPU parity at the full sizes of the model-shaped configurations, in the
-launch configuration the benchmark times (ready marks in reverse registration
-order through ddp_mark_ready_many, 25 MiB cap).  ResNet-50 and BERT-large with
-R = 8 are compared element by element over the whole model; the bucket-size
-sweep (fp16, R = 16) over every cap; the R = 32 no_sync configuration on
-sampled buckets that the oracle recomputes one by one, plus properties that
-hold everywhere (never-marked parameters receive exact zeros, inputs of the
-other replicas stay untouched)."""
+launch configurations the benchmark times (ready marks in reverse registration
+order, one ddp_mark_ready call per parameter or all in one ddp_mark_ready_many
+call, 25 MiB cap).  ResNet-50 and BERT-large with R = 8 are compared element by
+element over the whole model; the bucket-size sweep (fp16, R = 16) over every
+cap; the R = 32 no_sync configuration over all 50 buckets (fused pipeline; the
+oracle is streamed over the buckets) with the accumulators of every replica,
+plus properties that hold everywhere (never-marked parameters receive exact
+zeros, inputs of the other replicas stay untouched)."""
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -64,10 +65,12 @@ def test_model_shapes_r8_fp32(name, config_id, sigma, nb):
     # the library's defaults (what bench.py's headline line times), one launch per bucket, and the
     # benchmark's other legs: one launch per bucket on the reduction stream, and on two of them
     per_bucket = ((d.DDP_OPT_COALESCE, 0), (d.DDP_OPT_TAIL_ON_BACKWARD, 0))
-    configs = [(STAGED, ()), (FUSED, ()), (FUSED, ((d.DDP_OPT_COALESCE, 0),)), (FUSED, per_bucket),
-               (FUSED, per_bucket + ((d.DDP_OPT_REDUCE_STREAMS, 2),))]
-    for pipeline, options in configs:
-        progress(f"{name}: pipeline {pipeline} options {options}")
+    configs = [(STAGED, (), False), (FUSED, (), False), (FUSED, ((d.DDP_OPT_COALESCE, 0),), False),
+               (FUSED, per_bucket, False), (FUSED, per_bucket + ((d.DDP_OPT_REDUCE_STREAMS, 2),), False),
+               (FUSED, (), True),                                    # the benchmark's headline: marks one call at a time
+               (FUSED, ((d.DDP_OPT_FLAG_ORDER, 0),), True)]          # ... and with events instead of device flags
+    for pipeline, options, one_by_one in configs:
+        progress(f"{name}: pipeline {pipeline} options {options} one_by_one {one_by_one}")
         grads.upload_replica(0, reps[0])
         with harness.Session(grads, 25 * MIB, pipeline) as s:
             for opt, val in options:
@@ -75,7 +78,7 @@ def test_model_shapes_r8_fp32(name, config_id, sigma, nb):
             assert s.n_buckets == nb
             bucket_of, offset = d.ddp_get_assignment(s.ctx, n)
             assert bucket_of.tolist() == asg.bucket_of.tolist() and offset.tolist() == asg.offset_of.tolist()
-            s.sync()
+            s.sync(one_by_one=one_by_one)
             assert d.ddp_get_launch_log(s.ctx, 1) == wlog
             if pipeline == STAGED:      # flat buckets of two replicas, bit for bit
                 for b in (0, nb // 2, nb - 1):
@@ -124,21 +127,41 @@ def test_bucket_size_sweep_resnet50_fp16_r16():
                 check_bits(got, want[p], f"cap {cap} pipeline {pipeline} parameter {p}")
 
 
-@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
-def test_bert_large_no_sync_r32_with_unmarked_parameters(pipeline):
-    """K = 4 micro-steps accumulated locally, then one bucketed reduction over
-    R = 32 replicas; 39 seeded parameters never receive a gradient or a ready
-    mark.  Buckets {0, 1, one in the middle, the last} get host-generated
-    Gaussian micro-gradients and are recomputed by the oracle; every other
-    parameter gets device-generated noise (not compared)."""
+def bucket_groups(asg, buckets, limit_bytes):
+    """Consecutive runs of `buckets` holding at most limit_bytes (a bucket larger than that alone)."""
+    groups, cur, size = [], [], 0
+    for b in buckets:
+        nbytes = asg.buckets[b].elems * 4
+        if cur and size + nbytes > limit_bytes:
+            groups.append(cur)
+            cur, size = [], 0
+        cur.append(b)
+        size += nbytes
+    if cur:
+        groups.append(cur)
+    return groups
+
+
+@pytest.mark.parametrize("pipeline,every_bucket", [(STAGED, False), (FUSED, True)])
+def test_bert_large_no_sync_r32_with_unmarked_parameters(pipeline, every_bucket):
+    """Configuration 5: K = 4 micro-steps accumulated locally, then one bucketed
+    reduction over R = 32 replicas (ready marks one call at a time, as the
+    benchmark delivers them); 39 seeded parameters never receive a gradient or a
+    ready mark.  The oracle is streamed over the buckets in groups of about
+    100 MiB: host-generated Gaussian micro-gradients for every replica and
+    micro-step of the group, the accumulators of EVERY replica compared bit for
+    bit after the K steps, the expected averages computed from them.  Fused
+    pipeline: all 50 buckets.  Staged pipeline: buckets {0, 1, one in the middle,
+    the last}; the other parameters get device-generated noise and the
+    properties that hold everywhere are checked on them."""
     import torch
     d, harness = lib()
     numel = workloads.numel_of(workloads.bert_large_shapes())
     n, R, K = len(numel), 32, 4
     asg = oracle.assign_buckets(numel, [FP32] * n, 25 * MIB)
     nb = len(asg.buckets)
-    sampled_buckets = [0, 1, nb // 2, nb - 1]
-    sampled = sorted(p for b in sampled_buckets for p in asg.buckets[b].params)
+    compared = list(range(nb)) if every_bucket else [0, 1, nb // 2, nb - 1]
+    compared_params = set(p for b in compared for p in asg.buckets[b].params)
     unused = workloads.unused_param_set(5, n)
     assert len(unused) == 39
     unused_set = set(unused)
@@ -150,50 +173,73 @@ def test_bert_large_no_sync_r32_with_unmarked_parameters(pipeline):
     for r in range(R):
         for p in unused:
             grads.fill_bytes(r, p, 0xFF)         # NaN: must never be read
-    acc = {p: [np.zeros(numel[p], np.float32) for _ in range(R)] for p in sampled if p not in unused_set}
-    micro_ptrs = [None if p in unused_set else micro.ptr(r, p) for r in range(R) for p in range(n)]
-    gen_dev = torch.Generator(device="cuda")
-    gen_dev.manual_seed(5)
+    expected = {}
+    pool = ThreadPoolExecutor(max_workers=16)
     with harness.Session(grads, 25 * MIB, pipeline) as s:
-        for k in range(K):
-            progress(f"no_sync R=32 pipeline {pipeline}: micro-step {k}")
-            for r in range(R):
-                micro.bufs[r][: micro.slab_bytes // 4 * 4].view(torch.float32).normal_(0.0, 1e-3, generator=gen_dev)
-            host = gen(5, numel, R, 1e-3, FP32, k=k, params=list(acc))
-            for r in range(R):
-                for j, p in enumerate(acc):
-                    micro.upload(r, p, host[r][j])
-                    acc[p][r] = acc[p][r] + host[r][j]          # binary32, k ascending
-            torch.cuda.synchronize()
-            d.ddp_no_sync_accumulate(s.ctx, micro_ptrs)
-            d.ddp_synchronize(s.ctx)
-        for p in list(acc)[:3]:
-            check_bits(grads.download(R - 1, p), acc[p][R - 1], f"accumulator of parameter {p}")
-        progress("no_sync R=32: reduction")
-        s.sync(order)
+        noise = [p for p in range(n) if p not in compared_params and p not in unused_set]
+        if noise:
+            gen_dev = torch.Generator(device="cuda")
+            gen_dev.manual_seed(5)
+            ptrs = [micro.ptr(r, p) if p in set(noise) else None for r in range(R) for p in range(n)]
+            for k in range(K):
+                progress(f"no_sync R=32 pipeline {pipeline}: device noise, micro-step {k}")
+                for r in range(R):
+                    micro.bufs[r][: micro.slab_bytes // 4 * 4].view(torch.float32).normal_(0.0, 1e-3, generator=gen_dev)
+                torch.cuda.synchronize()
+                d.ddp_no_sync_accumulate(s.ctx, ptrs)
+                d.ddp_synchronize(s.ctx)
+        for group in bucket_groups(asg, compared, 100 * MIB):
+            progress(f"no_sync R=32 pipeline {pipeline}: buckets {group[0]}..{group[-1]} of {nb}")
+            params = [p for b in group for p in asg.buckets[b].params if p not in unused_set]
+            in_group = set(params)
+            ptrs = [micro.ptr(r, p) if p in in_group else None for r in range(R) for p in range(n)]
+            acc = [[np.zeros(numel[p], np.float32) for p in params] for _ in range(R)]
+            for k in range(K):
+                host = gen(5, numel, R, 1e-3, FP32, k=k, params=params)
+                for r in range(R):
+                    for j, p in enumerate(params):
+                        micro.upload(r, p, host[r][j])
+                torch.cuda.synchronize()
+                d.ddp_no_sync_accumulate(s.ctx, ptrs)
+
+                def add(r):                       # binary32, k ascending (Section 3.2.4)
+                    for j in range(len(params)):
+                        np.add(acc[r][j], host[r][j], out=acc[r][j])
+                list(pool.map(add, range(R)))
+                d.ddp_synchronize(s.ctx)
+            for r in range(R):                    # the accumulators of every replica
+                for j, p in enumerate(params):
+                    check_bits(grads.download(r, p), acc[r][j], f"accumulator of replica {r} parameter {p}")
+            index = {p: j for j, p in enumerate(params)}
+            for b in group:
+                bk = asg.buckets[b]
+                skipped = [p for p in bk.params if p in unused_set]
+                flats = list(pool.map(
+                    lambda r: oracle.pack_bucket(asg, b, {p: (acc[r][index[p]] if p in index else None) for p in bk.params}, skipped),
+                    range(R)))
+                avg = oracle.reduce_average(flats, FP32)
+                outs = [None] * n
+                oracle.unpack_bucket(asg, b, avg, outs)
+                for p in bk.params:
+                    expected[p] = outs[p]
+            del acc, host
+        progress(f"no_sync R=32 pipeline {pipeline}: reduction")
+        s.sync(order, one_by_one=True)
         assert d.ddp_get_launch_log(s.ctx, 1) == wlog
         used = d.ddp_get_used_map(s.ctx, n, 1)
         assert used.tolist() == [0 if p in unused_set else 1 for p in range(n)]
-    for b in sampled_buckets:
-        progress(f"no_sync R=32: oracle on bucket {b}")
-        bk = asg.buckets[b]
-        replica_grads = [{p: (acc[p][r] if p in acc else None) for p in bk.params} for r in range(R)]
-        flats = [oracle.pack_bucket(asg, b, replica_grads[r], [p for p in bk.params if p in unused_set]) for r in range(R)]
-        avg = oracle.reduce_average(flats, FP32)
-        outs = [None] * n
-        oracle.unpack_bucket(asg, b, avg, outs)
-        for p in bk.params:
-            got = grads.download(0, p)
-            if p in unused_set:
-                check_bits(got, np.zeros(numel[p], np.float32), f"never-marked parameter {p}")
-            else:
-                check_tolerance(got, outs[p], acc[p], 1e-6)
-                check_bits(got, outs[p], f"bucket {b} parameter {p}")
+    pool.shutdown()
+    progress(f"no_sync R=32 pipeline {pipeline}: comparing {len(expected)} parameters")
+    for p, want in expected.items():
+        got = grads.download(0, p)
+        if p in unused_set:
+            check_bits(want, np.zeros(numel[p], np.float32), f"oracle: never-marked parameter {p}")
+        check_bits(got, want, f"parameter {p} (bucket {int(asg.bucket_of[p])})")
     for p in unused:                         # everywhere: exact zeros, nothing leaked
         check_bits(grads.download(0, p), np.zeros(numel[p], np.float32), f"never-marked parameter {p}")
-    probe = [p for p in range(0, n, 37) if p not in unused_set]
-    for p in probe:                          # everywhere: finite averages
-        assert np.isfinite(grads.download(0, p)).all()
+    for p in range(0, n, 37):                # everywhere: finite averages
+        if p not in unused_set:
+            assert np.isfinite(grads.download(0, p)).all()
 
 
 def test_resnet50_partial_participation_r8():
