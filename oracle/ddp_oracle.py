@@ -31,6 +31,13 @@ Data Parallel Training", arXiv 2006.15704):
     the hooks is traced and the parameter-to-bucket mapping is rebuilt to
     follow it (`traced_visit_order`, `assign_buckets_in_order`).
 
+  * Section 6.2.3 (gradient compression): gradients need not travel in the
+    parameter's own type.  `compress` is what a rank would send (its fp32
+    gradient rounded once to a 16-bit format), `reduce_average_transport` /
+    `synchronize_transport` sum the R 16-bit copies in binary32, divide by R
+    and deliver the average in the parameter's type (fp32) -- the final
+    rounding to 16 bits of the all-16-bit path does not happen.
+
 The method is an exact reorganisation of the plain definition
 
     out_p[j] = (1/R) * sum_{r=0}^{R-1} g_{r,p}[j]
@@ -51,7 +58,10 @@ conversions, the tiny linear-regression mean-gradient identity, the no_sync
 identity and hand-worked launch schedules; for the traced-order mapping the
 reduction to the pinned default assignment, a hand-worked example, partition
 invariants, the earliest-possible-launch property and a brute-force search
-over small cases.
+over small cases; for the lower-precision transport a hand-worked example, the
+identity "its result rounded to the transport format equals the pinned
+all-16-bit result", integer inputs against exact arithmetic and the float64
+bound.
 
 Not pinned by anything in the paper: absolute timings and the best bucket
 size (the paper's curves are figures that are not available) -- "parity
@@ -344,6 +354,63 @@ def synchronize(numel: Sequence[int], dtype: Sequence[int], cap_bytes: int,
         flats = [pack_bucket(asg, b, replica_grads[r], unused) for r in range(R)]
         avg = reduce_average(flats, asg.buckets[b].dtype)
         unpack_bucket(asg, b, avg, outs)
+    return outs, asg, log
+
+
+# --------------------------------------------------------------------------
+# lower-precision transport  (Section 6.2.3)
+# --------------------------------------------------------------------------
+def compress(grad_f32: np.ndarray, transport: int) -> np.ndarray:
+    """What a rank sends for a binary32 gradient: every element rounded once,
+    to nearest even, to the 16-bit transport format."""
+    if transport not in (DT_FP16, DT_BF16):
+        raise ValueError("the transport format is fp16 or bf16")
+    return from_f32(np.ascontiguousarray(grad_f32, dtype=np.float32), transport)
+
+
+def reduce_average_transport(flats: Sequence[np.ndarray], transport: int,
+                             out_dtype: int = DT_FP32) -> np.ndarray:
+    """Elementwise over the R transported copies of one bucket:
+    s = float(x_0); s = s + float(x_r) for r = 1..R-1 (binary32);
+    y = s / float32(R); the result is y in the parameter's format (for
+    binary32 parameters: y itself, no second rounding)."""
+    R = len(flats)
+    if R < 1:
+        raise ValueError("need at least one replica")
+    with np.errstate(over="ignore", invalid="ignore"):
+        s = to_f32(flats[0], transport).copy()
+        for r in range(1, R):
+            s = s + to_f32(flats[r], transport)
+        y = s / np.float32(R)
+    return from_f32(y.astype(np.float32), out_dtype)
+
+
+def synchronize_transport(numel: Sequence[int], transport: Sequence[int], cap_bytes: int,
+                          replica_grads: Sequence[Sequence[np.ndarray]],
+                          ready_sequence: Optional[Sequence[int]] = None,
+                          out_dtype: int = DT_FP32):
+    """One synchronization whose replica gradients are held in a 16-bit
+    transport format (`transport[i]`, `replica_grads[r][i]` in that format)
+    while the averages are delivered in `out_dtype`.  A bucket is what is
+    communicated, so buckets are filled and capped by transport bytes; pack,
+    launch order and the handling of parameters that were never marked are
+    those of `synchronize`.  Returns (outs, assignment, launch_log)."""
+    n = len(numel)
+    R = len(replica_grads)
+    asg = assign_buckets(numel, transport, cap_bytes)
+    if ready_sequence is None:
+        ready_sequence = list(range(n - 1, -1, -1))
+    marked = set(int(p) for p in ready_sequence)
+    unused = [i for i in range(n) if i not in marked]
+    log = launch_schedule(asg, ready_sequence)
+    outs: List[Optional[np.ndarray]] = [None] * n
+    for b, _ in log:
+        bk = asg.buckets[b]
+        flats = [pack_bucket(asg, b, replica_grads[r], unused) for r in range(R)]
+        avg = reduce_average_transport(flats, bk.dtype, out_dtype)
+        for i in bk.params:                       # the write-back of unpack_bucket, in the output type
+            off = int(asg.offset_of[i])
+            outs[i] = np.array(avg[off:off + int(asg.numel[i])], copy=True)
     return outs, asg, log
 
 
