@@ -56,9 +56,10 @@ WORKLOADS = {
     "bert_large": ("bert_large", 3, 8, 1e-3, 0, 25 * MIB),
     "resnet50_fp16_r16": ("resnet50", 4, 16, 1e-2, 1, 25 * MIB),      # the bucket-size sweep's configuration
     "bert_large_r32": ("bert_large", 5, 32, 1e-3, 0, 25 * MIB),        # configuration 5's reduction (R = 32)
+    "bert_large_bf16": ("bert_large", 3, 8, 1e-3, 2, 25 * MIB),        # 16-bit transport of BERT-large's gradients
 }
-ALL_LEGS = ["headline", "bert_large", "one_call", "single_set", "per_bucket", "overlap", "r32", "staged",
-            "accumulate", "cpu"]
+ALL_LEGS = ["headline", "bert_large", "one_call", "single_set", "per_bucket", "overlap", "r32", "transport",
+            "staged", "accumulate", "cpu"]
 DT_NAME = {0: "f32", 1: "f16", 2: "bf16"}
 
 
@@ -102,7 +103,8 @@ class Rig:
     """`sets` independent sets of replica gradients of one workload, one context
     per set, all contexts on the same pair of streams."""
 
-    def __init__(self, lib, harness, torch, workload, sets, pipeline, options=(), same_stream=False):
+    def __init__(self, lib, harness, torch, workload, sets, pipeline, options=(), same_stream=False,
+                 binary32_outputs=False):
         self.lib, self.torch = lib, torch
         shape_name, self.config_id, self.R, self.sigma, self.dtype, self.cap = WORKLOADS[workload]
         import workloads
@@ -113,10 +115,16 @@ class Rig:
         self.order = list(range(self.n - 1, -1, -1))
         self.grads = [device_grads(harness, torch, self.numel, self.dtype, self.R, self.sigma, 1000 * self.config_id + k)
                       for k in range(sets)]
+        # bytes a synchronization has to move: every replica gradient read once, the average written once
+        self.alg_bytes = (self.R + 1) * self.B
+        self.outputs = [None] * sets
+        if binary32_outputs:         # 16-bit gradients in, binary32 averages out (Section 6.2.3)
+            self.outputs = [harness.DeviceGrads(self.numel, [0] * self.n, 1) for _ in range(sets)]
+            self.alg_bytes = self.R * self.B + 4 * sum(self.numel)
         self.sessions = []
         streams = None
-        for g in self.grads:
-            s = harness.Session(g, self.cap, pipeline, same_stream=same_stream, streams=streams)
+        for g, o in zip(self.grads, self.outputs):
+            s = harness.Session(g, self.cap, pipeline, same_stream=same_stream, streams=streams, outputs=o)
             streams = (s.reduce_stream, s.backward_stream)
             for opt, val in options:
                 lib.ddp_set_option(s.ctx, opt, val)
@@ -129,7 +137,7 @@ class Rig:
     def close(self):
         for s in self.sessions:
             s.close()
-        self.sessions, self.grads = [], []
+        self.sessions, self.grads, self.outputs = [], [], []
 
     def step(self, k, per_call):
         ctx = self.sessions[k % len(self.sessions)].ctx
@@ -184,14 +192,14 @@ class Rig:
         it_ms = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_ITERATION)[0] for s in self.sessions])
         for s in self.sessions:
             lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 0)
-        R, B = self.R, self.B
+        alg = self.alg_bytes
         ms_per_step = (t1 - t0) * 1e3 / steps
         launches = launches_per_step * steps
-        achieved = (R + 1) * B * steps / region_ms / 1e6
+        achieved = alg * steps / region_ms / 1e6
         return {
             "ms_per_step": round(ms_per_step, 4),
-            "value_gbps": round((R + 1) * B / ms_per_step / 1e6, 1),
-            "pct_hbm_peak_end_to_end": round(100.0 * (R + 1) * B / ms_per_step / 1e6 / HBM_PEAK_GBPS, 2),
+            "value_gbps": round(alg / ms_per_step / 1e6, 1),
+            "pct_hbm_peak_end_to_end": round(100.0 * alg / ms_per_step / 1e6 / HBM_PEAK_GBPS, 2),
             "host_enqueue_ms_per_step": round((t_enq - t0) * 1e3 / steps, 4),
             "launches_per_step": launches_per_step,
             "roofline": {
@@ -203,7 +211,7 @@ class Rig:
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "avg_launch_ms": round(region_ms / max(launches, 1), 5),
                 "launches": launches,
-                "algorithmic_bytes_per_launch": round((R + 1) * B / max(launches_per_step, 1)),
+                "algorithmic_bytes_per_launch": round(alg / max(launches_per_step, 1)),
                 "timing": "one HIP event pair around the timed region on the backward stream; "
                           "launches on the two reduction streams may overlap, the average is region / launches",
                 "iteration_ms": spread(it_ms),
@@ -359,6 +367,27 @@ def r32_leg(lib, harness, torch, steps=8):
     finally:
         rig.close()
     return out
+
+
+def transport_leg(lib, harness, torch, steps):
+    """Section 6.2.3 in the form 16-bit gradients in, binary32 averages out: BERT-large's gradients
+    as bf16 copies, R = 8.  Bytes per synchronization: R x 2 bytes + 4 bytes per element, i.e.
+    (R/2 + 1) x the binary32 model instead of (R + 1) x."""
+    rig = Rig(lib, harness, torch, "bert_large_bf16", 2, lib.DDP_PIPELINE_FUSED, binary32_outputs=True)
+    try:
+        res = rig.measure(steps, 2, per_call=True)
+        one = rig.measure(steps, 2, per_call=False)
+        elems = sum(rig.numel)
+        return {"workload": f"bert_large shape, bf16 gradients of R={rig.R} replicas, binary32 averages to separate tensors",
+                "bytes_per_sync": rig.alg_bytes, "bytes_per_sync_all_binary32": (rig.R + 1) * 4 * elems,
+                "ms_per_sync": res["ms_per_step"], "gbps": res["roofline"]["achieved"],
+                "frac_of_hbm_peak": res["roofline"]["frac"], "launches_per_step": res["launches_per_step"],
+                "iteration_ms": res["roofline"]["iteration_ms"],
+                "marks_in_one_call": {"ms_per_sync": one["ms_per_step"], "gbps": one["roofline"]["achieved"],
+                                      "frac_of_hbm_peak": one["roofline"]["frac"],
+                                      "launches_per_step": one["launches_per_step"]}}
+    finally:
+        rig.close()
 
 
 def staged_leg(lib, harness, torch, steps):
@@ -546,6 +575,8 @@ def main() -> int:
         out["overlap"] = overlap_leg(lib, harness, torch)
     if "r32" in legs:
         out["bert_large_r32"] = r32_leg(lib, harness, torch)
+    if "transport" in legs:
+        out["bf16_transport"] = transport_leg(lib, harness, torch, max(10, args.steps // 2))
     if "staged" in legs:
         out["staged"] = staged_leg(lib, harness, torch, max(5, args.steps // 4))
     if "accumulate" in legs:

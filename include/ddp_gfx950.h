@@ -238,6 +238,24 @@ int32_t ddp_get_option(ddp_ctx* ctx, int32_t option, int64_t* value);
 int32_t ddp_register_params(ddp_ctx* ctx, int32_t n, const int64_t* numel,
                             const int32_t* dtype, void* const* grad_ptrs);
 
+/* Section 6.2.3 (gradient compression: gradients need not be communicated in
+ * the parameter's type), in the form "16-bit on the wire, binary32 arithmetic and
+ * result": every registered gradient is fp16 or bf16 -- what each of the R
+ * processes would send -- and the average of parameter i, the binary32 sum over
+ * the replicas in order r = 0 .. R-1 divided by R, is written UNROUNDED as
+ * numel[i] binary32 values to out_ptrs[i] (device pointers, host array of n
+ * entries, copied; memory owned by the caller and borrowed until ddp_destroy;
+ * aligned to 4 bytes, 16-byte alignment is exploited).  No gradient tensor is
+ * written; buckets are still filled and capped by the 16-bit gradient bytes (a
+ * bucket is what is communicated).  A synchronization then moves (R/2 + 1) x
+ * the binary32 model bytes instead of (R + 1) x.  Parameters that nobody used
+ * receive binary32 zeros, or are left untouched with DDP_OPT_FIND_UNUSED.
+ * Between ddp_register_params and ddp_build_buckets, fused pipeline, not with
+ * DDP_OPT_WRITE_ALL (DDP_ERR_UNSUPPORTED from ddp_build_buckets otherwise).
+ * Errors: a binary32 gradient among the registered ones, null or misaligned
+ * pointer -> DDP_ERR_ARG; called out of order -> DDP_ERR_STATE. */
+int32_t ddp_set_outputs(ddp_ctx* ctx, void* const* out_ptrs);
+
 /* Algorithm 1, constructor: buckets are filled with the parameters taken in
  * reverse registration order, under the size cap `cap_bytes` (Section 4.2,
  * bucket_cap_mb; 0 = every gradient alone, Section 5.2; DDP_CAP_WHOLE_MODEL =

@@ -47,7 +47,7 @@ DDP_K_PACK, DDP_K_REDUCE, DDP_K_UNPACK, DDP_K_ACCUMULATE, DDP_K_ITERATION = 0, 1
 
 EXPORTS = [
     "ddp_version", "ddp_last_error", "ddp_create", "ddp_destroy", "ddp_set_option", "ddp_get_option",
-    "ddp_register_params", "ddp_build_buckets", "ddp_rebuild_buckets", "ddp_get_ready_order",
+    "ddp_register_params", "ddp_set_outputs", "ddp_build_buckets", "ddp_rebuild_buckets", "ddp_get_ready_order",
     "ddp_get_assignment",
     "ddp_get_bucket_info", "ddp_get_bucket_ptr", "ddp_mark_ready", "ddp_mark_ready_local",
     "ddp_get_global_used",
@@ -96,6 +96,7 @@ _lib.ddp_destroy.argtypes = [_vp]
 _lib.ddp_set_option.argtypes = [_vp, _i32, _i64]
 _lib.ddp_get_option.argtypes = [_vp, _i32, C.POINTER(_i64)]
 _lib.ddp_register_params.argtypes = [_vp, _i32, C.POINTER(_i64), C.POINTER(_i32), C.POINTER(_vp)]
+_lib.ddp_set_outputs.argtypes = [_vp, C.POINTER(_vp)]
 _lib.ddp_build_buckets.argtypes = [_vp, _u64]
 _lib.ddp_rebuild_buckets.argtypes = [_vp, _u64]
 _lib.ddp_get_ready_order.argtypes = [_vp, _i32, C.POINTER(_i32), _i32, C.POINTER(_i32)]
@@ -153,6 +154,7 @@ def ddp_last_error(ctx) -> str:
 
 
 _replicas = {}      # context address -> R, for checking array lengths before they cross the C ABI
+_nparams = {}       # context address -> n
 
 
 def ddp_create(R: int, device: int, reduce_stream: int = 0, backward_stream: int = 0):
@@ -167,6 +169,7 @@ def ddp_create(R: int, device: int, reduce_stream: int = 0, backward_stream: int
 
 def ddp_destroy(ctx) -> None:
     _replicas.pop(ctx.value, None)
+    _nparams.pop(ctx.value, None)
     _check(ctx, _lib.ddp_destroy(ctx))
 
 
@@ -190,6 +193,18 @@ def ddp_register_params(ctx, numel: Sequence[int], dtype: Sequence[int],
         arr = _ptr_array(grad_ptrs)
         gp = _as(arr, _vp)
     _check(ctx, _lib.ddp_register_params(ctx, len(ne), _as(ne, _i64), _as(dt, _i32), gp))
+    _nparams[ctx.value] = len(ne)
+
+
+def ddp_set_outputs(ctx, out_ptrs: Optional[Sequence[int]]) -> None:
+    """out_ptrs: n device addresses of binary32 tensors that receive the averages."""
+    if out_ptrs is None:
+        _check(ctx, _lib.ddp_set_outputs(ctx, None))
+        return
+    arr = _ptr_array(out_ptrs)
+    if len(arr) != _nparams.get(ctx.value, len(arr)):      # the library reads exactly n pointers
+        raise ValueError(f"out_ptrs has {len(arr)} entries, {_nparams[ctx.value]} parameters are registered")
+    _check(ctx, _lib.ddp_set_outputs(ctx, _as(arr, _vp)))
 
 
 def ddp_build_buckets(ctx, cap_bytes: int) -> int:

@@ -70,6 +70,7 @@ struct ddp_ctx {
     ddp::BucketPlan plan;
     ddp::ReadyTracker tracker;
     std::vector<void*> grad_ptrs;            // [R][n], registration order
+    std::vector<void*> out_ptrs;             // [n] binary32 output tensors (ddp_set_outputs), else empty
 
     // device memory owned by the library
     char* slabs = nullptr;                   // R input slabs followed by the output slab
@@ -425,7 +426,7 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
         // Paired tiles keep more loads in flight per thread, which pays on long launches made of
         // large tensors (most tiles interior); with many small tensors the pairs fall back to two
         // tiles one after the other and only lengthen the blocks.
-        const bool pair = bytes >= c->pair_min_bytes &&
+        const bool pair = c->out_ptrs.empty() && bytes >= c->pair_min_bytes &&
                           (c->pair_min_bytes == 0 ||      // 0 = always (lets tests reach every path of the kernel)
                            ntiles >= ddp_ctx::kPairMinTilesPerSegment * static_cast<int64_t>(seg_end - seg_begin));
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
@@ -798,6 +799,28 @@ int32_t ddp_register_params(ddp_ctx* c, int32_t n, const int64_t* numel, const i
     return DDP_OK;
 }
 
+int32_t ddp_set_outputs(ddp_ctx* c, void* const* out_ptrs) {
+    if (!c) return DDP_ERR_ARG;
+    if (!c->registered) return fail(c, DDP_ERR_STATE, "ddp_set_outputs before ddp_register_params");
+    if (c->built) return fail(c, DDP_ERR_STATE, "ddp_set_outputs after ddp_build_buckets");
+    const int32_t n = static_cast<int32_t>(c->plan.params.size());
+    for (int32_t i = 0; i < n; ++i)
+        if (c->plan.params[i].dtype != DDP_FP16 && c->plan.params[i].dtype != DDP_BF16)
+            return fail(c, DDP_ERR_ARG, "ddp_set_outputs: binary32 outputs are for gradients held in fp16 or bf16");
+    if (c->plan_only) {            // the plan does not depend on where the averages go
+        c->out_ptrs.assign(n, nullptr);
+        return DDP_OK;
+    }
+    if (!out_ptrs) return fail(c, DDP_ERR_ARG, "ddp_set_outputs: out_ptrs is null");
+    for (int32_t i = 0; i < n; ++i) {
+        if (c->plan.params[i].numel > 0 && !out_ptrs[i]) return fail(c, DDP_ERR_ARG, "ddp_set_outputs: null output pointer");
+        if (reinterpret_cast<uintptr_t>(out_ptrs[i]) % 4 != 0)
+            return fail(c, DDP_ERR_ARG, "ddp_set_outputs: output pointer not aligned to 4 bytes");
+    }
+    c->out_ptrs.assign(out_ptrs, out_ptrs + n);
+    return DDP_OK;
+}
+
 // Assigns the buckets (visiting the parameters in `order`, or in reverse
 // registration order without one) and builds everything that depends on the
 // assignment: tracker, flag tables, slabs, segment tables, events.
@@ -817,7 +840,13 @@ static int32_t build_internal(ddp_ctx* c, uint64_t cap_bytes, const std::vector<
         // slab layout (bucket bases aligned to 256 bytes, lengths padded to 16) and segment
         // tables in bucket-major fill order
         ddp::HostTables ht;
-        ddp::build_host_tables(c->plan, c->grad_ptrs.data(), c->R, ht);
+        if (!c->out_ptrs.empty()) {
+            if (c->pipeline != DDP_PIPELINE_FUSED)
+                return fail(c, DDP_ERR_UNSUPPORTED, "binary32 outputs (ddp_set_outputs) need the fused pipeline");
+            if (c->write_all)
+                return fail(c, DDP_ERR_UNSUPPORTED, "binary32 outputs (ddp_set_outputs) cannot be combined with DDP_OPT_WRITE_ALL");
+        }
+        ddp::build_host_tables(c->plan, c->grad_ptrs.data(), c->R, ht, c->out_ptrs.empty() ? nullptr : c->out_ptrs.data());
         c->bucket_slab_off = ht.bucket_slab_off;
         c->bucket_vecs = ht.bucket_vecs;
         c->slab_stride = ht.slab_stride;
@@ -831,15 +860,18 @@ static int32_t build_internal(ddp_ctx* c, uint64_t cap_bytes, const std::vector<
         // one allocation for the segment records and the pointer rows
         const int64_t R = c->R;
         const size_t seg_bytes = sizeof(ddp::SegInfo) * n;
-        const size_t bytes = seg_bytes + sizeof(void*) * ht.grad.size();
+        const size_t grad_bytes = sizeof(void*) * ht.grad.size();
+        const size_t bytes = seg_bytes + grad_bytes + sizeof(void*) * ht.out.size();
         std::vector<char> host(bytes);
         std::memcpy(host.data(), ht.seg.data(), seg_bytes);
-        std::memcpy(host.data() + seg_bytes, ht.grad.data(), sizeof(void*) * ht.grad.size());
+        std::memcpy(host.data() + seg_bytes, ht.grad.data(), grad_bytes);
+        if (!ht.out.empty()) std::memcpy(host.data() + seg_bytes + grad_bytes, ht.out.data(), sizeof(void*) * ht.out.size());
         HIPCHK(c, hipMalloc(&c->d_tables, bytes));
         HIPCHK(c, hipMemcpy(c->d_tables, host.data(), bytes, hipMemcpyHostToDevice));
         char* d = static_cast<char*>(c->d_tables);
         c->tables.seg = reinterpret_cast<const ddp::SegInfo*>(d);
         c->tables.grad = reinterpret_cast<void* const*>(d + seg_bytes);
+        c->tables.out = ht.out.empty() ? nullptr : reinterpret_cast<void* const*>(d + seg_bytes + grad_bytes);
         c->tables.G = n;
         c->tables.R = c->R;
         {

@@ -38,6 +38,9 @@ struct SegInfo {               // 32 bytes, read with one scalar load
                                // modulo 16 (replica 0)
     __host__ __device__ int dtype() const { return flags & 0xFF; }
     __host__ __device__ bool congruent() const { return (flags & 0x100) != 0; }
+    // bit 9 (binary32 outputs only): the output tensor's address modulo 16 equals twice
+    // replica 0's address modulo 16, so whole input vectors map to whole output vectors
+    __host__ __device__ bool out_congruent() const { return (flags & 0x200) != 0; }
     __host__ __device__ int lead_bytes() const { return (flags >> 16) & 0xF; }
 };
 
@@ -46,6 +49,8 @@ struct SegTables {
     const int32_t* tile_seg;   // [tiles] segment that each tile belongs to
     void* const* grad;         // [G*R + 8] replica r's gradient of segment g at [g*R+r]; eight
                                // null entries of padding so that any row can be read 8 wide
+    void* const* out;          // [G] binary32 output tensor of segment g (lower-precision
+                               // transport, Section 6.2.3), or null: averages go to the gradients
     int32_t G;
     int32_t R;
 };
@@ -105,6 +110,8 @@ hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
                                int unroll, bool pair, bool nontemporal, unsigned lds,
                                const GateRecord* gate, uint32_t tag, hipStream_t s);
+// (with t.out set -- 16-bit gradients, binary32 averages written to t.out -- nwrite must be 1
+// and pair is ignored)
 
 // ---- stream ordering through device flags -------------------------------------
 // A bucket launch on a reduction stream must come after the backward-stream work

@@ -434,7 +434,25 @@ __device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r, 
         for (int u = 0; u < U; ++u) add_into<DT>(acc[u], x[i][u]);
 }
 
-template <int DT>
+// Where the averages go.  Normally into the gradient tensors themselves, in
+// their own format (replica 0's, or all of them).  With OUT32 the gradients are a
+// 16-bit transport format (Section 6.2.3) and the averages are written as
+// binary32, unrounded, to a separate tensor per parameter (SegTables::out): two
+// 16-byte stores per 16-byte input vector, at twice the byte offset.
+template <int DT, bool NT>
+__device__ __forceinline__ void store_out32(char* out, int64_t in_byte_off, const float (&y)[Fmt<DT>::VEC]) {
+    static_assert(Fmt<DT>::VEC == 8, "binary32 outputs are for the 16-bit formats");
+    u32x4 lo, hi;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        lo[i] = __float_as_uint(y[i]);
+        hi[i] = __float_as_uint(y[4 + i]);
+    }
+    store16s<NT>(out + 2 * in_byte_off, lo);
+    store16s<NT>(out + 2 * in_byte_off + 16, hi);
+}
+
+template <int DT, bool OUT32 = false>
 __device__ __forceinline__ void reduce_element(const SegTables& t, int g, int R, int nwrite,
                                                int64_t idx, bool zero, uint64_t used, const Scale& sc) {
     constexpr int ES = Fmt<DT>::ES;
@@ -449,6 +467,10 @@ __device__ __forceinline__ void reduce_element(const SegTables& t, int g, int R,
         }
         y = apply_scale(sc, s);
     }
+    if (OUT32) {
+        gstore<float>(static_cast<char*>(t.out[g]) + idx * 4, y);
+        return;
+    }
     for (int w = 0; w < nwrite; ++w)
         Fmt<DT>::store1(static_cast<char*>(t.grad[static_cast<int64_t>(g) * t.R + w]) + idx * ES, y);
 }
@@ -462,7 +484,7 @@ __device__ __forceinline__ uint64_t used_mask(const uint8_t* __restrict__ flags,
 }
 
 // One tile of the fused gather-reduce-scatter.
-template <int DT, bool NT, int U>
+template <int DT, bool NT, int U, bool OUT32 = false>
 __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int R, int nwrite,
                                            const uint8_t* __restrict__ local, int keep_unused,
                                            const Scale& sc) {
@@ -487,7 +509,10 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
     const bool zero = used == 0;            // ... or become zeros
     const bool all_used = used == everyone;
     const int sh = si.lead_bytes() / ES;    // replica 0's tensor starts this many elements past a 16-byte boundary
-    const bool fast = si.congruent();       // every replica's tensor sits at the same offset modulo 16
+    // every replica's tensor sits at the same offset modulo 16 (and, with binary32 outputs, the
+    // output tensor sits where whole input vectors map to whole output vectors)
+    const bool fast = si.congruent() && (!OUT32 || si.out_congruent());
+    char* const outp = OUT32 ? static_cast<char*>(t.out[g]) : nullptr;
     const int64_t e_tile = ltile * (TILE_BYTES / ES) - sh;
 
     if (fast && all_used && e_tile >= 0 && e_tile + TILE_BYTES / ES <= numel) {
@@ -504,6 +529,13 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
                 lane_off, acc);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                if (OUT32) {
+                    float y[VEC];
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) y[i] = apply_scale(sc, acc[u][i]);
+                    if constexpr (OUT32) store_out32<DT, NT>(outp, tile_byte + lane_off[u], y);
+                    continue;
+                }
                 const u32x4 out = scaled<DT>(sc, acc[u]);
                 store16s<NT>(const_cast<char*>(pre[0]) + tile_byte + lane_off[u], out);
                 for (int w = 1; w < nwrite; ++w)
@@ -538,7 +570,12 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kind[u] == V_NONE) continue;
-            if (kind[u] == V_FULL && (fast || zero)) {
+            if (OUT32 && kind[u] == V_FULL && fast) {
+                float y[VEC];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) y[i] = zero ? 0.0f : apply_scale(sc, acc[u][i]);
+                if constexpr (OUT32) store_out32<DT, NT>(outp, off[u], y);
+            } else if (!OUT32 && kind[u] == V_FULL && (fast || zero)) {
                 u32x4 out = zero16();
                 if (!zero) {
                     float y[VEC];
@@ -561,7 +598,7 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
             } else {
                 for (int i = 0; i < VEC; ++i) {
                     const int64_t idx = e[u] + i;
-                    if (idx >= 0 && idx < numel) reduce_element<DT>(t, g, R, nwrite, idx, zero, used, sc);
+                    if (idx >= 0 && idx < numel) reduce_element<DT, OUT32>(t, g, R, nwrite, idx, zero, used, sc);
                 }
             }
         }
@@ -574,7 +611,7 @@ __device__ __forceinline__ bool gate_failed(const GateRecord* __restrict__ gate,
     return gate != nullptr && gate->failed_tag == tag;
 }
 
-template <int DT, bool NT, int U>
+template <int DT, bool NT, int U, bool OUT32 = false>
 __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int64_t tile_base, int R,
                                                              int nwrite,
                                                              const uint8_t* __restrict__ local,
@@ -582,7 +619,7 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int64_
                                                              const GateRecord* __restrict__ gate,
                                                              uint32_t tag) {
     if (gate_failed(gate, tag)) return;
-    fused_tile<DT, NT, U>(t, tile_base + blockIdx.x, R, nwrite, local, keep_unused, sc);
+    fused_tile<DT, NT, U, OUT32>(t, tile_base + blockIdx.x, R, nwrite, local, keep_unused, sc);
 }
 
 // Large launches: a block takes two neighbouring tiles.  When both lie inside
@@ -679,7 +716,7 @@ __global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long 
 
 // Launches whose gate gave up, redone once every gradient exists.  Block j takes
 // the tiles j, j + G, ... of each failed launch.
-template <int DT, bool NT, int U>
+template <int DT, bool NT, int U, bool OUT32 = false>
 __global__ __launch_bounds__(BLOCK) void repair_kernel(SegTables t, OrderState* st,
                                                        const GateRecord* __restrict__ rec,
                                                        int nb, uint32_t tag, int R, int nwrite,
@@ -690,7 +727,7 @@ __global__ __launch_bounds__(BLOCK) void repair_kernel(SegTables t, OrderState* 
         if (r.failed_tag != tag || r.dtype != DT) continue;
         if (blockIdx.x == 0 && threadIdx.x == 0) st->repaired += 1;   // (repair launches run one after the other)
         for (int64_t i = blockIdx.x; i < r.ntiles; i += gridDim.x)
-            fused_tile<DT, NT, U>(t, r.tile_base + i, R, nwrite, local, keep_unused, sc);
+            fused_tile<DT, NT, U, OUT32>(t, r.tile_base + i, R, nwrite, local, keep_unused, sc);
     }
 }
 
@@ -946,6 +983,17 @@ hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base,
                                const GateRecord* gate, uint32_t tag, hipStream_t s) {
     if (ntiles <= 0) return hipSuccess;
     const int keep = keep_unused ? 1 : 0;
+    if (t.out != nullptr) {
+        // 16-bit gradients, binary32 averages to separate tensors
+        constexpr int U = TILE_VECS / BLOCK >= 2 ? 2 : 1;
+        if (nwrite != 1 || (dtype != 1 && dtype != 2)) return hipErrorInvalidValue;
+        const dim3 grid(static_cast<unsigned>(ntiles));
+        if (dtype == 1)
+            return nontemporal ? launch(fused_reduce_kernel<1, true, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag)
+                               : launch(fused_reduce_kernel<1, false, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        return nontemporal ? launch(fused_reduce_kernel<2, true, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag)
+                           : launch(fused_reduce_kernel<2, false, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+    }
     switch (dtype) {
         case 0: return fused_unroll<0>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
         case 1: return fused_unroll<1>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
@@ -973,6 +1021,14 @@ hipError_t launch_repair(int dtype, const SegTables& t, OrderState* st, const Ga
     constexpr int U = TILE_VECS / BLOCK >= 2 ? 2 : 1;
     const dim3 grid(static_cast<unsigned>(blocks));
     const int keep = keep_unused ? 1 : 0;
+    if (t.out != nullptr) {
+        if (nwrite != 1 || (dtype != 1 && dtype != 2)) return hipErrorInvalidValue;
+        if (dtype == 1)
+            return nt ? launch(repair_kernel<1, true, U, true>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc)
+                      : launch(repair_kernel<1, false, U, true>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc);
+        return nt ? launch(repair_kernel<2, true, U, true>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc)
+                  : launch(repair_kernel<2, false, U, true>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc);
+    }
     switch (dtype) {
         case 0: return nt ? launch(repair_kernel<0, true, U>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc)
                           : launch(repair_kernel<0, false, U>, grid, 0u, s, t, st, rec, nb, tag, R, nwrite, local, keep, sc);

@@ -19,12 +19,15 @@ struct HostTables {
     std::vector<SegInfo> seg;               // [G]
     std::vector<void*> grad;                // [G * R + 8], see SegTables::grad
     std::vector<int32_t> tile_seg;          // [tile0[G]]
+    std::vector<void*> out;                 // [G] binary32 output tensors (empty without outputs)
 };
 
 inline int64_t round_up_to(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 // grad_ptrs: [R][n] in registration order (the layout of ddp_register_params).
-inline void build_host_tables(const BucketPlan& plan, void* const* grad_ptrs, int R, HostTables& h) {
+// out_ptrs: [n] binary32 output tensors in registration order, or null.
+inline void build_host_tables(const BucketPlan& plan, void* const* grad_ptrs, int R, HostTables& h,
+                              void* const* out_ptrs = nullptr) {
     const int32_t n = static_cast<int32_t>(plan.params.size());
     const int32_t nb = static_cast<int32_t>(plan.buckets.size());
     h.bucket_slab_off.resize(nb);
@@ -41,6 +44,7 @@ inline void build_host_tables(const BucketPlan& plan, void* const* grad_ptrs, in
     h.tile0.assign(n + 1, 0);
     h.seg.assign(n, SegInfo{});
     h.grad.assign(static_cast<size_t>(R) * n + 8, nullptr);
+    h.out.assign(out_ptrs ? n : 0, nullptr);
     for (int32_t b = 0; b < nb; ++b) {
         const BucketInfo& bk = plan.buckets[b];
         for (size_t k = 0; k < bk.params.size(); ++k) {
@@ -67,6 +71,11 @@ inline void build_host_tables(const BucketPlan& plan, void* const* grad_ptrs, in
             h.seg[g].flat_byte = flat_byte;
             h.seg[g].param = i;
             h.seg[g].flags = p.dtype | (cong ? 0x100 : 0) | (static_cast<int>(a0 & 15u) << 16);
+            if (out_ptrs) {
+                h.out[g] = out_ptrs[i];
+                const uintptr_t o = reinterpret_cast<uintptr_t>(out_ptrs[i]);
+                if ((o & 15u) == ((2 * (a0 & 15u)) & 15u)) h.seg[g].flags |= 0x200;
+            }
         }
     }
     h.tile_seg.resize(static_cast<size_t>(h.tile0[n]));

@@ -91,8 +91,12 @@ class Session:
     """A context with its two streams.  Thin convenience over the binding."""
 
     def __init__(self, grads: DeviceGrads, cap_bytes: int, pipeline: int = B.DDP_PIPELINE_STAGED,
-                 write_all: bool = False, same_stream: bool = False, streams=None):
+                 write_all: bool = False, same_stream: bool = False, streams=None,
+                 outputs: Optional[DeviceGrads] = None):
+        """outputs: a one-replica binary32 DeviceGrads of the same numel that receives the
+        averages of 16-bit gradients (ddp_set_outputs)."""
         self.grads = grads
+        self.outputs = outputs
         self.pipeline = pipeline
         self.ctx = None
         # HIP streams that share a hardware queue run one after the other: a reduction stream
@@ -111,6 +115,8 @@ class Session:
             B.ddp_set_option(self.ctx, B.DDP_OPT_PIPELINE, pipeline)
             B.ddp_set_option(self.ctx, B.DDP_OPT_WRITE_ALL, 1 if write_all else 0)
             B.ddp_register_params(self.ctx, grads.numel, grads.dtype, grads.ptrs())
+            if outputs is not None:
+                B.ddp_set_outputs(self.ctx, [outputs.ptr(0, i) for i in range(outputs.n)])
             self.n_buckets = B.ddp_build_buckets(self.ctx, cap_bytes)
             self.streams_concurrent = bool(B.ddp_get_option(self.ctx, B.DDP_OPT_FLAG_ORDER))
             if (self.streams_concurrent or streams is not None or same_stream

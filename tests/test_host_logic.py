@@ -369,3 +369,29 @@ def test_options_read_back_on_a_plan_only_context(d):
             assert e.value.code == d.DDP_ERR_ARG
     finally:
         d.ddp_destroy(ctx)
+
+
+def test_outputs_for_16_bit_gradients_on_a_plan_only_context(d):
+    ctx = d.ddp_create(2, d.DDP_DEVICE_NONE)
+    try:
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_set_outputs(ctx, None)
+        assert e.value.code == d.DDP_ERR_STATE
+        d.ddp_register_params(ctx, [1000, 2000, 3000], [1, 1, 2], None)
+        d.ddp_set_outputs(ctx, None)           # a plan has no memory: the pointers are not looked at
+        # buckets are capped by the 16-bit bytes: 2000 + 1000 elements of 2 bytes fit 6000 bytes
+        assert d.ddp_build_buckets(ctx, 6000) == 2
+        assert d.ddp_get_assignment(ctx, 3)[0].tolist() == oracle.assign_buckets([1000, 2000, 3000], [1, 1, 2], 6000).bucket_of.tolist()
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_set_outputs(ctx, None)
+        assert e.value.code == d.DDP_ERR_STATE
+    finally:
+        d.ddp_destroy(ctx)
+    ctx = d.ddp_create(2, d.DDP_DEVICE_NONE)
+    try:
+        d.ddp_register_params(ctx, [10, 10], [0, 1], None)
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_set_outputs(ctx, None)
+        assert e.value.code == d.DDP_ERR_ARG
+    finally:
+        d.ddp_destroy(ctx)
