@@ -231,8 +231,15 @@ int32_t ddp_get_option(ddp_ctx* ctx, int32_t option, int64_t* value);
  *   dtype[n]      host, DDP_FP32 / DDP_FP16 / DDP_BF16
  *   grad_ptrs     host array of R*n device pointers, row-major [r][i]: replica
  *                 r's gradient of parameter i; contiguous, aligned at least to
- *                 its element size (16-byte alignment is exploited, not
- *                 required).  Ignored (may be NULL) on a plan-only context.
+ *                 its element size.  16-byte alignment is exploited, not
+ *                 required: what matters is that the R tensors of a
+ *                 parameter share one address modulo 16 (whatever it is);
+ *                 then whole tiles take the unpredicated path (77 % of the HBM
+ *                 peak measured on 25 MiB tensors, R = 8).  Replicas that are
+ *                 shifted against each other are read with element-aligned
+ *                 16-byte loads and cost extra cache lines (62 % measured on
+ *                 the same list with the replicas 4 bytes apart modulo 16).
+ *                 Ignored (may be NULL) on a plan-only context.
  * Errors: n <= 0, null arrays or pointers, unknown dtype -> DDP_ERR_ARG;
  * second call -> DDP_ERR_STATE. */
 int32_t ddp_register_params(ddp_ctx* ctx, int32_t n, const int64_t* numel,

@@ -56,6 +56,22 @@ __device__ __forceinline__ u32x4 zero16() {
     u32x4 z = {0u, 0u, 0u, 0u};
     return z;
 }
+// 16 bytes at an address that is only element-aligned (2 or 4 bytes): gfx950
+// serves such an access with one vector instruction too, so a tensor that sits
+// off the 16-byte grid of its peers costs extra cache lines, not a scalar loop.
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+template <bool NT>
+__device__ __forceinline__ u32x4 load16u(const char* p) {
+    DDP_GLOBAL const u32x4_a2* q = (DDP_GLOBAL const u32x4_a2*)(p);
+    if (NT) return __builtin_nontemporal_load(q);
+    return *q;
+}
+template <bool NT>
+__device__ __forceinline__ void store16u(char* p, u32x4 v) {
+    DDP_GLOBAL u32x4_a2* q = (DDP_GLOBAL u32x4_a2*)(p);
+    if (NT) __builtin_nontemporal_store(v, q);
+    else *q = v;
+}
 
 // ---- element formats ------------------------------------------------------
 template <int DT> struct Fmt;
@@ -158,24 +174,6 @@ __device__ __forceinline__ int classify(int64_t e, int vec, int64_t numel) {
     return (e >= 0 && e + vec <= numel) ? V_FULL : V_EDGE;
 }
 
-// 16 bytes from an address that is only element-aligned.
-template <int ES>
-__device__ __forceinline__ u32x4 gather16(const char* p) {
-    u32x4 v;
-    if (ES == 4) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = gload<uint32_t>(p + 4 * i);
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t lo = gload<uint16_t>(p + 4 * i);
-            const uint32_t hi = gload<uint16_t>(p + 4 * i + 2);
-            v[i] = lo | (hi << 16);
-        }
-    }
-    return v;
-}
-
 // ---- K1 / K3: segment copies ---------------------------------------------
 template <int ES, bool NTS>
 __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __restrict__ dst,
@@ -194,7 +192,7 @@ __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __
         kind[k] = classify(e[k], VEC, numel);
         v[k] = zero16();
         if (kind[k] == V_FULL && !zero)
-            v[k] = cong ? load16<true>(src + e[k] * ES) : gather16<ES>(src + e[k] * ES);
+            v[k] = cong ? load16<true>(src + e[k] * ES) : load16u<true>(src + e[k] * ES);
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
@@ -414,7 +412,7 @@ __global__ __launch_bounds__(BLOCK) void flat_reduce_kernel(const char* __restri
 // and lanes are predicated.  The C pointers are fetched first (one scalar
 // load), then all C*U vector loads are issued, then the adds run in order.
 template <int DT, bool NT, int C, int U>
-__device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r, uint64_t used,
+__device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r, uint64_t used, bool aligned,
                                           const int64_t (&off)[U], const bool (&ok)[U],
                                           float (&acc)[U][Fmt<DT>::VEC]) {
     const char* base[C];
@@ -427,7 +425,9 @@ __device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r, 
     for (int i = 0; i < C; ++i)
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            x[i][u] = (ok[u] && ((used >> (r + i)) & 1u)) ? load16<NT>(base[i] + off[u]) : zero16();
+            x[i][u] = (ok[u] && ((used >> (r + i)) & 1u))
+                          ? (aligned ? load16<NT>(base[i] + off[u]) : load16u<NT>(base[i] + off[u]))
+                          : zero16();
 #pragma unroll
     for (int i = 0; i < C; ++i)
 #pragma unroll
@@ -440,7 +440,8 @@ __device__ __forceinline__ void chunk_seg(void* const* __restrict__ row, int r, 
 // binary32, unrounded, to a separate tensor per parameter (SegTables::out): two
 // 16-byte stores per 16-byte input vector, at twice the byte offset.
 template <int DT, bool NT>
-__device__ __forceinline__ void store_out32(char* out, int64_t in_byte_off, const float (&y)[Fmt<DT>::VEC]) {
+__device__ __forceinline__ void store_out32(char* out, int64_t in_byte_off, const float (&y)[Fmt<DT>::VEC],
+                                            bool aligned = true) {
     static_assert(Fmt<DT>::VEC == 8, "binary32 outputs are for the 16-bit formats");
     u32x4 lo, hi;
 #pragma unroll
@@ -448,8 +449,13 @@ __device__ __forceinline__ void store_out32(char* out, int64_t in_byte_off, cons
         lo[i] = __float_as_uint(y[i]);
         hi[i] = __float_as_uint(y[4 + i]);
     }
-    store16s<NT>(out + 2 * in_byte_off, lo);
-    store16s<NT>(out + 2 * in_byte_off + 16, hi);
+    if (aligned) {
+        store16s<NT>(out + 2 * in_byte_off, lo);
+        store16s<NT>(out + 2 * in_byte_off + 16, hi);
+    } else {
+        store16u<NT>(out + 2 * in_byte_off, lo);
+        store16u<NT>(out + 2 * in_byte_off + 16, hi);
+    }
 }
 
 template <int DT, bool OUT32 = false>
@@ -511,7 +517,8 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
     const int sh = si.lead_bytes() / ES;    // replica 0's tensor starts this many elements past a 16-byte boundary
     // every replica's tensor sits at the same offset modulo 16 (and, with binary32 outputs, the
     // output tensor sits where whole input vectors map to whole output vectors)
-    const bool fast = si.congruent() && (!OUT32 || si.out_congruent());
+    const bool src_aligned = si.congruent();
+    const bool fast = src_aligned && (!OUT32 || si.out_congruent());
     char* const outp = OUT32 ? static_cast<char*>(t.out[g]) : nullptr;
     const int64_t e_tile = ltile * (TILE_BYTES / ES) - sh;
 
@@ -555,45 +562,37 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
         for (int u = 0; u < U; ++u) {
             e[u] = e_tile + static_cast<int64_t>((step * U + u) * BLOCK + threadIdx.x) * VEC;
             kind[u] = classify(e[u], VEC, numel);
-            ok[u] = kind[u] == V_FULL && fast && !zero;
+            ok[u] = kind[u] == V_FULL && !zero;
             off[u] = e[u] * ES;
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[u][i] = -0.0f;
         }
-        if (!zero && fast) {
+        if (!zero) {
+            // vectors sit on replica 0's 16-byte grid; replicas that are shifted against it
+            // are read with element-aligned 16-byte loads
             int r = 0;
-            for (; r + 8 <= R; r += 8) chunk_seg<DT, NT, 8, U>(row, r, used, off, ok, acc);
-            if (r + 4 <= R) { chunk_seg<DT, NT, 4, U>(row, r, used, off, ok, acc); r += 4; }
-            if (r + 2 <= R) { chunk_seg<DT, NT, 2, U>(row, r, used, off, ok, acc); r += 2; }
-            if (r < R) { chunk_seg<DT, NT, 1, U>(row, r, used, off, ok, acc); }
+            for (; r + 8 <= R; r += 8) chunk_seg<DT, NT, 8, U>(row, r, used, src_aligned, off, ok, acc);
+            if (r + 4 <= R) { chunk_seg<DT, NT, 4, U>(row, r, used, src_aligned, off, ok, acc); r += 4; }
+            if (r + 2 <= R) { chunk_seg<DT, NT, 2, U>(row, r, used, src_aligned, off, ok, acc); r += 2; }
+            if (r < R) { chunk_seg<DT, NT, 1, U>(row, r, used, src_aligned, off, ok, acc); }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kind[u] == V_NONE) continue;
-            if (OUT32 && kind[u] == V_FULL && fast) {
+            if (kind[u] == V_FULL) {
                 float y[VEC];
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) y[i] = zero ? 0.0f : apply_scale(sc, acc[u][i]);
-                if constexpr (OUT32) store_out32<DT, NT>(outp, off[u], y);
-            } else if (!OUT32 && kind[u] == V_FULL && (fast || zero)) {
-                u32x4 out = zero16();
-                if (!zero) {
-                    float y[VEC];
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) y[i] = apply_scale(sc, acc[u][i]);
-                    out = Fmt<DT>::narrow(y);
+                if (OUT32) {
+                    if constexpr (OUT32) store_out32<DT, NT>(outp, off[u], y, si.out_congruent());
+                    continue;
                 }
-                // replica w's tensor is congruent with replica 0's when fast; for
-                // unused parameters only replica 0's alignment is known to be
-                // right, so the others go element by element below.
+                const u32x4 out = zero ? zero16() : Fmt<DT>::narrow(y);
                 store16s<NT>(static_cast<char*>(row[0]) + off[u], out);
                 for (int w = 1; w < nwrite; ++w) {
                     char* d = static_cast<char*>(t.grad[static_cast<int64_t>(g) * t.R + w]);
-                    if (fast) {
-                        store16s<NT>(d + off[u], out);
-                    } else {
-                        for (int i = 0; i < VEC; ++i) Fmt<DT>::store1(d + (e[u] + i) * ES, 0.0f);
-                    }
+                    if (src_aligned) store16s<NT>(d + off[u], out);
+                    else store16u<NT>(d + off[u], out);
                 }
             } else {
                 for (int i = 0; i < VEC; ++i) {
@@ -775,7 +774,7 @@ __device__ __forceinline__ void accumulate_tile(const char* __restrict__ src, ch
             b[u] = zero16();
             if (kind[u] == V_FULL) {
                 a[u] = load16<false>(dst + e[u] * ES);
-                b[u] = cong ? load16<true>(src + e[u] * ES) : gather16<ES>(src + e[u] * ES);
+                b[u] = cong ? load16<true>(src + e[u] * ES) : load16u<true>(src + e[u] * ES);
             }
         }
 #pragma unroll
