@@ -80,8 +80,6 @@ typedef struct ddp_ctx ddp_ctx;
                                      events on its stream; 2: one pair per iteration, from just
                                      before its first bucket launch to just after its last (kind
                                      DDP_K_ITERATION); 0: off.  Read with ddp_get_kernel_times */
-#define DDP_OPT_REDUCE_BLOCKS  4  /* any time: upper bound on thread blocks per reduce launch
-                                     (0 = one block per tile) */
 #define DDP_OPT_NONTEMPORAL    5  /* any time: 1 (default) = read-once inputs are loaded, and the
                                      averages stored, with the non-temporal hint; 0 = plain */
 #define DDP_OPT_PAIR_MIN_BYTES 7  /* any time: fused pipeline, launches of at least this many bytes
@@ -93,8 +91,6 @@ typedef struct ddp_ctx ddp_ctx;
                                      thread block that sleeps between clock polls; n > 0: n blocks
                                      that do arithmetic between polls, so that the delay loads the
                                      GPU the way backward compute does */
-#define DDP_OPT_COPY_NT_STORE  9  /* any time: staged pipeline, pack and unpack store with the
-                                     non-temporal hint (1) or plainly (0, default) */
 #define DDP_OPT_COALESCE      10  /* any time: value > 0 = buckets that one API call makes launchable
                                      (ddp_mark_ready_many, ddp_finalize_backward, ddp_synth_backward
                                      between two of its kernels) and that are consecutive and of one
@@ -140,10 +136,6 @@ typedef struct ddp_ctx ddp_ctx;
                                      bytes of bucket data (measured: it gains 1 to 2.5 points of
                                      HBM peak from 50 MiB up and loses 1.5 to 3 on launches of 25
                                      MiB and less).  Default 40 MiB */
-#define DDP_OPT_COPY_BLOCKS_PER_CU 15 /* any time: the same kind of cap for the pack and unpack kernels,
-                                     which keep only one or two loads per thread in flight and want
-                                     many blocks (measured: no gain from any cap, a quarter of the
-                                     rate lost at 2 or 3).  Default 0 = no cap */
 #define DDP_OPT_ACCUMULATE_BLOCKS_PER_CU 16 /* any time: likewise for the accumulate kernel (two loads
                                      and a store per vector; registers allow 8 blocks).  Default 5 */
 #define DDP_OPT_TAIL_ON_BACKWARD 17 /* any time between iterations: 1 (default) = the buckets launched by
@@ -173,8 +165,6 @@ typedef struct ddp_ctx ddp_ctx;
 #define DDP_OPT_GATE_WAIT_US  19  /* any time: upper bound, in microseconds, on a gate's wait (0 = look
                                      once).  Default 100000.  A backward pass that lags further behind
                                      the host only loses overlap for that iteration, never correctness */
-#define DDP_OPT_REDUCE_UNROLL  6  /* any time: 16-byte vectors per thread and replica in the reduce
-                                     kernels: 1, 2 (default) or 4 */
 
 /* DDP_PIPELINE_STAGED follows the paper's data flow literally: gradients are
  * copied into flat per-replica bucket buffers (Algorithm 1, autograd_hook),

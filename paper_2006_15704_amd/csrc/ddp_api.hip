@@ -47,10 +47,7 @@ struct ddp_ctx {
     int32_t pipeline = DDP_PIPELINE_STAGED;
     int32_t write_all = 0;
     int32_t timing = 0;
-    int32_t reduce_blocks = 0;
     int32_t nontemporal = 1;
-    int32_t unroll = 2;
-    int32_t copy_nt_store = 0;
     int64_t coalesce = -1;                        // > 0: consecutive buckets of one API call share a
                                                   // launch while it stays within this many bytes
     int64_t pair_min_bytes = int64_t(48) << 20;   // launches at least this large use paired tiles ...
@@ -62,7 +59,6 @@ struct ddp_ctx {
     int32_t blocks_per_cu = -1;                   // reduce kernels: resident blocks per compute unit (0 = no cap,
                                                   // -1 = chosen from R, see auto_blocks_per_cu)
     int64_t cap_min_bytes = int64_t(40) << 20;    // ... applied to launches of at least this many bytes
-    int32_t copy_blocks_per_cu = 0;               // pack / unpack kernels: the same kind of cap (0 = none)
     int32_t acc_blocks_per_cu = 5;                // accumulate kernel: likewise
     int64_t lds_per_cu = 160 * 1024;              // read from the device at creation
 
@@ -201,7 +197,6 @@ unsigned lds_for_blocks(const ddp_ctx* c, int32_t blocks) {
     if (blocks <= 0) return 0;
     return static_cast<unsigned>((c->lds_per_cu / blocks) & ~int64_t(1023));
 }
-unsigned copy_lds(const ddp_ctx* c) { return lds_for_blocks(c, c->copy_blocks_per_cu); }
 
 using ddp::make_scale;
 
@@ -415,11 +410,11 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
         const int64_t nvec = (c->bucket_slab_off[last] - c->bucket_slab_off[first]) / 16 + c->bucket_vecs[last];
         if ((rc = timed_begin(c, DDP_K_PACK, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_pack(c->tables, tile_base, ntiles, c->slabs, c->slab_stride, c->R,
-                                   d_flags, c->copy_nt_store != 0, copy_lds(c), st));
+                                   d_flags, st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_flat_reduce(bf.dtype, in0, c->slab_stride, out, nvec, c->R, sc,
-                                          c->reduce_blocks, c->unroll, c->nontemporal != 0,
+                                          c->nontemporal != 0,
                                           occupancy_lds(c, bytes), st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     } else {
@@ -432,7 +427,7 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_fused_reduce(bf.dtype, c->tables, tile_base, ntiles, c->R,
                                            c->write_all ? c->R : 1, d_flags, c->find_unused != 0, sc,
-                                           c->unroll, pair, c->nontemporal != 0, occupancy_lds(c, bytes),
+                                           pair, c->nontemporal != 0, occupancy_lds(c, bytes),
                                            gate, static_cast<uint32_t>(c->iteration + 1), st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     }
@@ -676,10 +671,6 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             if (value < -1 || value > 16) return fail(c, DDP_ERR_ARG, "blocks per compute unit outside [-1, 16]");
             c->blocks_per_cu = static_cast<int32_t>(value);
             return DDP_OK;
-        case DDP_OPT_COPY_BLOCKS_PER_CU:
-            if (value < 0 || value > 16) return fail(c, DDP_ERR_ARG, "blocks per compute unit outside [0, 16]");
-            c->copy_blocks_per_cu = static_cast<int32_t>(value);
-            return DDP_OK;
         case DDP_OPT_ACCUMULATE_BLOCKS_PER_CU:
             if (value < 0 || value > 16) return fail(c, DDP_ERR_ARG, "blocks per compute unit outside [0, 16]");
             c->acc_blocks_per_cu = static_cast<int32_t>(value);
@@ -719,20 +710,9 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             if (value < -1) return fail(c, DDP_ERR_ARG, "bad size");
             c->coalesce = value;
             return DDP_OK;
-        case DDP_OPT_COPY_NT_STORE:
-            c->copy_nt_store = value != 0;
-            return DDP_OK;
         case DDP_OPT_PAIR_MIN_BYTES:
             if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
             c->pair_min_bytes = value;
-            return DDP_OK;
-        case DDP_OPT_REDUCE_UNROLL:
-            if (value != 1 && value != 2 && value != 4) return fail(c, DDP_ERR_ARG, "unroll must be 1, 2 or 4");
-            c->unroll = static_cast<int32_t>(value);
-            return DDP_OK;
-        case DDP_OPT_REDUCE_BLOCKS:
-            if (value < 0 || value > (1 << 30)) return fail(c, DDP_ERR_ARG, "bad block bound");
-            c->reduce_blocks = static_cast<int32_t>(value);
             return DDP_OK;
         case DDP_OPT_NONTEMPORAL:
             c->nontemporal = value != 0;
@@ -1136,7 +1116,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             HIPCHK(c, ddp::launch_unpack(c->tables, 0, c->h_tile0[n],
                                          c->slabs + static_cast<int64_t>(c->R) * c->slab_stride,
                                          c->write_all ? c->R : 1, c->iter_zero ? c->d_global : nullptr,
-                                         c->find_unused != 0, c->copy_nt_store != 0, copy_lds(c), c->reduce));
+                                         c->find_unused != 0, c->reduce));
             if ((rc = timed_end(c, slot, c->reduce)) != DDP_OK) return rc;
             reduce_side_used = true;
         }

@@ -71,31 +71,29 @@ inline Scale make_scale(int R) {
 }
 
 // All segment launches cover the tiles [tile_base, tile_base + ntiles) of the
-// global tile numbering (tile0 / tile_seg).  `lds` in K1-K4: bytes of dynamic
-// LDS per block that the kernels do not use; they cap the number of blocks
-// resident on a compute unit (0 = no cap).
+// global tile numbering (tile0 / tile_seg).  `lds` in K2 and K4: bytes of
+// dynamic LDS per block that the kernels do not use; they cap the number of
+// blocks resident on a compute unit (0 = no cap).  The copy kernels K1 and K3
+// keep one or two loads per thread in flight and want every block they can get.
 
 // K1: gradients -> flat replica slabs for all `nrep` replicas.  local (may be
 // null = every replica used every parameter): participation flags
 // [segment][replica]; 0 = write zeros into that replica's slot and do not read
 // its tensor.
 hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
-                       int64_t slab_stride, int nrep, const uint8_t* local, bool nt_store,
-                       unsigned lds, hipStream_t s);
+                       int64_t slab_stride, int nrep, const uint8_t* local, hipStream_t s);
 
 // K3: averaged slab -> gradient tensors of replicas [0, nrep).  global_used (may
 // be null): per segment, 0 = no replica used the parameter; with keep_unused
 // such parameters are not written.
 hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
                          const char* out_slab, int nrep, const uint8_t* global_used, bool keep_unused,
-                         bool nt_store, unsigned lds, hipStream_t s);
+                         hipStream_t s);
 
 // K2 (staged): out[v] = scale(sum_r in_r[v]) over nvec 16-byte vectors;
-// in_r = in0 + r*stride.  unroll = vectors per thread (1, 2 or 4);
-// max_blocks > 0 bounds the grid (blocks then loop).
+// in_r = in0 + r*stride.
 hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* out, int64_t nvec,
-                              int R, Scale sc, int max_blocks, int unroll, bool nontemporal,
-                              unsigned lds, hipStream_t s);
+                              int R, Scale sc, bool nontemporal, unsigned lds, hipStream_t s);
 
 // K2 (fused): gather R replicas through the segment table, reduce, scatter to
 // the gradient tensors of replicas [0, nwrite).  local / keep_unused as above
@@ -108,7 +106,7 @@ struct GateRecord;   // below, with the flag-ordering kernels
 // launch; if gate->failed_tag == tag the launch does nothing.
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
-                               int unroll, bool pair, bool nontemporal, unsigned lds,
+                               bool pair, bool nontemporal, unsigned lds,
                                const GateRecord* gate, uint32_t tag, hipStream_t s);
 // (with t.out set -- 16-bit gradients, binary32 averages written to t.out -- nwrite must be 1
 // and pair is ignored)

@@ -175,7 +175,7 @@ __device__ __forceinline__ int classify(int64_t e, int vec, int64_t numel) {
 }
 
 // ---- K1 / K3: segment copies ---------------------------------------------
-template <int ES, bool NTS>
+template <int ES>
 __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __restrict__ dst,
                                           int64_t numel, int64_t ltile, bool zero) {
     constexpr int VEC = 16 / ES;
@@ -197,7 +197,7 @@ __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __
 #pragma unroll
     for (int k = 0; k < U; ++k) {
         if (kind[k] == V_FULL) {
-            store16s<NTS>(dst + e[k] * ES, v[k]);
+            store16(dst + e[k] * ES, v[k]);
         } else if (kind[k] == V_EDGE) {
             for (int i = 0; i < VEC; ++i) {
                 const int64_t idx = e[k] + i;
@@ -213,7 +213,7 @@ __device__ __forceinline__ void copy_tile(const char* __restrict__ src, char* __
 }
 
 // PACK: grad[r][g] -> slab_r + flat_byte[g];  UNPACK: out slab -> grad[r][g].
-template <bool PACK, bool NTS>
+template <bool PACK>
 __global__ __launch_bounds__(BLOCK) void seg_copy_kernel(SegTables t, int64_t tile_base,
                                                          char* slab0, int64_t slab_stride,
                                                          const uint8_t* __restrict__ flags,
@@ -240,8 +240,8 @@ __global__ __launch_bounds__(BLOCK) void seg_copy_kernel(SegTables t, int64_t ti
         src = slab0 + si.flat_byte;
         dst = grad;
     }
-    if (si.dtype() == 0) copy_tile<4, NTS>(src, dst, numel, ltile, zero);
-    else copy_tile<2, NTS>(src, dst, numel, ltile, zero);
+    if (si.dtype() == 0) copy_tile<4>(src, dst, numel, ltile, zero);
+    else copy_tile<2>(src, dst, numel, ltile, zero);
 }
 
 // ---- K2: reduce and average ------------------------------------------------
@@ -359,52 +359,50 @@ __device__ __forceinline__ void chunk_flat(const char* __restrict__ in0, int64_t
         for (int u = 0; u < U; ++u) add_into<DT>(acc[u], x[i][u]);
 }
 
-// One block iteration handles a row of BLOCK*U consecutive vectors; with the
-// default grid every block handles exactly one row, so blocks stream through
-// memory in launch order.
+// Every block handles one row of BLOCK*U consecutive vectors, so blocks stream
+// through memory in launch order (a bounded grid whose blocks loop over distant
+// rows measured slower).
 template <int DT, bool NT, int U>
 __global__ __launch_bounds__(BLOCK) void flat_reduce_kernel(const char* __restrict__ in0,
                                                             int64_t stride, char* __restrict__ out,
                                                             int64_t nvec, int R, Scale sc) {
     constexpr int VEC = Fmt<DT>::VEC;
-    const int64_t nrows = (nvec + BLOCK * U - 1) / (BLOCK * U);
-    for (int64_t row = blockIdx.x; row < nrows; row += gridDim.x) {
-        float acc[U][VEC];
-        if ((row + 1) * (BLOCK * U) <= nvec) {
-            const int64_t row_byte = row * (BLOCK * U * 16);
-            uint32_t lane_off[U];
+    const int64_t row = blockIdx.x;
+    float acc[U][VEC];
+    if ((row + 1) * (BLOCK * U) <= nvec) {
+        const int64_t row_byte = row * (BLOCK * U * 16);
+        uint32_t lane_off[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) lane_off[u] = (u * BLOCK + threadIdx.x) * 16u;
-            sum_interior<DT, NT, U>(
-                [&](int r) { return in0 + static_cast<int64_t>(r) * stride + row_byte; }, R, lane_off, acc);
+        for (int u = 0; u < U; ++u) lane_off[u] = (u * BLOCK + threadIdx.x) * 16u;
+        sum_interior<DT, NT, U>(
+            [&](int r) { return in0 + static_cast<int64_t>(r) * stride + row_byte; }, R, lane_off, acc);
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                store16s<NT>(out + row_byte + lane_off[u], scaled<DT>(sc, acc[u]));
-            continue;
-        }
-        int64_t off[U];
-        bool ok[U];
+        for (int u = 0; u < U; ++u)
+            store16s<NT>(out + row_byte + lane_off[u], scaled<DT>(sc, acc[u]));
+        return;
+    }
+    int64_t off[U];
+    bool ok[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t v = row * (BLOCK * U) + u * BLOCK + threadIdx.x;
-            ok[u] = v < nvec;
-            off[u] = v * 16;
+    for (int u = 0; u < U; ++u) {
+        const int64_t v = row * (BLOCK * U) + u * BLOCK + threadIdx.x;
+        ok[u] = v < nvec;
+        off[u] = v * 16;
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[u][i] = -0.0f;   // -0 + x == x for every x
-        }
-        int r = 0;
-        for (; r + 8 <= R; r += 8) chunk_flat<DT, NT, 8, U>(in0, stride, r, off, ok, acc);
-        if (r + 4 <= R) { chunk_flat<DT, NT, 4, U>(in0, stride, r, off, ok, acc); r += 4; }
-        if (r + 2 <= R) { chunk_flat<DT, NT, 2, U>(in0, stride, r, off, ok, acc); r += 2; }
-        if (r < R) { chunk_flat<DT, NT, 1, U>(in0, stride, r, off, ok, acc); }
+        for (int i = 0; i < VEC; ++i) acc[u][i] = -0.0f;   // -0 + x == x for every x
+    }
+    int r = 0;
+    for (; r + 8 <= R; r += 8) chunk_flat<DT, NT, 8, U>(in0, stride, r, off, ok, acc);
+    if (r + 4 <= R) { chunk_flat<DT, NT, 4, U>(in0, stride, r, off, ok, acc); r += 4; }
+    if (r + 2 <= R) { chunk_flat<DT, NT, 2, U>(in0, stride, r, off, ok, acc); r += 2; }
+    if (r < R) { chunk_flat<DT, NT, 1, U>(in0, stride, r, off, ok, acc); }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (!ok[u]) continue;
-            float y[VEC];
+    for (int u = 0; u < U; ++u) {
+        if (!ok[u]) continue;
+        float y[VEC];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) y[i] = apply_scale(sc, acc[u][i]);
-            store16s<NT>(out + off[u], Fmt<DT>::narrow(y));
-        }
+        for (int i = 0; i < VEC; ++i) y[i] = apply_scale(sc, acc[u][i]);
+        store16s<NT>(out + off[u], Fmt<DT>::narrow(y));
     }
 }
 
@@ -903,88 +901,68 @@ static hipError_t launch(void (*kernel)(KArgs...), dim3 grid, unsigned lds, hipS
 
 // ---- launch wrappers ---------------------------------------------------------
 hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
-                       int64_t slab_stride, int nrep, const uint8_t* local, bool nt_store,
-                       unsigned lds, hipStream_t s) {
+                       int64_t slab_stride, int nrep, const uint8_t* local, hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
-    if (nt_store) return launch(seg_copy_kernel<true, true>, grid, lds, s, t, tile_base, slab0, slab_stride, local, 0);
-    return launch(seg_copy_kernel<true, false>, grid, lds, s, t, tile_base, slab0, slab_stride, local, 0);
+    return launch(seg_copy_kernel<true>, grid, 0u, s, t, tile_base, slab0, slab_stride, local, 0);
 }
 
 hipError_t launch_unpack(const SegTables& t, int64_t tile_base, int64_t ntiles,
                          const char* out_slab, int nrep, const uint8_t* global_used, bool keep_unused,
-                         bool nt_store, unsigned lds, hipStream_t s) {
+                         hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
     dim3 grid(static_cast<unsigned>(ntiles), static_cast<unsigned>(nrep));
     const int keep = keep_unused ? 1 : 0;
-    if (nt_store) return launch(seg_copy_kernel<false, true>, grid, lds, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), global_used, keep);
-    return launch(seg_copy_kernel<false, false>, grid, lds, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), global_used, keep);
+    return launch(seg_copy_kernel<false>, grid, 0u, s, t, tile_base, const_cast<char*>(out_slab), int64_t(0), global_used, keep);
 }
 
-template <int DT, int U>
-static hipError_t flat_reduce_dispatch(bool nt, int64_t nrows, int max_blocks, unsigned lds, hipStream_t s,
-                                 const char* in0, int64_t stride, char* out, int64_t nvec, int R,
-                                 Scale sc) {
-    int64_t blocks = nrows;
-    if (max_blocks > 0 && blocks > max_blocks) blocks = max_blocks;
-    dim3 grid(static_cast<unsigned>(blocks));
-    if (nt) return launch(flat_reduce_kernel<DT, true, U>, grid, lds, s, in0, stride, out, nvec, R, sc);
-    return launch(flat_reduce_kernel<DT, false, U>, grid, lds, s, in0, stride, out, nvec, R, sc);
-}
+// Vectors per thread and replica in the reduce kernels: a tile's worth (two), which measured
+// best against one and four on both model-shaped lists.
+constexpr int RU = TILE_VECS / BLOCK;
 
 template <int DT>
-static hipError_t flat_reduce_unroll(int unroll, bool nt, int max_blocks, unsigned lds, hipStream_t s,
-                                     const char* in0, int64_t stride, char* out, int64_t nvec, int R, Scale sc) {
-    if (unroll >= 4) return flat_reduce_dispatch<DT, 4>(nt, (nvec + BLOCK * 4 - 1) / (BLOCK * 4), max_blocks, lds, s, in0, stride, out, nvec, R, sc);
-    if (unroll >= 2) return flat_reduce_dispatch<DT, 2>(nt, (nvec + BLOCK * 2 - 1) / (BLOCK * 2), max_blocks, lds, s, in0, stride, out, nvec, R, sc);
-    return flat_reduce_dispatch<DT, 1>(nt, (nvec + BLOCK - 1) / BLOCK, max_blocks, lds, s, in0, stride, out, nvec, R, sc);
+static hipError_t flat_reduce_dispatch(bool nt, unsigned lds, hipStream_t s, const char* in0, int64_t stride,
+                                       char* out, int64_t nvec, int R, Scale sc) {
+    const int64_t nrows = (nvec + BLOCK * RU - 1) / (BLOCK * RU);
+    dim3 grid(static_cast<unsigned>(nrows));
+    if (nt) return launch(flat_reduce_kernel<DT, true, RU>, grid, lds, s, in0, stride, out, nvec, R, sc);
+    return launch(flat_reduce_kernel<DT, false, RU>, grid, lds, s, in0, stride, out, nvec, R, sc);
 }
 
 hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* out, int64_t nvec,
-                              int R, Scale sc, int max_blocks, int unroll, bool nontemporal,
-                              unsigned lds, hipStream_t s) {
+                              int R, Scale sc, bool nontemporal, unsigned lds, hipStream_t s) {
     if (nvec <= 0) return hipSuccess;
     switch (dtype) {
-        case 0: return flat_reduce_unroll<0>(unroll, nontemporal, max_blocks, lds, s, in0, stride, out, nvec, R, sc);
-        case 1: return flat_reduce_unroll<1>(unroll, nontemporal, max_blocks, lds, s, in0, stride, out, nvec, R, sc);
-        case 2: return flat_reduce_unroll<2>(unroll, nontemporal, max_blocks, lds, s, in0, stride, out, nvec, R, sc);
+        case 0: return flat_reduce_dispatch<0>(nontemporal, lds, s, in0, stride, out, nvec, R, sc);
+        case 1: return flat_reduce_dispatch<1>(nontemporal, lds, s, in0, stride, out, nvec, R, sc);
+        case 2: return flat_reduce_dispatch<2>(nontemporal, lds, s, in0, stride, out, nvec, R, sc);
         default: return hipErrorInvalidValue;
     }
 }
 
-template <int DT, int U>
-static hipError_t fused_dispatch(bool nt, dim3 grid, unsigned lds, hipStream_t s, const SegTables& t,
-                                 int64_t tile_base, int R, int nwrite, const uint8_t* local, int keep, Scale sc,
-                                 const GateRecord* gate, uint32_t tag) {
-    if (nt) return launch(fused_reduce_kernel<DT, true, U>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-    return launch(fused_reduce_kernel<DT, false, U>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-}
-
 template <int DT>
-static hipError_t fused_unroll(int unroll, bool pair, bool nt, int64_t ntiles, unsigned lds, hipStream_t s,
-                               const SegTables& t, int64_t tile_base, int R, int nwrite,
-                               const uint8_t* local, int keep, Scale sc, const GateRecord* gate, uint32_t tag) {
-    constexpr int UMAX = TILE_VECS / BLOCK;      // a tile holds at most this many vectors per thread
+static hipError_t fused_dispatch(bool pair, bool nt, int64_t ntiles, unsigned lds, hipStream_t s,
+                                 const SegTables& t, int64_t tile_base, int R, int nwrite,
+                                 const uint8_t* local, int keep, Scale sc, const GateRecord* gate, uint32_t tag) {
     if (pair) {
         dim3 grid(static_cast<unsigned>((ntiles + 1) / 2));
-        if (nt) return launch(fused_reduce_pair_kernel<DT, true, UMAX>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc, gate, tag);
-        return launch(fused_reduce_pair_kernel<DT, false, UMAX>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc, gate, tag);
+        if (nt) return launch(fused_reduce_pair_kernel<DT, true, RU>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc, gate, tag);
+        return launch(fused_reduce_pair_kernel<DT, false, RU>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc, gate, tag);
     }
     dim3 grid(static_cast<unsigned>(ntiles));
-    if (unroll >= 4 && UMAX >= 4) return fused_dispatch<DT, (UMAX >= 4 ? 4 : 1)>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-    if (unroll >= 2 && UMAX >= 2) return fused_dispatch<DT, (UMAX >= 2 ? 2 : 1)>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-    return fused_dispatch<DT, 1>(nt, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+    if (nt) return launch(fused_reduce_kernel<DT, true, RU>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+    return launch(fused_reduce_kernel<DT, false, RU>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
 }
 
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
-                               int unroll, bool pair, bool nontemporal, unsigned lds,
+                               bool pair, bool nontemporal, unsigned lds,
                                const GateRecord* gate, uint32_t tag, hipStream_t s) {
     if (ntiles <= 0) return hipSuccess;
     const int keep = keep_unused ? 1 : 0;
     if (t.out != nullptr) {
         // 16-bit gradients, binary32 averages to separate tensors
-        constexpr int U = TILE_VECS / BLOCK >= 2 ? 2 : 1;
+        constexpr int U = RU;
         if (nwrite != 1 || (dtype != 1 && dtype != 2)) return hipErrorInvalidValue;
         const dim3 grid(static_cast<unsigned>(ntiles));
         if (dtype == 1)
@@ -994,9 +972,9 @@ hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base,
                            : launch(fused_reduce_kernel<2, false, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
     }
     switch (dtype) {
-        case 0: return fused_unroll<0>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-        case 1: return fused_unroll<1>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-        case 2: return fused_unroll<2>(unroll, pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        case 0: return fused_dispatch<0>(pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        case 1: return fused_dispatch<1>(pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        case 2: return fused_dispatch<2>(pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1017,7 +995,7 @@ hipError_t launch_repair(int dtype, const SegTables& t, OrderState* st, const Ga
                          int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
                          int blocks, bool nt, hipStream_t s) {
     if (blocks <= 0 || nb <= 0) return hipSuccess;
-    constexpr int U = TILE_VECS / BLOCK >= 2 ? 2 : 1;
+    constexpr int U = RU;
     const dim3 grid(static_cast<unsigned>(blocks));
     const int keep = keep_unused ? 1 : 0;
     if (t.out != nullptr) {

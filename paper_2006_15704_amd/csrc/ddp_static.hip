@@ -179,12 +179,12 @@ extern "C" int32_t ddp_sync_static(int32_t R, int32_t device, void* stream, int3
         }
     }
     const int64_t ntiles = ht.tile0[n];
-    HIPCHK0(ddp::launch_pack(t, 0, ntiles, slabs, ht.slab_stride, R, nullptr, false, 0, s));
+    HIPCHK0(ddp::launch_pack(t, 0, ntiles, slabs, ht.slab_stride, R, nullptr, s));
     const ddp::Scale sc = ddp::make_scale(R);
     char* out = slabs + static_cast<int64_t>(R) * ht.slab_stride;
     for (int32_t b = 0; b < nb; ++b)      // in bucket order (Section 3.2.3)
         HIPCHK0(ddp::launch_flat_reduce(plan.buckets[b].dtype, slabs + ht.bucket_slab_off[b], ht.slab_stride,
-                                        out + ht.bucket_slab_off[b], ht.bucket_vecs[b], R, sc, 0, 2, true, 0, s));
-    HIPCHK0(ddp::launch_unpack(t, 0, ntiles, out, 1, nullptr, false, false, 0, s));
+                                        out + ht.bucket_slab_off[b], ht.bucket_vecs[b], R, sc, true, 0, s));
+    HIPCHK0(ddp::launch_unpack(t, 0, ntiles, out, 1, nullptr, false, s));
     return nb;
 }

@@ -148,10 +148,10 @@ def test_mixed_element_types(pipeline):
 
 
 @pytest.mark.parametrize("dtype", [FP32, FP16, BF16])
-@pytest.mark.parametrize("unroll", [1, 2, 4])
-def test_kernel_variants_give_the_same_bits(dtype, unroll):
-    """Every unroll setting, with and without two-tile blocks and with plain
-    loads, on a list that mixes large, tiny, unaligned and unmarked tensors."""
+def test_kernel_variants_give_the_same_bits(dtype):
+    """With and without two-tile blocks, with hinted and plain loads, under every
+    cap on resident blocks, on a list that mixes large, tiny, unaligned and
+    unmarked tensors."""
     d, _ = lib()
     es = 4 if dtype == FP32 else 2
     numel = [70000, 3, 2048, 4096, 12289, 1, 40000, 64, 9999]
@@ -161,8 +161,7 @@ def test_kernel_variants_give_the_same_bits(dtype, unroll):
     order = [8, 7, 6, 4, 3, 2, 0]          # parameters 5 and 1 never marked
     for pair_min in (0, 1 << 40):
         for nt in (1, 0):
-            opts = [(d.DDP_OPT_REDUCE_UNROLL, unroll), (d.DDP_OPT_PAIR_MIN_BYTES, pair_min),
-                    (d.DDP_OPT_NONTEMPORAL, nt), (d.DDP_OPT_COPY_NT_STORE, nt),
+            opts = [(d.DDP_OPT_PAIR_MIN_BYTES, pair_min), (d.DDP_OPT_NONTEMPORAL, nt),
                     (d.DDP_OPT_COALESCE, (1 << 62) if pair_min == 0 else 0),
                     # occupancy cap of the reduce kernels: none, one block per unit (the largest
                     # LDS allocation), three

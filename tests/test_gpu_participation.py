@@ -131,9 +131,9 @@ def test_partial_participation_with_misaligned_tensors(pipeline):
 def test_participation_with_coalesced_launches_and_kernel_variants(pipeline):
     d, _ = lib()
     numel, dtypes, reps, marks, _, _ = random_case(30, 40, 8, FP32, 6000)
-    for options in ([(d.DDP_OPT_COALESCE, 1 << 62)], [(d.DDP_OPT_REDUCE_UNROLL, 1)],
-                    [(d.DDP_OPT_REDUCE_UNROLL, 4), (d.DDP_OPT_PAIR_MIN_BYTES, 0)],
-                    [(d.DDP_OPT_NONTEMPORAL, 0), (d.DDP_OPT_COPY_NT_STORE, 1)]):
+    for options in ([(d.DDP_OPT_COALESCE, 1 << 62)], [(d.DDP_OPT_COALESCE, 0), (d.DDP_OPT_REDUCE_STREAMS, 1)],
+                    [(d.DDP_OPT_COALESCE, 1 << 62), (d.DDP_OPT_PAIR_MIN_BYTES, 0)],
+                    [(d.DDP_OPT_NONTEMPORAL, 0)]):
         check_against_oracle(numel, dtypes, reps, marks, 20000, pipeline, False, True, options=options)
 
 
