@@ -17,9 +17,11 @@ Prints ONE JSON line.
   roofline  the reduce kernel (fused_reduce_kernel, the dominant one) against
             the 8 TB/s HBM peak: algorithmic bytes per launch = (R + 1) * bytes
             of the bucket(s) a launch covers; average launch duration = the time
-            between two HIP events around the timed region (on the backward
+            between two HIP events around the timed steps (on the backward
             stream, which every launch runs on or is joined to by finalize)
-            divided by the number of launches.
+            divided by the number of launches -- the launches of a step run on
+            two reduction streams and overlap at their ends, so this is the
+            duration that adds up to the whole, gates, joins and gaps included.
   bert_large    the same measurement on the BERT-large-shaped list (the metric
             is quoted on both shapes).
   marks_in_one_call   both shapes again with all marks of a step in ONE
@@ -58,7 +60,7 @@ WORKLOADS = {
     "bert_large_r32": ("bert_large", 5, 32, 1e-3, 0, 25 * MIB),        # configuration 5's reduction (R = 32)
     "bert_large_bf16": ("bert_large", 3, 8, 1e-3, 2, 25 * MIB),        # 16-bit transport of BERT-large's gradients
 }
-ALL_LEGS = ["headline", "bert_large", "one_call", "single_set", "per_bucket", "overlap", "r32", "transport",
+ALL_LEGS = ["headline", "bert_large", "one_call", "hold", "single_set", "per_bucket", "overlap", "r32", "transport",
             "staged", "accumulate", "cpu"]
 DT_NAME = {0: "f32", 1: "f16", 2: "bf16"}
 
@@ -190,11 +192,24 @@ class Rig:
             self.step(k, per_call)
         self.sync()
         it_ms = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_ITERATION)[0] for s in self.sessions])
+        # the reduce kernel by itself: one event pair per launch, on the stream the launch runs on
+        for s in self.sessions:
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 1)
+        for k in range(spread_iters):
+            self.step(k, per_call)
+        self.sync()
+        k_ms = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_REDUCE)[0] for s in self.sessions])
         for s in self.sessions:
             lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 0)
         alg = self.alg_bytes
         ms_per_step = (t1 - t0) * 1e3 / steps
         launches = launches_per_step * steps
+        # The launches of an iteration run on two reduction streams and overlap each other at
+        # their ends, so "the duration of a launch" that sums up to the time of the whole is
+        # the time of the timed region divided by its launches; what one launch takes between
+        # its own two events (it shares the memory system with its neighbour meanwhile) is
+        # reported next to it.
+        avg_launch_ms = region_ms / max(launches, 1)
         achieved = alg * steps / region_ms / 1e6
         return {
             "ms_per_step": round(ms_per_step, 4),
@@ -209,11 +224,16 @@ class Rig:
                 "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "avg_launch_ms": round(region_ms / max(launches, 1), 5),
+                "avg_launch_ms": round(avg_launch_ms, 5),
                 "launches": launches,
                 "algorithmic_bytes_per_launch": round(alg / max(launches_per_step, 1)),
-                "timing": "one HIP event pair around the timed region on the backward stream; "
-                          "launches on the two reduction streams may overlap, the average is region / launches",
+                "timing": "one HIP event pair around the timed steps on the backward stream (every launch runs on it "
+                          "or is joined to it by finalize), divided by the launches: kernels, gates, joins and gaps",
+                "per_launch_event_pairs": {
+                    "what": f"one HIP event pair per launch on the stream it runs on (third pass of {spread_iters} steps); "
+                            "launches on the two reduction streams overlap, each then takes longer than its share",
+                    "launch_ms": spread(k_ms),
+                    "mean_ms": round(float(k_ms.mean()), 5)},
                 "iteration_ms": spread(it_ms),
                 "iteration_what": "first bucket launch to the end of the iteration, one HIP event pair per "
                                   "iteration (second pass; the pairs cost a few us each)",
@@ -221,30 +241,36 @@ class Rig:
         }
 
     def per_bucket(self, steps):
-        """One reduction stream, one HIP event pair per launch: the rate of every bucket."""
+        """The rate of every bucket's launch by itself: one reduction stream, one launch per
+        bucket, all marks of a step in one call (so that the launches queue up behind each other
+        and no host latency sits between a launch's two events), one HIP event pair per launch."""
         lib = self.lib
         for s in self.sessions:
             lib.ddp_set_option(s.ctx, lib.DDP_OPT_REDUCE_STREAMS, 1)
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_COALESCE, 0)
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TAIL_ON_BACKWARD, 0)
             lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 1)
         for k in range(steps):
-            self.step(k, True)
+            self.step(k, False)
         self.sync()
         ms = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_REDUCE)[0] for s in self.sessions])
         ids = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_REDUCE)[1] for s in self.sessions])
         for s in self.sessions:
             lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 0)
             lib.ddp_set_option(s.ctx, lib.DDP_OPT_REDUCE_STREAMS, -1)
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_COALESCE, -1)
+            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TAIL_ON_BACKWARD, 1)
         out = {}
         for b in range(self.n_buckets):
             sel = ms[ids == b]
             if len(sel):
                 out[str(b)] = round((self.R + 1) * self.bucket_elems[b] * self.es / float(np.median(sel)) / 1e6, 1)
-        total = (self.R + 1) * self.B * steps / float(ms.sum()) / 1e6
+        total = self.alg_bytes * steps / float(ms.sum()) / 1e6
         return {"reduce_gbps_per_bucket": out, "reduce_gbps": round(total, 1),
                 "frac_of_hbm_peak": round(total / HBM_PEAK_GBPS, 4),
                 "bucket_mib": [round(e * self.es / MIB, 2) for e in self.bucket_elems],
-                "note": "one reduction stream, median over steps of one HIP event pair per launch "
-                        "(the pair adds about 3 us to each launch)"}
+                "note": "one reduction stream, one launch per bucket, launches queued back to back; median over "
+                        "steps of one HIP event pair per launch (the pair adds about 3 us to each launch)"}
 
 
 def shape_leg(lib, harness, torch, workload, sets, steps, warmup, legs, traffic_mode):
@@ -264,6 +290,15 @@ def shape_leg(lib, harness, torch, workload, sets, steps, warmup, legs, traffic_
             one = rig.measure(steps, warmup, per_call=False)
             one["what"] = "all marks of a step in one ddp_mark_ready_many call: consecutive buckets share launches"
             res["marks_in_one_call"] = one
+        if "hold" in legs:
+            for s in rig.sessions:
+                lib.ddp_set_option(s.ctx, lib.DDP_OPT_LAUNCH_HOLD, 16)
+            held = rig.measure(steps, warmup, per_call=True)
+            for s in rig.sessions:
+                lib.ddp_set_option(s.ctx, lib.DDP_OPT_LAUNCH_HOLD, 0)
+            held["what"] = ("one ddp_mark_ready call per parameter with DDP_OPT_LAUNCH_HOLD = 16: a launchable bucket waits "
+                            "for up to 16 further marks so that its successors can share its launch")
+            res["marks_one_by_one_hold_16"] = held
         if "per_bucket" in legs and rig.n_buckets <= 64:
             res["one_launch_per_bucket"] = rig.per_bucket(max(5, steps // 2))
     finally:
@@ -326,10 +361,17 @@ def overlap_leg(lib, harness, torch, reps=10, delay_us=10):
             for _ in range(3):
                 sync_alone()
             t_sync, t_bwd, t_tot = timed(sync_alone), timed(backward_alone), timed(backward_and_sync)
-            rows.append({"cap_mib": cap_mib, "buckets": s.n_buckets, "sync_alone_ms": round(t_sync, 4),
-                         "backward_alone_ms": round(t_bwd, 4), "exposed_ms": round(t_tot - t_bwd, 4),
-                         "overlap": round(1.0 - (t_tot - t_bwd) / t_sync, 3),
-                         "ordered_by": "flags" if lib.ddp_get_option(ctx, lib.DDP_OPT_FLAG_ORDER) else "events"})
+            row = {"cap_mib": cap_mib, "buckets": s.n_buckets, "sync_alone_ms": round(t_sync, 4),
+                   "backward_alone_ms": round(t_bwd, 4), "exposed_ms": round(t_tot - t_bwd, 4),
+                   "overlap": round(1.0 - (t_tot - t_bwd) / t_sync, 3),
+                   "ordered_by": "flags" if lib.ddp_get_option(ctx, lib.DDP_OPT_FLAG_ORDER) else "events"}
+            if s.n_buckets > 4:
+                # many small buckets: the same with a launch hold of 8 marks and launches shared up to the default limit
+                lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE, -1)
+                lib.ddp_set_option(ctx, lib.DDP_OPT_LAUNCH_HOLD, 8)
+                t_hold = timed(backward_and_sync)
+                row["exposed_ms_hold_8"] = round(t_hold - t_bwd, 4)
+            rows.append(row)
     return {"workload": f"resnet50 shape, fp16, R={R}, {n} parameters, {delay_us} us of synthetic backward per parameter",
             "algorithmic_bytes": (R + 1) * B, "reps": reps,
             "what": "GPU time between two events on the backward stream, median; exposed = t(backward + sync) - "
@@ -508,6 +550,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--legs", default=",".join(ALL_LEGS),
                     help="comma list of " + ", ".join(ALL_LEGS) + " (headline is always run)")
+    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "bert_large"],
+                    help="the workload of the headline measurement (the default run reports bert_large as a "
+                         "sub-object; this switch is for profiling one shape alone)")
     ap.add_argument("--sets", type=int, default=4,
                     help="independent sets of replica gradients taken in turn by consecutive steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -540,8 +585,9 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    head = shape_leg(lib, harness, torch, "resnet50", args.sets, args.steps, args.warmup, legs, "per_bucket")
-    _, _, R, _, dtype, _ = WORKLOADS["resnet50"]
+    sets = args.sets if args.workload == "resnet50" else min(args.sets, 2)
+    head = shape_leg(lib, harness, torch, args.workload, sets, args.steps, args.warmup, legs, "per_call")
+    _, _, R, _, dtype, _ = WORKLOADS[args.workload]
     out = {
         "metric": "bucketed grad-sync throughput ((R+W)*B per synchronization)",
         "value": head["value_gbps"],
@@ -561,13 +607,13 @@ def main() -> int:
         "launches_per_step": head["launches_per_step"],
         "roofline": head["roofline"],
     }
-    for key in ("marks_in_one_call", "one_launch_per_bucket", "single_replica_set"):
+    for key in ("marks_in_one_call", "marks_one_by_one_hold_16", "one_launch_per_bucket", "single_replica_set"):
         if key in head:
             out[key] = head[key]
-    if "bert_large" in legs:
+    if "bert_large" in legs and args.workload != "bert_large":
         # 12 GB per step already: two sets are far beyond any cache
         bert = shape_leg(lib, harness, torch, "bert_large", 2, max(10, args.steps // 2), 2,
-                         legs - {"single_set"}, "per_bucket")
+                         legs - {"single_set"}, "per_call")
         bert["value"] = bert.pop("value_gbps")
         bert["unit"] = "GB/s"
         out["bert_large"] = bert

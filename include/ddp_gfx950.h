@@ -82,11 +82,6 @@ typedef struct ddp_ctx ddp_ctx;
                                      DDP_K_ITERATION); 0: off.  Read with ddp_get_kernel_times */
 #define DDP_OPT_NONTEMPORAL    5  /* any time: 1 (default) = read-once inputs are loaded, and the
                                      averages stored, with the non-temporal hint; 0 = plain */
-#define DDP_OPT_PAIR_MIN_BYTES 7  /* any time: fused pipeline, launches of at least this many bytes
-                                     whose tensors average at least 256 tiles (2 MiB) are reduced
-                                     with two tiles per thread block (more loads in flight per
-                                     thread; pays off on long launches of large tensors).  0 = every
-                                     launch, whatever its tensors.  Default 48 MiB */
 #define DDP_OPT_EMIT_BUSY_BLOCKS 8 /* any time: ddp_synth_backward's delay kernel.  0 (default): one
                                      thread block that sleeps between clock polls; n > 0: n blocks
                                      that do arithmetic between polls, so that the delay loads the
@@ -130,7 +125,7 @@ typedef struct ddp_ctx ddp_ctx;
                                      16-byte loads per thread in flight, so two or three blocks per
                                      unit fill the memory system; more only interleave more request
                                      streams at the DRAM channels and throughput drops.  0 = no cap
-                                     (registers decide: 5, or 3 with paired tiles).  Default -1 =
+                                     (registers decide: 5).  Default -1 =
                                      chosen from R: no cap up to R = 4 (few loads per block), else 2 */
 #define DDP_OPT_REDUCE_CAP_MIN_BYTES 14 /* any time: the cap applies to launches of at least this many
                                      bytes of bucket data (measured: it gains 1 to 2.5 points of
@@ -147,6 +142,18 @@ typedef struct ddp_ctx ddp_ctx;
                                      hand-over takes about 0.2 ms on this system when the waiting
                                      queue was armed long before the event fires.  0 = every bucket
                                      goes to a reduction stream */
+#define DDP_OPT_LAUNCH_HOLD   21  /* between iterations: 0 (default) = a bucket is launched by the ready
+                                     mark that completes it, as in Algorithm 1.  n > 0 = it is kept back
+                                     until n further ready marks have arrived, the iteration's last
+                                     bucket is launchable, the held buckets fill a launch
+                                     (DDP_OPT_COALESCE) or ddp_finalize_backward / the end of a
+                                     ddp_mark_ready_many call comes, whichever is first; every bucket
+                                     that becomes launchable meanwhile joins it and restarts the count.
+                                     Consecutive buckets then share launches although their marks
+                                     arrive one call at a time: fewer launches, gates and announcements
+                                     (what costs with many small buckets), at the price of starting
+                                     each reduction up to n marks later.  Order, launch log and results
+                                     are unchanged */
 #define DDP_OPT_FLAG_ORDER    18  /* between iterations: how a bucket launch on a reduction stream is ordered
                                      after the work on backward_stream that produces its gradients
                                      (fused pipeline).  -1 (default): through device flags where the
@@ -201,7 +208,7 @@ const char* ddp_last_error(const ddp_ctx* ctx);
 int32_t ddp_set_option(ddp_ctx* ctx, int32_t option, int64_t value);
 
 /* Reads back what is in effect for DDP_OPT_PIPELINE, _WRITE_ALL, _TIMING,
- * _FIND_UNUSED, _REDUCE_STREAMS, _TAIL_ON_BACKWARD, _GATE_WAIT_US, _COALESCE (the
+ * _FIND_UNUSED, _REDUCE_STREAMS, _TAIL_ON_BACKWARD, _GATE_WAIT_US, _LAUNCH_HOLD, _COALESCE (the
  * byte limit in effect, also when it was chosen from R) and _FLAG_ORDER (1 if
  * the launches of the next iteration would be ordered through device flags: the
  * option allows it, the pipeline is the fused one, the buckets are built and

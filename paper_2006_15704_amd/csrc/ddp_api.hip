@@ -50,8 +50,6 @@ struct ddp_ctx {
     int32_t nontemporal = 1;
     int64_t coalesce = -1;                        // > 0: consecutive buckets of one API call share a
                                                   // launch while it stays within this many bytes
-    int64_t pair_min_bytes = int64_t(48) << 20;   // launches at least this large use paired tiles ...
-    static constexpr int64_t kPairMinTilesPerSegment = 256;   // ... if their tensors are large on average
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
     int32_t n_streams = -1;                       // reduction streams taken in turn by the launches; -1 = two
                                                   // for launches below cap_min_bytes, one for larger ones
@@ -121,6 +119,9 @@ struct ddp_ctx {
     bool tail_used = false;                       // some launch of the running iteration went to the backward stream
     bool backward_idle_in_call = false;           // backward stream was found drained in this API call
     bool ordered_in_call = false;   // backward stream position of this API call already examined
+    int32_t hold_marks = 0;         // DDP_OPT_LAUNCH_HOLD: a launchable bucket waits for up to this many
+                                    // further ready marks for its successors to share its launch
+    int32_t hold_until = 0;         // ready-mark count at which the held buckets go out at the latest
     std::vector<int32_t> deferred;  // buckets made launchable by the running API call, not yet enqueued
 
     // Stream ordering through device flags (DDP_OPT_FLAG_ORDER): the backward stream announces a
@@ -135,7 +136,7 @@ struct ddp_ctx {
     // Several iterations may be enqueued before the first one's repair launch has run, and a
     // gate of a later iteration that gives up early must not overwrite a record that an
     // earlier iteration's repair launch has yet to read.
-    static constexpr int64_t kGateRows = 8;
+    static constexpr int64_t kGateRows = 64;
     ddp::GateRecord* d_gate = nullptr;            // [kGateRows][buckets], allocated with the buckets
     int64_t safe_iteration = 0;                   // everything enqueued before this iteration is known to be done
     uint64_t seq_issued = 0;                      // sequence numbers announced so far
@@ -329,9 +330,13 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
             hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
             const bool capturing = hipStreamIsCapturing(c->backward, &cap) == hipSuccess &&
                                    cap != hipStreamCaptureStatusNone;
-            const hipError_t q = capturing ? hipErrorNotReady : hipStreamQuery(c->backward);
+            const bool by_flag = !capturing && flags_usable(c);
+            // With flags the announcement is enqueued without first asking whether the backward
+            // stream has drained: the question (a stream query takes as long on the host as
+            // two launches) would only save the two small kernels when it has.
+            const hipError_t q = (capturing || by_flag) ? hipErrorNotReady : hipStreamQuery(c->backward);
             if (q == hipErrorNotReady) {
-                if (!capturing && flags_usable(c)) {
+                if (by_flag) {
                     // a one-block kernel instead of an event record (which stalls the stream
                     // for about 12 us here)
                     c->call_seq = ++c->seq_issued;
@@ -354,7 +359,8 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
             // is skipped and redone by the repair launch of the finalizing step
             if (c->gates_in_iter == 0 && c->iteration - c->safe_iteration >= ddp_ctx::kGateRows - 1) {
                 // this iteration's row of gate records was last used kGateRows iterations ago:
-                // that iteration's repair launch must have read it
+                // that iteration's repair launch must have read it (a host that enqueues that
+                // many iterations without ever synchronizing waits here once per cycle)
                 HIPCHK(c, hipStreamSynchronize(c->backward));
                 c->safe_iteration = c->iteration;
             }
@@ -418,16 +424,10 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
                                           occupancy_lds(c, bytes), st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     } else {
-        // Paired tiles keep more loads in flight per thread, which pays on long launches made of
-        // large tensors (most tiles interior); with many small tensors the pairs fall back to two
-        // tiles one after the other and only lengthen the blocks.
-        const bool pair = c->out_ptrs.empty() && bytes >= c->pair_min_bytes &&
-                          (c->pair_min_bytes == 0 ||      // 0 = always (lets tests reach every path of the kernel)
-                           ntiles >= ddp_ctx::kPairMinTilesPerSegment * static_cast<int64_t>(seg_end - seg_begin));
         if ((rc = timed_begin(c, DDP_K_REDUCE, id, st, &slot)) != DDP_OK) return rc;
         HIPCHK(c, ddp::launch_fused_reduce(bf.dtype, c->tables, tile_base, ntiles, c->R,
                                            c->write_all ? c->R : 1, d_flags, c->find_unused != 0, sc,
-                                           pair, c->nontemporal != 0, occupancy_lds(c, bytes),
+                                           c->nontemporal != 0, occupancy_lds(c, bytes),
                                            gate, static_cast<uint32_t>(c->iteration + 1), st));
         if ((rc = timed_end(c, slot, st)) != DDP_OK) return rc;
     }
@@ -696,6 +696,12 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             }
             c->n_streams = static_cast<int32_t>(value);
             return DDP_OK;
+        case DDP_OPT_LAUNCH_HOLD:
+            if (value < 0 || value > 1000000) return fail(c, DDP_ERR_ARG, "launch hold outside [0, 1000000] marks");
+            if (c->tracker.marks() != 0 || !c->log_running.empty())
+                return fail(c, DDP_ERR_STATE, "the launch hold can only change between iterations");
+            c->hold_marks = static_cast<int32_t>(value);
+            return DDP_OK;
         case DDP_OPT_FLAG_ORDER:
             if (value != -1 && value != 0) return fail(c, DDP_ERR_ARG, "flag ordering must be -1 (where possible) or 0 (never)");
             if (c->tracker.marks() != 0 || !c->log_running.empty())
@@ -709,10 +715,6 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
         case DDP_OPT_COALESCE:
             if (value < -1) return fail(c, DDP_ERR_ARG, "bad size");
             c->coalesce = value;
-            return DDP_OK;
-        case DDP_OPT_PAIR_MIN_BYTES:
-            if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
-            c->pair_min_bytes = value;
             return DDP_OK;
         case DDP_OPT_NONTEMPORAL:
             c->nontemporal = value != 0;
@@ -744,6 +746,7 @@ int32_t ddp_get_option(ddp_ctx* c, int32_t option, int64_t* value) {
         case DDP_OPT_COALESCE: *value = coalesce_limit(c); return DDP_OK;
         case DDP_OPT_TAIL_ON_BACKWARD: *value = c->tail_on_backward; return DDP_OK;
         case DDP_OPT_GATE_WAIT_US: *value = c->gate_wait_us; return DDP_OK;
+        case DDP_OPT_LAUNCH_HOLD: *value = c->hold_marks; return DDP_OK;
         case DDP_OPT_FLAG_ORDER: *value = flags_usable(c) ? 1 : 0; return DDP_OK;
         default: return DDP_ERR_ARG;
     }
@@ -1002,6 +1005,23 @@ static bool set_participation(ddp_ctx* c, int32_t param_id, const uint8_t* used)
     return any;
 }
 
+// What a single ready-mark call does with the buckets that are launchable: enqueue them now
+// (the default: Algorithm 1 launches a bucket as soon as it is ready), or, with
+// DDP_OPT_LAUNCH_HOLD, keep them back for a bounded number of further marks so that buckets
+// that become ready shortly afterwards share their launch.
+static int32_t flush_or_hold(ddp_ctx* c) {
+    if (c->deferred.empty() || c->hold_marks <= 0) return flush_deferred(c);
+    const int32_t last = static_cast<int32_t>(c->plan.buckets.size()) - 1;
+    bool now = c->deferred.back() == last || c->tracker.marks() >= c->hold_until;
+    if (!now) {
+        uint64_t bytes = 0;
+        for (int32_t b : c->deferred) bytes += c->plan.buckets[b].bytes();
+        const int64_t limit = coalesce_limit(c);
+        now = limit <= 0 || bytes >= static_cast<uint64_t>(limit);     // nothing more fits into the launch
+    }
+    return now ? flush_deferred(c) : DDP_OK;
+}
+
 static int32_t mark_one(ddp_ctx* c, int32_t param_id, const uint8_t* used) {
     std::vector<int32_t> launch;
     const int rc = c->tracker.mark(param_id, launch);
@@ -1010,6 +1030,7 @@ static int32_t mark_one(ddp_ctx* c, int32_t param_id, const uint8_t* used) {
     c->order_running.push_back(param_id);
     if (set_participation(c, param_id, used)) c->used_running[param_id] = 1;
     for (int32_t b : launch) note_launch(c, b, c->tracker.marks() - 1);
+    if (!launch.empty()) c->hold_until = c->tracker.marks() + c->hold_marks;
     if (coalesce_limit(c) <= 0) return flush_deferred(c);
     return DDP_OK;
 }
@@ -1020,7 +1041,7 @@ int32_t ddp_mark_ready(ddp_ctx* c, int32_t param_id) {
     new_call(c);
     const int32_t st = mark_one(c, param_id, nullptr);
     if (st != DDP_OK) return st;
-    return flush_deferred(c);
+    return flush_or_hold(c);
 }
 
 int32_t ddp_mark_ready_local(ddp_ctx* c, int32_t param_id, const uint8_t* used) {
@@ -1030,7 +1051,7 @@ int32_t ddp_mark_ready_local(ddp_ctx* c, int32_t param_id, const uint8_t* used) 
     new_call(c);
     const int32_t st = mark_one(c, param_id, used);
     if (st != DDP_OK) return st;
-    return flush_deferred(c);
+    return flush_or_hold(c);
 }
 
 int32_t ddp_mark_ready_many(ddp_ctx* c, const int32_t* ids, int32_t count) {
@@ -1311,7 +1332,8 @@ int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, cons
         const int64_t ticks = delay_ns ? delay_ns[k] * c->wall_clock_khz / 1000000 : 0;
         if (ticks > 0 || d_rows) {
             // buckets completed so far go out before more backward work is enqueued
-            const int32_t stf = flush_deferred(c);
+            // (unless a launch hold keeps them back for a few more marks)
+            const int32_t stf = flush_or_hold(c);
             if (stf != DDP_OK) return stf;
             new_call(c);
             HIPCHK(c, ddp::launch_emit(ticks, d_rows ? d_rows + 2 * R * k : nullptr, c->R,
@@ -1328,7 +1350,8 @@ int32_t ddp_synth_backward(ddp_ctx* c, const int32_t* order, int32_t count, cons
             }
         }
     }
-    return flush_deferred(c);
+    // with marks this is a call that delivers many of them: what they completed goes out now
+    return mark ? flush_deferred(c) : flush_or_hold(c);
 }
 
 int32_t ddp_get_kernel_times(ddp_ctx* c, int32_t kind, float* ms, int32_t* ids, int32_t cap,

@@ -106,10 +106,9 @@ struct GateRecord;   // below, with the flag-ordering kernels
 // launch; if gate->failed_tag == tag the launch does nothing.
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
-                               bool pair, bool nontemporal, unsigned lds,
+                               bool nontemporal, unsigned lds,
                                const GateRecord* gate, uint32_t tag, hipStream_t s);
-// (with t.out set -- 16-bit gradients, binary32 averages written to t.out -- nwrite must be 1
-// and pair is ignored)
+// (with t.out set -- 16-bit gradients, binary32 averages written to t.out -- nwrite must be 1)
 
 // ---- stream ordering through device flags -------------------------------------
 // A bucket launch on a reduction stream must come after the backward-stream work
@@ -136,8 +135,8 @@ struct GateRecord {                 // one per bucket, used by the launch whose 
     int32_t dtype;
 };
 
-// backward stream: ready_seq = seq (release: everything enqueued before is visible
-// to whoever observes the number).
+// backward stream: ready_seq = seq.  (Everything enqueued before it on that stream has
+// ended, and is visible device-wide, by the time the kernel that stores the number runs.)
 hipError_t launch_announce(OrderState* st, unsigned long long seq, hipStream_t s);
 
 // reduction stream: wait (at most wait_ticks of the device wall clock) until

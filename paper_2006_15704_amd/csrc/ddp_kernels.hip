@@ -488,12 +488,18 @@ __device__ __forceinline__ uint64_t used_mask(const uint8_t* __restrict__ flags,
 }
 
 // One tile of the fused gather-reduce-scatter.
+// gate / tag: see GateRecord (null = no gate).  A launch whose gate gave up must
+// not touch gradients that may still be incomplete; the repair launch redoes it.
+// The gate word is fetched together with the tile's tables (one round of scalar
+// loads, not one more in front of them) and looked at before any gradient is.
 template <int DT, bool NT, int U, bool OUT32 = false>
 __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int R, int nwrite,
                                            const uint8_t* __restrict__ local, int keep_unused,
-                                           const Scale& sc) {
+                                           const Scale& sc, const GateRecord* __restrict__ gate = nullptr,
+                                           uint32_t tag = 0) {
     constexpr int ES = Fmt<DT>::ES;
     constexpr int VEC = Fmt<DT>::VEC;
+    const uint32_t gate_word = gate != nullptr ? gate->failed_tag : ~tag;
     const int g = t.tile_seg[tile];
     // Everything that depends on g alone is fetched together: the segment
     // record and the first eight replica pointers (the pointer table is padded
@@ -503,6 +509,7 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
     const char* pre[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) pre[i] = static_cast<const char*>(row[i]);
+    if (gate_word == tag) return;          // the gate in front of this launch gave up
     const int64_t numel = si.numel;
     const int64_t ltile = tile - si.tile0;
     // participation of the R replicas in this parameter (bit r = replica r used
@@ -602,12 +609,6 @@ __device__ __forceinline__ void fused_tile(const SegTables& t, int64_t tile, int
     }
 }
 
-// gate / tag: see GateRecord.  A launch whose gate gave up must not touch
-// gradients that may still be incomplete; the repair launch redoes it.
-__device__ __forceinline__ bool gate_failed(const GateRecord* __restrict__ gate, uint32_t tag) {
-    return gate != nullptr && gate->failed_tag == tag;
-}
-
 template <int DT, bool NT, int U, bool OUT32 = false>
 __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int64_t tile_base, int R,
                                                              int nwrite,
@@ -615,72 +616,26 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int64_
                                                              int keep_unused, Scale sc,
                                                              const GateRecord* __restrict__ gate,
                                                              uint32_t tag) {
-    if (gate_failed(gate, tag)) return;
-    fused_tile<DT, NT, U, OUT32>(t, tile_base + blockIdx.x, R, nwrite, local, keep_unused, sc);
-}
-
-// Large launches: a block takes two neighbouring tiles.  When both lie inside
-// the same segment and need no predication they are handled as one piece with
-// twice the vectors per thread in flight; otherwise one after the other.
-template <int DT, bool NT, int U>
-__global__ __launch_bounds__(BLOCK) void fused_reduce_pair_kernel(SegTables t, int64_t tile_base,
-                                                                  int64_t tile_end, int R, int nwrite,
-                                                                  const uint8_t* __restrict__ local,
-                                                                  int keep_unused, Scale sc,
-                                                                  const GateRecord* __restrict__ gate,
-                                                                  uint32_t tag) {
-    constexpr int ES = Fmt<DT>::ES;
-    constexpr int VEC = Fmt<DT>::VEC;
-    constexpr int U2 = 2 * U;
-    if (gate_failed(gate, tag)) return;
-    static_assert(TILE_VECS == BLOCK * U, "pairing assumes one step per tile");
-    const int64_t tile_a = tile_base + 2 * static_cast<int64_t>(blockIdx.x);
-    const int64_t tile_b = tile_a + 1;
-    if (tile_b < tile_end) {
-        const int g = t.tile_seg[tile_a];
-        if (g == t.tile_seg[tile_b]) {
-            void* const* __restrict__ row = t.grad + static_cast<int64_t>(g) * t.R;
-            const SegInfo si = t.seg[g];
-            const char* pre[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) pre[i] = static_cast<const char*>(row[i]);
-            const int sh = si.lead_bytes() / ES;
-            const int64_t e_tile = (tile_a - si.tile0) * (TILE_BYTES / ES) - sh;
-            const bool all_used =
-                local == nullptr ||
-                used_mask(local + static_cast<int64_t>(g) * t.R, R) == (R >= 64 ? ~uint64_t(0) : ((uint64_t(1) << R) - 1));
-            if (si.congruent() && all_used && e_tile >= 0 && e_tile + 2 * (TILE_BYTES / ES) <= si.numel) {
-                const int64_t tile_byte = e_tile * ES;
-                uint32_t lane_off[U2];
-                float acc[U2][VEC];
-#pragma unroll
-                for (int u = 0; u < U2; ++u) lane_off[u] = (u * BLOCK + threadIdx.x) * 16u;
-                sum_interior_pre<DT, NT, U2>(
-                    pre, tile_byte, [&](int r) { return static_cast<const char*>(row[r]) + tile_byte; }, R,
-                    lane_off, acc);
-#pragma unroll
-                for (int u = 0; u < U2; ++u) {
-                    const u32x4 out = scaled<DT>(sc, acc[u]);
-                    store16s<NT>(const_cast<char*>(pre[0]) + tile_byte + lane_off[u], out);
-                    for (int w = 1; w < nwrite; ++w)
-                        store16s<NT>(static_cast<char*>(row[w]) + tile_byte + lane_off[u], out);
-                }
-                return;
-            }
-        }
-        fused_tile<DT, NT, U>(t, tile_a, R, nwrite, local, keep_unused, sc);
-        fused_tile<DT, NT, U>(t, tile_b, R, nwrite, local, keep_unused, sc);
-        return;
-    }
-    fused_tile<DT, NT, U>(t, tile_a, R, nwrite, local, keep_unused, sc);
+    fused_tile<DT, NT, U, OUT32>(t, tile_base + blockIdx.x, R, nwrite, local, keep_unused, sc, gate, tag);
 }
 
 // ---- stream ordering through device flags ------------------------------------
 constexpr uint32_t MAX_GATE_POLLS = 1u << 22;
 
+// Memory ordering of the handshake.  What the bucket kernel must see is written
+// by kernels that precede the announcement on the backward stream, and the bucket
+// kernel is a launch of its own behind the gate.  Both hops are kernel boundaries
+// of a stream: the writers have ended (their results are released to the device)
+// before the announcing kernel starts, and the bucket kernel acquires at its
+// start, after the gate has ended.  The sequence number itself therefore needs no
+// release or acquire of its own -- a release here would only write back this
+// XCD's L2, which holds none of the gradients in question but a good deal of the
+// concurrently running reduce kernel's lines (measured: 11 us per announcement
+// next to a BERT-sized reduction) -- just device-wide atomicity and visibility,
+// which relaxed agent-scope atomics give.
 __global__ __launch_bounds__(64) void announce_kernel(OrderState* st, unsigned long long seq) {
     if (threadIdx.x == 0)
-        __hip_atomic_store(&st->ready_seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&st->ready_seq, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // One wave; lane 0 polls.  Both bounds (wall-clock ticks and the poll count) end
@@ -694,7 +649,7 @@ __global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long 
     if (__hip_atomic_load(&st->abort_tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tag) {
         const uint64_t t0 = wall_clock64();
         for (uint32_t poll = 0; poll < MAX_GATE_POLLS; ++poll) {
-            if (__hip_atomic_load(&st->ready_seq, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= need) {
+            if (__hip_atomic_load(&st->ready_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= need) {
                 ok = true;
                 break;
             }
@@ -734,7 +689,7 @@ __global__ __launch_bounds__(64) void probe_wait_kernel(unsigned long long* word
     const uint64_t t0 = wall_clock64();
     unsigned long long seen = 0;
     for (uint32_t poll = 0; poll < MAX_GATE_POLLS; ++poll) {
-        if (__hip_atomic_load(&word[0], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == value) {
+        if (__hip_atomic_load(&word[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == value) {
             seen = 1;
             break;
         }
@@ -746,7 +701,7 @@ __global__ __launch_bounds__(64) void probe_wait_kernel(unsigned long long* word
 
 __global__ __launch_bounds__(64) void probe_write_kernel(unsigned long long* word, unsigned long long value) {
     if (threadIdx.x == 0)
-        __hip_atomic_store(&word[0], value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&word[0], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- K4: no_sync accumulation ---------------------------------------------
@@ -941,14 +896,9 @@ hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* 
 }
 
 template <int DT>
-static hipError_t fused_dispatch(bool pair, bool nt, int64_t ntiles, unsigned lds, hipStream_t s,
+static hipError_t fused_dispatch(bool nt, int64_t ntiles, unsigned lds, hipStream_t s,
                                  const SegTables& t, int64_t tile_base, int R, int nwrite,
                                  const uint8_t* local, int keep, Scale sc, const GateRecord* gate, uint32_t tag) {
-    if (pair) {
-        dim3 grid(static_cast<unsigned>((ntiles + 1) / 2));
-        if (nt) return launch(fused_reduce_pair_kernel<DT, true, RU>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc, gate, tag);
-        return launch(fused_reduce_pair_kernel<DT, false, RU>, grid, lds, s, t, tile_base, tile_base + ntiles, R, nwrite, local, keep, sc, gate, tag);
-    }
     dim3 grid(static_cast<unsigned>(ntiles));
     if (nt) return launch(fused_reduce_kernel<DT, true, RU>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
     return launch(fused_reduce_kernel<DT, false, RU>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
@@ -956,7 +906,7 @@ static hipError_t fused_dispatch(bool pair, bool nt, int64_t ntiles, unsigned ld
 
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
-                               bool pair, bool nontemporal, unsigned lds,
+                               bool nontemporal, unsigned lds,
                                const GateRecord* gate, uint32_t tag, hipStream_t s) {
     if (ntiles <= 0) return hipSuccess;
     const int keep = keep_unused ? 1 : 0;
@@ -972,9 +922,9 @@ hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base,
                            : launch(fused_reduce_kernel<2, false, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
     }
     switch (dtype) {
-        case 0: return fused_dispatch<0>(pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-        case 1: return fused_dispatch<1>(pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-        case 2: return fused_dispatch<2>(pair, nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        case 0: return fused_dispatch<0>(nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        case 1: return fused_dispatch<1>(nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        case 2: return fused_dispatch<2>(nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
         default: return hipErrorInvalidValue;
     }
 }

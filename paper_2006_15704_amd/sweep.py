@@ -20,6 +20,9 @@ For every cap and delay the script reports
                  DDP_OPT_TAIL_ON_BACKWARD that includes the last buckets
     overlap      1 - exposed / t_sync
 one JSON object per line.  Run:  python -m paper_2006_15704_amd.sweep
+
+`python -m paper_2006_15704_amd.sweep --knobs` runs the sweeps that the
+library's launch defaults rest on instead (see knob_sweep).
 """
 from __future__ import annotations
 
@@ -77,7 +80,78 @@ def timed_exposed(backward, finalize, sync, reps, torch, stream):
     return statistics.median(total), statistics.median(exposed)
 
 
+def knob_sweep(args) -> int:
+    """The measurements behind the library's launch defaults, one JSON object per
+    line: resident reduce blocks per compute unit, launch size (coalescing
+    limit) against the number of replicas, and the non-temporal hint, on the
+    BERT-large- and ResNet-50-shaped lists in binary32.  All marks of a step
+    arrive in one call; GPU time between two events around the timed steps."""
+    import torch
+    import workloads
+    import paper_2006_15704_amd as lib
+    from paper_2006_15704_amd import harness
+
+    def rate(workload, R, options, steps, replica_skew=None):
+        if workload == "uniform":          # 40 tensors of 25 MiB: every tile is interior
+            numel = [25 * MIB // 4] * 40
+        else:
+            numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[workload]())
+        n = len(numel)
+        grads = harness.DeviceGrads(numel, [0] * n, R, replica_skew=replica_skew)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(7)
+        for r in range(R):
+            b = grads.bufs[r]
+            b[: b.numel() // 4 * 4].view(torch.float32).normal_(0.0, 1e-3, generator=gen)
+        order = list(range(n - 1, -1, -1))
+        with harness.Session(grads, 25 * MIB, lib.DDP_PIPELINE_FUSED) as s:
+            for opt, val in options:
+                lib.ddp_set_option(s.ctx, opt, val)
+            for _ in range(2):
+                lib.ddp_mark_ready_many(s.ctx, order)
+                lib.ddp_finalize_backward(s.ctx)
+            lib.ddp_synchronize(s.ctx)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(s.backward_stream)
+            for _ in range(steps):
+                lib.ddp_mark_ready_many(s.ctx, order)
+                lib.ddp_finalize_backward(s.ctx)
+            b.record(s.backward_stream)
+            lib.ddp_synchronize(s.ctx)
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / steps
+        total = (R + 1) * sum(numel) * 4
+        return round(ms, 4), round(total / ms / 1e6 / 8000.0, 4)
+
+    def emit(**kw):
+        print(json.dumps(kw), flush=True)
+
+    for workload, steps in (("resnet50", 40), ("bert_large", 8)):
+        for blocks in (0, 1, 2, 3, 4):
+            ms, frac = rate(workload, 8, ((lib.DDP_OPT_REDUCE_BLOCKS_PER_CU, blocks), (lib.DDP_OPT_REDUCE_CAP_MIN_BYTES, 0)), steps)
+            emit(sweep="blocks_per_cu", workload=workload, R=8, blocks_per_cu=blocks, ms_per_sync=ms, frac_of_hbm_peak=frac)
+    for R in (2, 4, 8, 16, 32):
+        for mib in (25, 50, 70, 100, 240, 400):
+            ms, frac = rate("bert_large", R, ((lib.DDP_OPT_COALESCE, mib * MIB),), 4 if R >= 16 else 8)
+            emit(sweep="launch_size", workload="bert_large", R=R, coalesce_mib=mib, ms_per_sync=ms, frac_of_hbm_peak=frac)
+        ms, frac = rate("bert_large", R, (), 4 if R >= 16 else 8)
+        emit(sweep="launch_size", workload="bert_large", R=R, coalesce_mib="default", ms_per_sync=ms, frac_of_hbm_peak=frac)
+    for workload, steps in (("resnet50", 40), ("bert_large", 8)):
+        for nt in (1, 0):
+            ms, frac = rate(workload, 8, ((lib.DDP_OPT_NONTEMPORAL, nt),), steps)
+            emit(sweep="nontemporal", workload=workload, R=8, nontemporal=nt, ms_per_sync=ms, frac_of_hbm_peak=frac)
+    # replicas whose tensors sit at different offsets modulo 16 bytes
+    for what, skew in (("all replicas alike modulo 16 bytes", None),
+                       ("replica r shifted by 4 * (r mod 4) bytes", [4 * (r % 4) for r in range(8)])):
+        ms, frac = rate("uniform", 8, (), 8, replica_skew=skew)
+        emit(sweep="replica_alignment", workload="40 tensors of 25 MiB", R=8, placement=what, ms_per_sync=ms,
+             frac_of_hbm_peak=frac)
+    return 0
+
+
 def main() -> int:
+    if "--knobs" in sys.argv:
+        return knob_sweep(None)
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "bert_large"])
     ap.add_argument("--dtype", default="f16", choices=["f32", "f16", "bf16"])

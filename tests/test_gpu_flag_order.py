@@ -191,3 +191,40 @@ def test_events_and_flags_give_the_same_bits_and_options_are_validated():
             d.ddp_synchronize(s.ctx)
             for i in range(n):
                 assert grads.download(0, i).tobytes() == want[i].tobytes(), f"flag_order {flag_order} parameter {i}"
+
+
+@pytest.mark.parametrize("hold", [2, 6, 1000])
+@pytest.mark.parametrize("flag_order", [-1, 0])
+def test_launch_hold_under_a_running_backward_pass(hold, flag_order):
+    """DDP_OPT_LAUNCH_HOLD: launchable buckets wait for a few more marks and share launches;
+    the ordering after the backward stream, the launch log and the bits stay what they are.
+    Marks arrive through the synthetic backward pass (NaN until produced) in a seeded random
+    order with three parameters never marked."""
+    d, harness = lib()
+    import torch
+    rng = np.random.default_rng(40 + hold)
+    numel = ragged(35, 30, 5000)
+    n, R, cap = len(numel), 3, 20 << 10
+    dtypes = [FP32] * n
+    order = [int(p) for p in rng.permutation(n)][: n - 3]
+    reps = [workloads.gaussian_replica(670, r, 0, numel, 1.0, FP32) for r in range(R)]
+    want, asg, wlog = oracle.synchronize(numel, dtypes, cap, reps, order)
+    grads = harness.DeviceGrads(numel, dtypes, R, fill=0xFF)
+    src = harness.DeviceGrads(numel, dtypes, R)
+    for r in range(R):
+        src.upload_replica(r, reps[r])
+    with harness.Session(grads, cap, FUSED) as s:
+        d.ddp_set_option(s.ctx, d.DDP_OPT_FLAG_ORDER, flag_order)
+        d.ddp_set_option(s.ctx, d.DDP_OPT_LAUNCH_HOLD, hold)
+        for it in range(2):
+            for p in order:                    # one call per parameter: produce it, then mark it
+                d.ddp_synth_backward(s.ctx, [p], [60_000], src.ptrs(), False)
+                d.ddp_mark_ready(s.ctx, p)
+            d.ddp_finalize_backward(s.ctx)
+            d.ddp_synchronize(s.ctx)
+            assert d.ddp_get_launch_log(s.ctx, 1) == wlog
+            for i in range(n):
+                assert grads.download(0, i).tobytes() == want[i].tobytes(), f"iteration {it} parameter {i}"
+            for r in range(R):                 # back to NaN for the next iteration
+                grads.bufs[r].fill_(0xFF)
+            torch.cuda.synchronize()

@@ -149,7 +149,7 @@ def test_mixed_element_types(pipeline):
 
 @pytest.mark.parametrize("dtype", [FP32, FP16, BF16])
 def test_kernel_variants_give_the_same_bits(dtype):
-    """With and without two-tile blocks, with hinted and plain loads, under every
+    """Coalesced and single launches, with hinted and plain loads, under every
     cap on resident blocks, on a list that mixes large, tiny, unaligned and
     unmarked tensors."""
     d, _ = lib()
@@ -159,14 +159,13 @@ def test_kernel_variants_give_the_same_bits(dtype):
     R = 5
     reps = gaussian_reps(13, numel, R, 1e-2, dtype)
     order = [8, 7, 6, 4, 3, 2, 0]          # parameters 5 and 1 never marked
-    for pair_min in (0, 1 << 40):
+    for coalesce in (1 << 62, 0):
         for nt in (1, 0):
-            opts = [(d.DDP_OPT_PAIR_MIN_BYTES, pair_min), (d.DDP_OPT_NONTEMPORAL, nt),
-                    (d.DDP_OPT_COALESCE, (1 << 62) if pair_min == 0 else 0),
+            opts = [(d.DDP_OPT_NONTEMPORAL, nt), (d.DDP_OPT_COALESCE, coalesce),
                     # occupancy cap of the reduce kernels: none, one block per unit (the largest
                     # LDS allocation), three
                     (d.DDP_OPT_REDUCE_CAP_MIN_BYTES, 0),
-                    (d.DDP_OPT_REDUCE_BLOCKS_PER_CU, (0 if nt else 1) if pair_min == 0 else 3)]
+                    (d.DDP_OPT_REDUCE_BLOCKS_PER_CU, (0 if nt else 1) if coalesce else 3)]
             for pipeline in (STAGED, FUSED):
                 run_sync(numel, [dtype] * len(numel), reps, 1 << 22, pipeline, order=order, skew=skew,
                          options=opts, write_all=(nt == 0))

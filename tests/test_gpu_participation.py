@@ -132,7 +132,7 @@ def test_participation_with_coalesced_launches_and_kernel_variants(pipeline):
     d, _ = lib()
     numel, dtypes, reps, marks, _, _ = random_case(30, 40, 8, FP32, 6000)
     for options in ([(d.DDP_OPT_COALESCE, 1 << 62)], [(d.DDP_OPT_COALESCE, 0), (d.DDP_OPT_REDUCE_STREAMS, 1)],
-                    [(d.DDP_OPT_COALESCE, 1 << 62), (d.DDP_OPT_PAIR_MIN_BYTES, 0)],
+                    [(d.DDP_OPT_COALESCE, 1 << 62), (d.DDP_OPT_REDUCE_BLOCKS_PER_CU, 1), (d.DDP_OPT_REDUCE_CAP_MIN_BYTES, 0)],
                     [(d.DDP_OPT_NONTEMPORAL, 0)]):
         check_against_oracle(numel, dtypes, reps, marks, 20000, pipeline, False, True, options=options)
 

@@ -395,3 +395,31 @@ def test_outputs_for_16_bit_gradients_on_a_plan_only_context(d):
         assert e.value.code == d.DDP_ERR_ARG
     finally:
         d.ddp_destroy(ctx)
+
+
+@pytest.mark.parametrize("hold", [1, 3, 50])
+def test_launch_hold_changes_neither_the_buckets_nor_the_launch_log(d, hold):
+    """DDP_OPT_LAUNCH_HOLD only postpones when a launchable bucket is enqueued; which bucket
+    became launchable after which mark is what the log records."""
+    rng = np.random.default_rng(hold)
+    numel = [int(x) for x in rng.integers(1, 400, size=60)]
+    order = [int(p) for p in rng.permutation(60)][:55]          # five never marked
+    ctx, nb = plan(d, numel, [0] * 60, 2000)
+    try:
+        d.ddp_set_option(ctx, d.DDP_OPT_LAUNCH_HOLD, hold)
+        assert d.ddp_get_option(ctx, d.DDP_OPT_LAUNCH_HOLD) == hold
+        asg = oracle.assign_buckets(numel, [0] * 60, 2000)
+        want = oracle.launch_schedule(asg, order)
+        for k, p in enumerate(order):
+            d.ddp_mark_ready(ctx, p)
+            assert d.ddp_get_launch_log(ctx, 0) == [x for x in want if x[1] <= k]
+        with pytest.raises(d.DdpError) as e:                    # only between iterations
+            d.ddp_set_option(ctx, d.DDP_OPT_LAUNCH_HOLD, 0)
+        assert e.value.code == d.DDP_ERR_STATE
+        d.ddp_finalize_backward(ctx)
+        assert d.ddp_get_launch_log(ctx, 1) == want
+        with pytest.raises(d.DdpError) as e:
+            d.ddp_set_option(ctx, d.DDP_OPT_LAUNCH_HOLD, -1)
+        assert e.value.code == d.DDP_ERR_ARG
+    finally:
+        d.ddp_destroy(ctx)
