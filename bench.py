@@ -282,9 +282,9 @@ class Rig:
                         "steps of one HIP event pair per launch (the pair adds about 3 us to each launch)"}
 
 
-def shape_leg(lib, harness, torch, workload, sets, steps, warmup, legs, traffic_mode):
+def shape_leg(lib, harness, torch, workload, sets, steps, warmup, legs, traffic_mode, options=()):
     """The per-call measurement of one workload plus its optional sub-legs."""
-    rig = Rig(lib, harness, torch, workload, sets, lib.DDP_PIPELINE_FUSED)
+    rig = Rig(lib, harness, torch, workload, sets, lib.DDP_PIPELINE_FUSED, options=options)
     try:
         res = rig.measure(steps, warmup, per_call=True)
         res["roofline"]["traffic"] = read_traffic(workload, traffic_mode)
@@ -565,6 +565,10 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=4,
                     help="independent sets of replica gradients taken in turn by consecutive steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--launch-ordering", default="default", choices=["default", "events"],
+                    help="events: order the launches behind the backward stream by HIP events instead of device "
+                         "flags (for runs under the profiler's counter collection, which serializes all kernels, "
+                         "so that a launch never finds the flag it waits for being set meanwhile)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling profiler counters)")
     args = ap.parse_args()
@@ -595,7 +599,8 @@ def main() -> int:
         del src, dst
 
     sets = args.sets if args.workload == "resnet50" else min(args.sets, 2)
-    head = shape_leg(lib, harness, torch, args.workload, sets, args.steps, args.warmup, legs, "per_call")
+    options = ((lib.DDP_OPT_FLAG_ORDER, 0),) if args.launch_ordering == "events" else ()
+    head = shape_leg(lib, harness, torch, args.workload, sets, args.steps, args.warmup, legs, "per_call", options)
     _, _, R, _, dtype, _ = WORKLOADS[args.workload]
     out = {
         "metric": "bucketed grad-sync throughput ((R+W)*B per synchronization)",
