@@ -200,7 +200,7 @@ class Rig:
             self.step(k, per_call)
         self.sync()
         it_ms = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_ITERATION)[0] for s in self.sessions])
-        # the reduce kernel by itself: one event pair per launch, on the stream the launch runs on
+        # the reduce kernel by itself: every launch carries an event pair stamped with its start and end
         for s in self.sessions:
             lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 1)
         for k in range(spread_iters):
@@ -239,8 +239,9 @@ class Rig:
                 "timing": "one HIP event pair around the timed steps on the backward stream (every launch runs on it "
                           "or is joined to it by finalize), divided by the launches: kernels, gates, joins and gaps",
                 "per_launch_event_pairs": {
-                    "what": f"one HIP event pair per launch on the stream it runs on (third pass of {spread_iters} steps); "
-                            "launches on the two reduction streams overlap, each then takes longer than its share",
+                    "what": f"every launch carries a pair of HIP events stamped with the kernel's own start and end "
+                            f"(third pass of {spread_iters} steps); launches on the two reduction streams overlap, each "
+                            "then takes longer than its share",
                     "launch_ms": spread(k_ms),
                     "mean_ms": round(float(k_ms.mean()), 5)},
                 "iteration_ms": spread(it_ms),
@@ -250,14 +251,35 @@ class Rig:
         }
 
     def per_bucket(self, steps):
-        """The rate of every bucket's launch by itself: one reduction stream, one launch per
-        bucket, all marks of a step in one call (so that the launches queue up behind each other
-        and no host latency sits between a launch's two events), one HIP event pair per launch."""
-        lib = self.lib
+        """Every bucket in a launch of its own, the launches back to back on one reduction stream
+        (all marks of a step in one call, so that no host latency sits between the launches; the
+        stream is ordered behind the backward stream by one event per step, so that no gate kernel
+        sits between the bucket kernels).  Every launch carries a pair of HIP events that the
+        runtime stamps with the kernel's own start and end; the iteration as a whole is timed
+        once more without any per-launch events."""
+        lib, torch = self.lib, self.torch
+        one_stream = ((lib.DDP_OPT_REDUCE_STREAMS, 1), (lib.DDP_OPT_COALESCE, 0),
+                      (lib.DDP_OPT_TAIL_ON_BACKWARD, 0), (lib.DDP_OPT_FLAG_ORDER, 0))
+        defaults = ((lib.DDP_OPT_REDUCE_STREAMS, -1), (lib.DDP_OPT_COALESCE, -1),
+                    (lib.DDP_OPT_TAIL_ON_BACKWARD, 1), (lib.DDP_OPT_FLAG_ORDER, -1))
         for s in self.sessions:
-            lib.ddp_set_option(s.ctx, lib.DDP_OPT_REDUCE_STREAMS, 1)
-            lib.ddp_set_option(s.ctx, lib.DDP_OPT_COALESCE, 0)
-            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TAIL_ON_BACKWARD, 0)
+            for o, v in one_stream:
+                lib.ddp_set_option(s.ctx, o, v)
+        for k in range(len(self.sessions)):
+            self.step(k, False)
+        self.sync()
+        region = []
+        for _ in range(3):
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record(self.backward_stream)
+            for k in range(steps):
+                self.step(k, False)
+            b.record(self.backward_stream)
+            self.sync()
+            region.append(a.elapsed_time(b) / steps)
+        it_ms = sorted(region)[1]
+        for s in self.sessions:
             lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 1)
         for k in range(steps):
             self.step(k, False)
@@ -266,20 +288,27 @@ class Rig:
         ids = np.concatenate([lib.ddp_get_kernel_times(s.ctx, lib.DDP_K_REDUCE)[1] for s in self.sessions])
         for s in self.sessions:
             lib.ddp_set_option(s.ctx, lib.DDP_OPT_TIMING, 0)
-            lib.ddp_set_option(s.ctx, lib.DDP_OPT_REDUCE_STREAMS, -1)
-            lib.ddp_set_option(s.ctx, lib.DDP_OPT_COALESCE, -1)
-            lib.ddp_set_option(s.ctx, lib.DDP_OPT_TAIL_ON_BACKWARD, 1)
-        out = {}
+            for o, v in defaults:
+                lib.ddp_set_option(s.ctx, o, v)
+        out, us = {}, {}
         for b in range(self.n_buckets):
             sel = ms[ids == b]
             if len(sel):
                 out[str(b)] = round((self.R + 1) * self.bucket_elems[b] * self.es / float(np.median(sel)) / 1e6, 1)
+                us[str(b)] = round(float(np.median(sel)) * 1e3, 2)
         total = self.alg_bytes * steps / float(ms.sum()) / 1e6
-        return {"reduce_gbps_per_bucket": out, "reduce_gbps": round(total, 1),
+        return {"reduce_gbps_per_bucket": out, "kernel_us_per_bucket": us, "reduce_gbps": round(total, 1),
                 "frac_of_hbm_peak": round(total / HBM_PEAK_GBPS, 4),
+                "iteration_ms": round(it_ms, 4),
+                "iteration_gbps": round(self.alg_bytes / it_ms / 1e6, 1),
+                "iteration_frac_of_hbm_peak": round(self.alg_bytes / it_ms / 1e6 / HBM_PEAK_GBPS, 4),
                 "bucket_mib": [round(e * self.es / MIB, 2) for e in self.bucket_elems],
-                "note": "one reduction stream, one launch per bucket, launches queued back to back; median over "
-                        "steps of one HIP event pair per launch (the pair adds about 3 us to each launch)"}
+                "note": "one reduction stream ordered by events, one launch per bucket, launches queued back to back. "
+                        "reduce_gbps*: from the kernels' own start and end stamps (median over steps per bucket; "
+                        "reduce_gbps over the sum of all kernel durations). iteration_*: the same steps without "
+                        "per-launch events, HIP events on the backward stream around the timed steps (median of three "
+                        "regions): kernels, the gaps between them, the cross-stream order at the start of a step and "
+                        "the join at its end"}
 
 
 def shape_leg(lib, harness, torch, workload, sets, steps, warmup, legs, traffic_mode, options=()):

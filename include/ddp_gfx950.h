@@ -76,8 +76,10 @@ typedef struct ddp_ctx ddp_ctx;
 #define DDP_OPT_PIPELINE       1  /* DDP_PIPELINE_STAGED (default) or DDP_PIPELINE_FUSED */
 #define DDP_OPT_WRITE_ALL      2  /* 0 (default): the average is written to replica 0's gradient
                                      tensors only (one rank's view); 1: to all R replicas' tensors */
-#define DDP_OPT_TIMING         3  /* any time.  1: bracket every kernel launch with a pair of HIP
-                                     events on its stream; 2: one pair per iteration, from just
+#define DDP_OPT_TIMING         3  /* any time.  1: every pack / reduce / unpack / accumulate launch
+                                     carries a pair of HIP events that the runtime stamps with the
+                                     kernel's own start and end (no event packet between the
+                                     kernels of a stream); 2: one pair per iteration, from just
                                      before its first bucket launch to just after its last (kind
                                      DDP_K_ITERATION); 0: off.  Read with ddp_get_kernel_times */
 #define DDP_OPT_NONTEMPORAL    5  /* any time: 1 (default) = read-once inputs are loaded, and the
@@ -207,13 +209,14 @@ const char* ddp_last_error(const ddp_ctx* ctx);
 
 int32_t ddp_set_option(ddp_ctx* ctx, int32_t option, int64_t value);
 
-/* Reads back what is in effect for DDP_OPT_PIPELINE, _WRITE_ALL, _TIMING,
- * _FIND_UNUSED, _REDUCE_STREAMS, _TAIL_ON_BACKWARD, _GATE_WAIT_US, _LAUNCH_HOLD, _COALESCE (the
- * byte limit in effect, also when it was chosen from R) and _FLAG_ORDER (1 if
- * the launches of the next iteration would be ordered through device flags: the
- * option allows it, the pipeline is the fused one, the buckets are built and
- * every reduction stream in use passed the concurrency probe; else 0), and for
- * DDP_STAT_REPAIRED_LAUNCHES below.  Other options -> DDP_ERR_ARG. */
+/* Reads back what is in effect for every DDP_OPT_ option as it was set (-1
+ * where that means "the library chooses"), except: DDP_OPT_COALESCE gives the
+ * byte limit in effect (also when it was chosen from R) and DDP_OPT_FLAG_ORDER
+ * gives 1 if the launches of the next iteration would be ordered through device
+ * flags (the option allows it, the pipeline is the fused one, the buckets are
+ * built and every reduction stream in use passed the concurrency probe), else
+ * 0.  Also reads DDP_STAT_REPAIRED_LAUNCHES below.  Unknown option ->
+ * DDP_ERR_ARG. */
 int32_t ddp_get_option(ddp_ctx* ctx, int32_t option, int64_t* value);
 
 /* Read-only through ddp_get_option: the number of bucket launches whose gate

@@ -201,13 +201,16 @@ unsigned lds_for_blocks(const ddp_ctx* c, int32_t blocks) {
 
 using ddp::make_scale;
 
+// DDP_OPT_TIMING = 1: the launch between timed_begin and timed_end (exactly one kernel) carries a
+// pair of events stamped with the kernel's own start and end.
 int32_t timed_begin(ddp_ctx* c, int32_t kind, int32_t bucket, hipStream_t s, size_t* slot) {
+    (void)s;
     *slot = static_cast<size_t>(-1);
     if (c->timing != 1) return DDP_OK;
     TimedLaunch t{kind, bucket, nullptr, nullptr};
     HIPCHK(c, hipEventCreateWithFlags(&t.start, kTimingEvent));
     HIPCHK(c, hipEventCreateWithFlags(&t.stop, kTimingEvent));
-    HIPCHK(c, hipEventRecord(t.start, s));
+    ddp::time_next_launch(t.start, t.stop);
     c->timed.push_back(t);
     *slot = c->timed.size() - 1;
     return DDP_OK;
@@ -215,7 +218,11 @@ int32_t timed_begin(ddp_ctx* c, int32_t kind, int32_t bucket, hipStream_t s, siz
 
 int32_t timed_end(ddp_ctx* c, size_t slot, hipStream_t s) {
     if (slot == static_cast<size_t>(-1)) return DDP_OK;
-    HIPCHK(c, hipEventRecord(c->timed[slot].stop, s));
+    if (ddp::timing_pair_unused()) {
+        // nothing was launched (an empty range): an empty interval on the stream
+        HIPCHK(c, hipEventRecord(c->timed[slot].start, s));
+        HIPCHK(c, hipEventRecord(c->timed[slot].stop, s));
+    }
     return DDP_OK;
 }
 
@@ -748,7 +755,12 @@ int32_t ddp_get_option(ddp_ctx* c, int32_t option, int64_t* value) {
         case DDP_OPT_GATE_WAIT_US: *value = c->gate_wait_us; return DDP_OK;
         case DDP_OPT_LAUNCH_HOLD: *value = c->hold_marks; return DDP_OK;
         case DDP_OPT_FLAG_ORDER: *value = flags_usable(c) ? 1 : 0; return DDP_OK;
-        default: return DDP_ERR_ARG;
+        case DDP_OPT_NONTEMPORAL: *value = c->nontemporal; return DDP_OK;
+        case DDP_OPT_EMIT_BUSY_BLOCKS: *value = c->emit_busy_blocks; return DDP_OK;
+        case DDP_OPT_REDUCE_BLOCKS_PER_CU: *value = c->blocks_per_cu; return DDP_OK;
+        case DDP_OPT_REDUCE_CAP_MIN_BYTES: *value = c->cap_min_bytes; return DDP_OK;
+        case DDP_OPT_ACCUMULATE_BLOCKS_PER_CU: *value = c->acc_blocks_per_cu; return DDP_OK;
+        default: return fail(c, DDP_ERR_ARG, "unknown option");
     }
 }
 

@@ -76,6 +76,13 @@ inline Scale make_scale(int R) {
 // blocks resident on a compute unit (0 = no cap).  The copy kernels K1 and K3
 // keep one or two loads per thread in flight and want every block they can get.
 
+// Timing: the next kernel launched on this thread through one of the pack / reduce / unpack /
+// accumulate wrappers below carries `start` and `stop`; the runtime stamps them with the
+// kernel's own start and end.  timing_pair_unused() clears the request and tells whether it
+// was still pending (the wrapper had nothing to launch).
+void time_next_launch(hipEvent_t start, hipEvent_t stop);
+bool timing_pair_unused();
+
 // K1: gradients -> flat replica slabs for all `nrep` replicas.  local (may be
 // null = every replica used every parameter): participation flags
 // [segment][replica]; 0 = write zeros into that replica's slot and do not read

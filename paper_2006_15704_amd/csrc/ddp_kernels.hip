@@ -11,6 +11,8 @@
 // local gradient accumulation of no_sync (Section 3.2.4).
 #include "ddp_kernels.h"
 
+#include <hip/hip_ext.h>
+
 #include <mutex>
 #include <set>
 #include <utility>
@@ -829,6 +831,9 @@ inline hipError_t after_launch() { return hipGetLastError(); }
 constexpr unsigned kLdsNoOptIn = 64 * 1024;
 constexpr unsigned kLdsPerUnit = 160 * 1024;     // gfx950
 
+// the pair of events that the next launch through launch() on this thread carries (time_next_launch)
+thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+
 template <typename... KArgs, typename... Args>
 static hipError_t launch(void (*kernel)(KArgs...), dim3 grid, unsigned lds, hipStream_t s, Args... args) {
     if (lds > kLdsNoOptIn) {
@@ -848,13 +853,32 @@ static hipError_t launch(void (*kernel)(KArgs...), dim3 grid, unsigned lds, hipS
             raised.insert(key);
         }
     }
-    hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), lds, s, static_cast<KArgs>(args)...);
+    if (g_time_start) {
+        // the runtime stamps the two events with this kernel's own start and end: no packet of
+        // its own sits between consecutive kernels, as an event record would
+        hipEvent_t a = g_time_start, b = g_time_stop;
+        g_time_start = g_time_stop = nullptr;
+        hipExtLaunchKernelGGL(kernel, grid, dim3(BLOCK), lds, s, a, b, 0u, static_cast<KArgs>(args)...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, dim3(BLOCK), lds, s, static_cast<KArgs>(args)...);
+    }
     return hipGetLastError();
 }
 
 }  // namespace
 
 // ---- launch wrappers ---------------------------------------------------------
+void time_next_launch(hipEvent_t start, hipEvent_t stop) {
+    g_time_start = start;
+    g_time_stop = stop;
+}
+
+bool timing_pair_unused() {
+    const bool unused = g_time_start != nullptr;
+    g_time_start = g_time_stop = nullptr;
+    return unused;
+}
+
 hipError_t launch_pack(const SegTables& t, int64_t tile_base, int64_t ntiles, char* slab0,
                        int64_t slab_stride, int nrep, const uint8_t* local, hipStream_t s) {
     if (ntiles <= 0 || nrep <= 0) return hipSuccess;
