@@ -118,9 +118,11 @@ typedef struct ddp_ctx ddp_ctx;
                                      round-robin process groups (Section 5.4 measures rr1/rr3/rr5):
                                      launches are still enqueued in bucket order, but buckets on
                                      different streams may run at the same time.  Every stream waits
-                                     for backward_stream like reduce_stream does, and at finalize all
-                                     of them are joined into reduce_stream before the averaged
-                                     gradients are handed back.  Results are unchanged */
+                                     for backward_stream like reduce_stream does, and at finalize
+                                     backward_stream is made to wait for all of them (directly in the
+                                     fused pipeline; through reduce_stream where the staged pipeline's
+                                     write-back or the bitmap step runs there).  Results are
+                                     unchanged */
 #define DDP_OPT_REDUCE_BLOCKS_PER_CU 13 /* any time: cap on the thread blocks of the reduce kernels that
                                      are resident on one compute unit at a time (an LDS allocation
                                      the kernels do not touch enforces it).  A block keeps R x 2
@@ -167,7 +169,13 @@ typedef struct ddp_ctx ddp_ctx;
                                      (DDP_OPT_GATE_WAIT_US); a launch whose gate gave up does nothing and
                                      is redone by a repair launch that ddp_finalize_backward enqueues on
                                      backward_stream once every gradient exists, so results never depend
-                                     on a wait succeeding.  Streams that share a hardware queue cannot
+                                     on a wait succeeding.  The way back at ddp_finalize_backward is
+                                     ordered likewise: each reduction stream stores the iteration's
+                                     number behind its last launch and one kernel on backward_stream
+                                     waits (bounded) for those numbers, followed by waits for events of
+                                     the same streams, which have fired by then (a wait for an event
+                                     that has yet to fire is handed over slowly on this system when it
+                                     was enqueued long before).  Streams that share a hardware queue cannot
                                      run a gate and its announcement concurrently; ddp_create (and
                                      DDP_OPT_REDUCE_STREAMS) probe for that with a bounded test and such
                                      streams keep events.  0: events always */

@@ -1107,14 +1107,38 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
         if (st != DDP_OK) return st;
     }
     if (!c->plan_only) {
-        // every reduction stream that received work in this iteration joins the caller's
+        // Fused pipeline, no bitmap step: nothing else runs on the reduction side at finalize, and
+        // every reduction stream that received work joins the backward stream directly.  If the
+        // iteration's launches were ordered by device flags, so is the way back: each stream
+        // stores the iteration's tag behind its last launch and one kernel on the backward
+        // stream waits for the tags; the events behind it have fired by then.
+        const bool direct_join = c->pipeline == DDP_PIPELINE_FUSED && !c->iter_zero;
         bool reduce_side_used = c->lane_used[0];
-        for (int l = 1; l < ddp_ctx::kMaxLanes; ++l)
-            if (c->lane_used[l]) {
-                HIPCHK(c, hipEventRecord(c->ev_join[l], c->lane[l]));
-                HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_join[l], 0));
-                reduce_side_used = true;
-            }
+        if (direct_join) {
+            const bool by_flag = c->gates_in_iter > 0;
+            const unsigned long long tag = static_cast<unsigned long long>(c->iteration + 1);
+            uint32_t mask = 0;
+            for (int l = 0; l < ddp_ctx::kMaxLanes; ++l)
+                if (c->lane_used[l] && c->lane[l] != c->backward) {
+                    HIPCHK(c, hipEventRecord(l == 0 ? c->ev_done : c->ev_join[l], c->lane[l]));
+                    if (by_flag) HIPCHK(c, ddp::launch_done(c->d_order, l, tag, c->lane[l]));
+                    mask |= 1u << l;
+                }
+            if (by_flag && mask)
+                HIPCHK(c, ddp::launch_join(c->d_order, mask, tag, c->gate_wait_us * c->wall_clock_khz / 1000, c->backward));
+            for (int l = 0; l < ddp_ctx::kMaxLanes; ++l)
+                if ((mask >> l) & 1u) HIPCHK(c, hipStreamWaitEvent(c->backward, l == 0 ? c->ev_done : c->ev_join[l], 0));
+            if (mask) c->tail_used = true;       // the iteration's launches end on the backward stream
+            reduce_side_used = false;            // (joined already)
+        } else {
+            // every reduction stream that received work in this iteration joins the caller's
+            for (int l = 1; l < ddp_ctx::kMaxLanes; ++l)
+                if (c->lane_used[l]) {
+                    HIPCHK(c, hipEventRecord(c->ev_join[l], c->lane[l]));
+                    HIPCHK(c, hipStreamWaitEvent(c->reduce, c->ev_join[l], 0));
+                    reduce_side_used = true;
+                }
+        }
         // the interval of this iteration's bucket launches ends here if all of them ran on the
         // reduction side, else on the backward stream below
         // an iteration that used gates ends with the repair launch on the backward stream

@@ -133,7 +133,10 @@ struct OrderState {
                                     //    later gates of the iteration give up at once
     uint32_t repaired;              // launches redone by repair launches since the context was created
     uint32_t pad1[30];
+    unsigned long long lane_done[16];   // per reduction stream: the latest iteration tag whose launches
+                                        //    on that stream have all ended (monotonic)
 };
+constexpr int kOrderLanes = 16;
 
 struct GateRecord {                 // one per bucket, used by the launch whose first bucket it is
     int32_t tile_base;              // tile range of the launch
@@ -145,6 +148,16 @@ struct GateRecord {                 // one per bucket, used by the launch whose 
 // backward stream: ready_seq = seq.  (Everything enqueued before it on that stream has
 // ended, and is visible device-wide, by the time the kernel that stores the number runs.)
 hipError_t launch_announce(OrderState* st, unsigned long long seq, hipStream_t s);
+
+// The way back at the end of an iteration.  Reduction stream `lane`, behind its last bucket
+// launch: lane_done[lane] = tag.  Backward stream: wait (at most wait_ticks) until lane_done[l]
+// >= tag for every l in lane_mask.  The join only spares the backward stream a wait for an
+// event that has not fired yet (slow on this system when the wait was enqueued long before):
+// the events of the same streams are recorded before the done kernels and waited for after
+// the join kernel, so a join that gives up changes nothing but the time.
+hipError_t launch_done(OrderState* st, int lane, unsigned long long tag, hipStream_t s);
+hipError_t launch_join(OrderState* st, uint32_t lane_mask, unsigned long long tag, long long wait_ticks,
+                       hipStream_t s);
 
 // reduction stream: wait (at most wait_ticks of the device wall clock) until
 // ready_seq >= need; on failure fill *rec and raise abort_tag.

@@ -668,6 +668,29 @@ __global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long 
     }
 }
 
+// The same handshake in the other direction, once per iteration and reduction stream: the
+// stream's bucket kernels have ended when done_kernel runs, and what follows join_kernel on the
+// backward stream starts after it has ended.
+__global__ __launch_bounds__(64) void done_kernel(OrderState* st, int lane, unsigned long long tag) {
+    if (threadIdx.x == 0)
+        __hip_atomic_store(&st->lane_done[lane], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ __launch_bounds__(64) void join_kernel(OrderState* st, uint32_t lane_mask, unsigned long long tag,
+                                                  long long wait_ticks) {
+    if (threadIdx.x != 0) return;
+    const uint64_t t0 = wall_clock64();
+    for (uint32_t poll = 0; poll < MAX_GATE_POLLS; ++poll) {
+        uint32_t missing = 0;
+        for (int l = 0; l < kOrderLanes; ++l)
+            if ((lane_mask >> l) & 1u)
+                missing |= __hip_atomic_load(&st->lane_done[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < tag ? 1u : 0u;
+        if (!missing) break;
+        if (static_cast<long long>(wall_clock64() - t0) >= wait_ticks) break;
+        __builtin_amdgcn_s_sleep(8);
+    }
+}
+
 // Launches whose gate gave up, redone once every gradient exists.  Block j takes
 // the tiles j, j + G, ... of each failed launch.
 template <int DT, bool NT, int U, bool OUT32 = false>
@@ -955,6 +978,19 @@ hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base,
 
 hipError_t launch_announce(OrderState* st, unsigned long long seq, hipStream_t s) {
     hipLaunchKernelGGL(announce_kernel, dim3(1), dim3(64), 0, s, st, seq);
+    return after_launch();
+}
+
+hipError_t launch_done(OrderState* st, int lane, unsigned long long tag, hipStream_t s) {
+    if (lane < 0 || lane >= kOrderLanes) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(done_kernel, dim3(1), dim3(64), 0, s, st, lane, tag);
+    return after_launch();
+}
+
+hipError_t launch_join(OrderState* st, uint32_t lane_mask, unsigned long long tag, long long wait_ticks,
+                       hipStream_t s) {
+    if (lane_mask >> kOrderLanes) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(join_kernel, dim3(1), dim3(64), 0, s, st, lane_mask, tag, wait_ticks);
     return after_launch();
 }
 
