@@ -132,12 +132,16 @@ struct ddp_ctx {
     char* d_order_mem = nullptr;                  // OrderState followed by the two probe words
     ddp::OrderState* d_order = nullptr;
     unsigned long long* d_probe = nullptr;
-    // Gate records: kGateRows rows of one record per bucket; iteration i uses row i % kGateRows.
+    // Gate records: kGateRows rows of one record per bucket plus one that summarizes the row
+    // ("a gate of this iteration gave up"); iteration i uses row i % kGateRows.
     // Several iterations may be enqueued before the first one's repair launch has run, and a
     // gate of a later iteration that gives up early must not overwrite a record that an
     // earlier iteration's repair launch has yet to read.
     static constexpr int64_t kGateRows = 64;
-    ddp::GateRecord* d_gate = nullptr;            // [kGateRows][buckets], allocated with the buckets
+    ddp::GateRecord* d_gate = nullptr;            // [kGateRows][buckets + 1], allocated with the buckets
+    ddp::GateRecord* gate_row() const {
+        return d_gate + (iteration % kGateRows) * (static_cast<int64_t>(plan.buckets.size()) + 1);
+    }
     int64_t safe_iteration = 0;                   // everything enqueued before this iteration is known to be done
     uint64_t seq_issued = 0;                      // sequence numbers announced so far
     uint64_t probe_value = 0;
@@ -371,8 +375,9 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
                 HIPCHK(c, hipStreamSynchronize(c->backward));
                 c->safe_iteration = c->iteration;
             }
-            ddp::GateRecord* rec = c->d_gate + (c->iteration % ddp_ctx::kGateRows) * static_cast<int64_t>(c->plan.buckets.size()) + first;
+            ddp::GateRecord* rec = c->gate_row() + first;
             HIPCHK(c, ddp::launch_gate(c->d_order, c->call_seq, c->gate_wait_us * c->wall_clock_khz / 1000, rec,
+                                       c->gate_row() + c->plan.buckets.size(),
                                        static_cast<int32_t>(tile_base), static_cast<int32_t>(ntiles), bf.dtype,
                                        static_cast<uint32_t>(c->iteration + 1), st));
             gate = rec;
@@ -886,8 +891,8 @@ static int32_t build_internal(ddp_ctx* c, uint64_t cap_bytes, const std::vector<
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_global), static_cast<size_t>(n), hipHostMallocDefault));
         HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_micro), sizeof(void*) * R * n));
         HIPCHK(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_micro), sizeof(void*) * R * n, hipHostMallocDefault));
-        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_gate), sizeof(ddp::GateRecord) * nb * ddp_ctx::kGateRows));
-        HIPCHK(c, hipMemset(c->d_gate, 0, sizeof(ddp::GateRecord) * nb * ddp_ctx::kGateRows));
+        HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->d_gate), sizeof(ddp::GateRecord) * (nb + 1) * ddp_ctx::kGateRows));
+        HIPCHK(c, hipMemset(c->d_gate, 0, sizeof(ddp::GateRecord) * (nb + 1) * ddp_ctx::kGateRows));
         c->gates_in_iter = 0;
         c->safe_iteration = c->iteration;
         c->ev_ready.resize(nb, nullptr);
@@ -1192,7 +1197,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
             for (int dt = 0; dt < 3; ++dt)
                 if (dtypes_seen & (1u << dt))
                     HIPCHK(c, ddp::launch_repair(dt, c->tables, c->d_order,
-                                                 c->d_gate + (c->iteration % ddp_ctx::kGateRows) * static_cast<int64_t>(c->plan.buckets.size()),
+                                                 c->gate_row(),
                                                  static_cast<int>(c->plan.buckets.size()),
                                                  static_cast<uint32_t>(c->iteration + 1), c->R,
                                                  c->write_all ? c->R : 1, c->iter_zero ? c->d_local : nullptr,

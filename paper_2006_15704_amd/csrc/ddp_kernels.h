@@ -160,9 +160,11 @@ hipError_t launch_join(OrderState* st, uint32_t lane_mask, unsigned long long ta
                        hipStream_t s);
 
 // reduction stream: wait (at most wait_ticks of the device wall clock) until
-// ready_seq >= need; on failure fill *rec and raise abort_tag.
+// ready_seq >= need; on failure fill *rec, tag *row_summary (the record behind the last bucket's
+// in the iteration's row: "a gate of this row gave up") and raise abort_tag.
 hipError_t launch_gate(OrderState* st, unsigned long long need, long long wait_ticks, GateRecord* rec,
-                       int32_t tile_base, int32_t ntiles, int32_t dtype, uint32_t tag, hipStream_t s);
+                       GateRecord* row_summary, int32_t tile_base, int32_t ntiles, int32_t dtype, uint32_t tag,
+                       hipStream_t s);
 
 // Redo the launches of element type `dtype` whose gate gave up in iteration `tag`
 // (rec[0..nb)).  `blocks` persistent blocks; normally there is nothing to do.

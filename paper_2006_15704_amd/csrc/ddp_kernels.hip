@@ -643,7 +643,7 @@ __global__ __launch_bounds__(64) void announce_kernel(OrderState* st, unsigned l
 // One wave; lane 0 polls.  Both bounds (wall-clock ticks and the poll count) end
 // the loop whatever the other stream does.
 __global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long long need,
-                                                  long long wait_ticks, GateRecord* rec,
+                                                  long long wait_ticks, GateRecord* rec, GateRecord* row_summary,
                                                   int32_t tile_base, int32_t ntiles, int32_t dtype,
                                                   uint32_t tag) {
     if (threadIdx.x != 0) return;
@@ -664,6 +664,7 @@ __global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long 
         rec->ntiles = ntiles;
         rec->dtype = dtype;
         rec->failed_tag = tag;
+        row_summary->failed_tag = tag;
         __hip_atomic_store(&st->abort_tag, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
@@ -699,6 +700,8 @@ __global__ __launch_bounds__(BLOCK) void repair_kernel(SegTables t, OrderState* 
                                                        int nb, uint32_t tag, int R, int nwrite,
                                                        const uint8_t* __restrict__ local,
                                                        int keep_unused, Scale sc) {
+    // rec[nb] is the row's summary: no gate of the iteration gave up (the normal case), nothing to look for
+    if (rec[nb].failed_tag != tag) return;
     for (int b = 0; b < nb; ++b) {
         const GateRecord r = rec[b];
         if (r.failed_tag != tag || r.dtype != DT) continue;
@@ -995,9 +998,10 @@ hipError_t launch_join(OrderState* st, uint32_t lane_mask, unsigned long long ta
 }
 
 hipError_t launch_gate(OrderState* st, unsigned long long need, long long wait_ticks, GateRecord* rec,
-                       int32_t tile_base, int32_t ntiles, int32_t dtype, uint32_t tag, hipStream_t s) {
-    hipLaunchKernelGGL(gate_kernel, dim3(1), dim3(64), 0, s, st, need, wait_ticks, rec, tile_base, ntiles,
-                       dtype, tag);
+                       GateRecord* row_summary, int32_t tile_base, int32_t ntiles, int32_t dtype, uint32_t tag,
+                       hipStream_t s) {
+    hipLaunchKernelGGL(gate_kernel, dim3(1), dim3(64), 0, s, st, need, wait_ticks, rec, row_summary, tile_base,
+                       ntiles, dtype, tag);
     return after_launch();
 }
 
