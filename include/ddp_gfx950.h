@@ -20,8 +20,9 @@
  *     call returns.  Gradient memory is owned by the caller and borrowed until
  *     ddp_destroy; bucket storage is owned by the library.
  *   - Streams are hipStream_t values passed as void* (NULL = the null stream).
- *     The library creates streams of its own only when DDP_OPT_REDUCE_STREAMS
- *     asks for more than one reduction stream, at the default priority.
+ *     The library creates reduction streams of its own (one at ddp_create when
+ *     the two streams differ, more if DDP_OPT_REDUCE_STREAMS asks for them), all
+ *     at the default priority and non-blocking with respect to the null stream.
  *   - A context is not thread-safe (the paper's hooks fire from one autograd
  *     thread).  Different contexts may be used from different threads.
  *   - All compute calls are asynchronous with respect to the host unless
@@ -129,7 +130,7 @@ typedef struct ddp_ctx ddp_ctx;
                                      16-byte loads per thread in flight, so two or three blocks per
                                      unit fill the memory system; more only interleave more request
                                      streams at the DRAM channels and throughput drops.  0 = no cap
-                                     (registers decide: 5).  Default -1 =
+                                     (wave slots decide: 8).  Default -1 =
                                      chosen from R: no cap up to R = 4 (few loads per block), else 2 */
 #define DDP_OPT_REDUCE_CAP_MIN_BYTES 14 /* any time: the cap applies to launches of at least this many
                                      bytes of bucket data (measured: it gains 1 to 2.5 points of
