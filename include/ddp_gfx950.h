@@ -108,7 +108,7 @@ typedef struct ddp_ctx ddp_ctx;
                                      skipping at the bucket level); 0 (default) = they are written as
                                      zeros */
 #define DDP_OPT_REDUCE_STREAMS 12  /* between iterations: number of reduction streams, 1 to 8, or -1
-                                     (default): two for launches of less than DDP_OPT_REDUCE_CAP_MIN_BYTES
+                                     (default): two for launches that move less than DDP_OPT_REDUCE_CAP_MIN_BYTES
                                      (start-up and drain of a short launch then overlap with its
                                      neighbour: +2 to 3 points of HBM peak with one launch per 25 MiB
                                      bucket), one for larger launches (two long launches at a time share
@@ -131,11 +131,15 @@ typedef struct ddp_ctx ddp_ctx;
                                      unit fill the memory system; more only interleave more request
                                      streams at the DRAM channels and throughput drops.  0 = no cap
                                      (wave slots decide: 8).  Default -1 =
-                                     chosen from R: no cap up to R = 4 (few loads per block), else 2 */
-#define DDP_OPT_REDUCE_CAP_MIN_BYTES 14 /* any time: the cap applies to launches of at least this many
-                                     bytes of bucket data (measured: it gains 1 to 2.5 points of
-                                     HBM peak from 50 MiB up and loses 1.5 to 3 on launches of 25
-                                     MiB and less).  Default 40 MiB */
+                                     chosen from R: no cap up to R = 4 (few loads per block), else 2
+                                     (4 with ddp_set_outputs, where a block stores twice as much) */
+#define DDP_OPT_REDUCE_CAP_MIN_BYTES 14 /* any time: the cap applies to launches that move at least this
+                                     many bytes, counted as (R + 1) x the launch's bucket bytes
+                                     (measured at R = 8: it gains 1 to 2.5 points of HBM peak from
+                                     50 MiB of bucket data up and loses 1.5 to 3 on launches of 25
+                                     MiB and less; at R = 16 and 32 a 25 MiB bucket is already a long
+                                     launch and gains 2.5 points).  Default 360 MiB (40 MiB of bucket
+                                     data at R = 8) */
 #define DDP_OPT_ACCUMULATE_BLOCKS_PER_CU 16 /* any time: likewise for the accumulate kernel (two loads
                                      and a store per vector; registers allow 8 blocks).  Default 5 */
 #define DDP_OPT_TAIL_ON_BACKWARD 17 /* any time between iterations: 1 (default) = the buckets launched by

@@ -52,11 +52,11 @@ struct ddp_ctx {
                                                   // launch while it stays within this many bytes
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
     int32_t n_streams = -1;                       // reduction streams taken in turn by the launches; -1 = two
-                                                  // for launches below cap_min_bytes, one for larger ones
+                                                  // for launches below cap_min_traffic, one for larger ones
     int32_t tail_on_backward = 1;                 // the call that completes an iteration launches on the backward stream
     int32_t blocks_per_cu = -1;                   // reduce kernels: resident blocks per compute unit (0 = no cap,
                                                   // -1 = chosen from R, see auto_blocks_per_cu)
-    int64_t cap_min_bytes = int64_t(40) << 20;    // ... applied to launches of at least this many bytes
+    int64_t cap_min_traffic = int64_t(360) << 20; // ... applied to launches that move at least this many bytes
     int32_t acc_blocks_per_cu = 5;                // accumulate kernel: likewise
     int64_t lds_per_cu = 160 * 1024;              // read from the device at creation
 
@@ -178,8 +178,11 @@ int32_t fail(ddp_ctx* c, int32_t code, const std::string& msg) {
 // one block is 1 to 1.5 points better on lists of large tensors (a block runs
 // several eight-replica phases) but 6 points worse on the ResNet-50 list in
 // fp16, whose many small tensors put slow boundary tiles on a unit that then
-// has nothing else to run -- so two it is.
-int32_t auto_blocks_per_cu(int32_t R) { return R <= 4 ? 0 : 2; }
+// has nothing else to run -- so two it is.  With binary32 outputs next to 16-bit
+// inputs (ddp_set_outputs) a block stores twice the bytes per byte it loads, and
+// four blocks are best (BERT-large shape, R = 8, launches of <= 100 MiB: 74.6 % with
+// four or five, 73.7 % without a cap, 71 % with two or three).
+int32_t auto_blocks_per_cu(int32_t R, bool binary32_outputs) { return R <= 4 ? 0 : binary32_outputs ? 4 : 2; }
 
 // A launch should run for roughly 150 to 300 us: shorter ones pay their start-up
 // and drain, much longer ones lose throughput again.  Bytes of bucket data per
@@ -192,9 +195,17 @@ int64_t auto_coalesce(int32_t R) {
 
 int64_t coalesce_limit(const ddp_ctx* c) { return c->coalesce < 0 ? auto_coalesce(c->R) : c->coalesce; }
 
+// Whether a launch over `launch_bytes` of bucket data is a long one: the cap on resident
+// blocks pays, and a second reduction stream does not, from about 360 MiB of traffic on
+// (R = 8: 40 MiB of bucket data; R = 32: every 25 MiB bucket, 72.0 against 69.4 % of peak with
+// one mark per call; R = 16 likewise 71.7 against 69.4 %).
+bool long_launch(const ddp_ctx* c, int64_t launch_bytes) {
+    return launch_bytes * (c->R + 1) >= c->cap_min_traffic;
+}
+
 unsigned occupancy_lds(const ddp_ctx* c, int64_t launch_bytes) {
-    const int32_t blocks = c->blocks_per_cu < 0 ? auto_blocks_per_cu(c->R) : c->blocks_per_cu;
-    if (blocks <= 0 || launch_bytes < c->cap_min_bytes) return 0;
+    const int32_t blocks = c->blocks_per_cu < 0 ? auto_blocks_per_cu(c->R, !c->out_ptrs.empty()) : c->blocks_per_cu;
+    if (blocks <= 0 || !long_launch(c, launch_bytes)) return 0;
     return static_cast<unsigned>((c->lds_per_cu / blocks) & ~int64_t(1023));
 }
 
@@ -321,7 +332,7 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
         // Short launches gain from a neighbour on a second stream (start-up and drain of one
         // overlap with the other); launches long enough for the cap on resident blocks lose
         // when two of them share the memory system, so by default those stay on one stream.
-        const int lanes = c->n_streams < 0 ? (bytes < c->cap_min_bytes && c->lane[1] && c->lane_concurrent[1] ? 2 : 1) : c->n_streams;
+        const int lanes = c->n_streams < 0 ? (!long_launch(c, bytes) && c->lane[1] && c->lane_concurrent[1] ? 2 : 1) : c->n_streams;
         lane = static_cast<int>(c->launches_in_iter++ % lanes);
         st = c->lane[lane];
         c->lane_used[lane] = true;
@@ -689,7 +700,7 @@ int32_t ddp_set_option(ddp_ctx* c, int32_t option, int64_t value) {
             return DDP_OK;
         case DDP_OPT_REDUCE_CAP_MIN_BYTES:
             if (value < 0) return fail(c, DDP_ERR_ARG, "bad size");
-            c->cap_min_bytes = value;
+            c->cap_min_traffic = value;
             return DDP_OK;
         case DDP_OPT_TAIL_ON_BACKWARD:
             c->tail_on_backward = value != 0;
@@ -763,7 +774,7 @@ int32_t ddp_get_option(ddp_ctx* c, int32_t option, int64_t* value) {
         case DDP_OPT_NONTEMPORAL: *value = c->nontemporal; return DDP_OK;
         case DDP_OPT_EMIT_BUSY_BLOCKS: *value = c->emit_busy_blocks; return DDP_OK;
         case DDP_OPT_REDUCE_BLOCKS_PER_CU: *value = c->blocks_per_cu; return DDP_OK;
-        case DDP_OPT_REDUCE_CAP_MIN_BYTES: *value = c->cap_min_bytes; return DDP_OK;
+        case DDP_OPT_REDUCE_CAP_MIN_BYTES: *value = c->cap_min_traffic; return DDP_OK;
         case DDP_OPT_ACCUMULATE_BLOCKS_PER_CU: *value = c->acc_blocks_per_cu; return DDP_OK;
         default: return fail(c, DDP_ERR_ARG, "unknown option");
     }

@@ -91,39 +91,51 @@ def knob_sweep(args) -> int:
     import paper_2006_15704_amd as lib
     from paper_2006_15704_amd import harness
 
-    def rate(workload, R, options, steps, replica_skew=None):
+    def rate(workload, R, options, steps, replica_skew=None, per_call=False, bf16_to_binary32=False):
         if workload == "uniform":          # 40 tensors of 25 MiB: every tile is interior
             numel = [25 * MIB // 4] * 40
         else:
             numel = workloads.numel_of(workloads.WORKLOAD_SHAPES[workload]())
         n = len(numel)
-        grads = harness.DeviceGrads(numel, [0] * n, R, replica_skew=replica_skew)
+        dtype = 2 if bf16_to_binary32 else 0
+        grads = harness.DeviceGrads(numel, [dtype] * n, R, replica_skew=replica_skew)
+        outputs = harness.DeviceGrads(numel, [0] * n, 1) if bf16_to_binary32 else None
         gen = torch.Generator(device="cuda")
         gen.manual_seed(7)
         for r in range(R):
             b = grads.bufs[r]
-            b[: b.numel() // 4 * 4].view(torch.float32).normal_(0.0, 1e-3, generator=gen)
+            if bf16_to_binary32:
+                b[: b.numel() // 2 * 2].view(torch.bfloat16).normal_(0.0, 1e-3, generator=gen)
+            else:
+                b[: b.numel() // 4 * 4].view(torch.float32).normal_(0.0, 1e-3, generator=gen)
         order = list(range(n - 1, -1, -1))
-        with harness.Session(grads, 25 * MIB, lib.DDP_PIPELINE_FUSED) as s:
+
+        def step(ctx):
+            if per_call:
+                for p in order:
+                    lib.ddp_mark_ready(ctx, p)
+            else:
+                lib.ddp_mark_ready_many(ctx, order)
+            lib.ddp_finalize_backward(ctx)
+
+        with harness.Session(grads, 25 * MIB, lib.DDP_PIPELINE_FUSED, outputs=outputs) as s:
             for opt, val in options:
                 lib.ddp_set_option(s.ctx, opt, val)
             for _ in range(2):
-                lib.ddp_mark_ready_many(s.ctx, order)
-                lib.ddp_finalize_backward(s.ctx)
+                step(s.ctx)
             lib.ddp_synchronize(s.ctx)
             runs = []
             for _ in range(3):          # the median of three runs: the box stalls a process now and then
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record(s.backward_stream)
                 for _ in range(steps):
-                    lib.ddp_mark_ready_many(s.ctx, order)
-                    lib.ddp_finalize_backward(s.ctx)
+                    step(s.ctx)
                 b.record(s.backward_stream)
                 lib.ddp_synchronize(s.ctx)
                 torch.cuda.synchronize()
                 runs.append(a.elapsed_time(b) / steps)
             ms = statistics.median(runs)
-        total = (R + 1) * sum(numel) * 4
+        total = (R * 2 + 4) * sum(numel) if bf16_to_binary32 else (R + 1) * sum(numel) * 4
         return round(ms, 4), round(total / ms / 1e6 / 8000.0, 4)
 
     def emit(**kw):
@@ -143,6 +155,20 @@ def knob_sweep(args) -> int:
         for nt in (1, 0):
             ms, frac = rate(workload, 8, ((lib.DDP_OPT_NONTEMPORAL, nt),), steps)
             emit(sweep="nontemporal", workload=workload, R=8, nontemporal=nt, ms_per_sync=ms, frac_of_hbm_peak=frac)
+    # one launch per 25 MiB bucket, one ready mark per call: from which launch size on the cap on resident
+    # blocks pays and a second reduction stream no longer does (DDP_OPT_REDUCE_CAP_MIN_BYTES)
+    for R in (8, 16, 32):
+        for what, opts in (("short launch: no cap, two reduction streams", ((lib.DDP_OPT_REDUCE_CAP_MIN_BYTES, 1 << 50),)),
+                           ("long launch: cap, one reduction stream", ((lib.DDP_OPT_REDUCE_CAP_MIN_BYTES, 0),)),
+                           ("library default", ())):
+            ms, frac = rate("bert_large", R, opts, 4 if R >= 16 else 8, per_call=True)
+            emit(sweep="long_launch", workload="bert_large", R=R, treated_as=what, ms_per_sync=ms, frac_of_hbm_peak=frac)
+    # 16-bit gradients in, binary32 averages out (ddp_set_outputs): resident blocks per compute unit
+    for blocks in (0, 2, 3, 4, 5, -1):
+        ms, frac = rate("bert_large", 8, ((lib.DDP_OPT_REDUCE_BLOCKS_PER_CU, blocks),) + (((lib.DDP_OPT_REDUCE_CAP_MIN_BYTES, 0),) if blocks >= 0 else ()),
+                        8, bf16_to_binary32=True)
+        emit(sweep="blocks_per_cu_binary32_outputs", workload="bert_large bf16 -> binary32", R=8,
+             blocks_per_cu="default" if blocks < 0 else blocks, ms_per_sync=ms, frac_of_hbm_peak=frac)
     # replicas whose tensors sit at different offsets modulo 16 bytes
     for what, skew in (("all replicas alike modulo 16 bytes", None),
                        ("replica r shifted by 4 * (r mod 4) bytes", [4 * (r % 4) for r in range(8)])):
