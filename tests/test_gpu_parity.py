@@ -402,6 +402,54 @@ def test_coalesced_launches_keep_order_results_and_cover_every_bucket(pipeline):
         assert grads.download(0, p).tobytes() == want[p].tobytes(), f"parameter {p}"
 
 
+# ---- kernel time stamps ------------------------------------------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("pipeline", [STAGED, FUSED])
+def test_kernel_time_stamps_cover_every_launch_and_are_plausible(pipeline):
+    """DDP_OPT_TIMING = 1: every pack / reduce / unpack / accumulate launch carries its own pair of
+    time stamps.  Durations are positive and far below the wall time of the whole step, their number
+    matches the launches, and the results are the ones without timing."""
+    import time
+    d, harness = lib()
+    numel = [1 << 20, 300, 1 << 18, 5000, 1 << 19]
+    n, R, cap = len(numel), 4, 1 << 21
+    dtypes = [FP32] * n
+    reps = gaussian_reps(21, numel, R, 1e-2)
+    micro = gaussian_reps(22, numel, R, 1e-2)
+    acc = [list(reps[r]) for r in range(R)]
+    for r in range(R):
+        oracle.accumulate(acc[r], micro[r], dtypes)
+    want, asg, _ = oracle.synchronize(numel, dtypes, cap, acc)
+    grads = harness.DeviceGrads(numel, dtypes, R)
+    mg = harness.DeviceGrads(numel, dtypes, R)
+    for r in range(R):
+        grads.upload_replica(r, reps[r])
+        mg.upload_replica(r, micro[r])
+    with harness.Session(grads, cap, pipeline) as s:
+        d.ddp_set_option(s.ctx, d.DDP_OPT_COALESCE, 0)
+        d.ddp_set_option(s.ctx, d.DDP_OPT_TIMING, 1)
+        d.ddp_synchronize(s.ctx)
+        t0 = time.perf_counter()
+        d.ddp_no_sync_accumulate(s.ctx, mg.ptrs())
+        for p in range(n - 1, -1, -1):
+            d.ddp_mark_ready(s.ctx, p)
+        d.ddp_finalize_backward(s.ctx)
+        d.ddp_synchronize(s.ctx)
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        nb = len(asg.buckets)
+        expect = {d.DDP_K_ACCUMULATE: 1, d.DDP_K_REDUCE: nb,
+                  d.DDP_K_PACK: nb if pipeline == STAGED else 0, d.DDP_K_UNPACK: 1 if pipeline == STAGED else 0}
+        for kind, count in expect.items():
+            ms, ids = d.ddp_get_kernel_times(s.ctx, kind)
+            assert len(ms) == count, f"kind {kind}: {len(ms)} timed launches, expected {count}"
+            assert np.all(ms > 0.0) and np.all(ms < wall_ms), f"kind {kind}: durations {ms} ms, wall {wall_ms} ms"
+            if count == nb:
+                assert ids.tolist() == list(range(nb))
+        outs = [grads.download(0, i) for i in range(n)]
+    for i in range(n):
+        assert outs[i].tobytes() == want[i].tobytes(), f"parameter {i}"
+
+
 # ---- several reduction streams -----------------------------------------------------------------
 @pytest.mark.parametrize("pipeline", [STAGED, FUSED])
 @pytest.mark.parametrize("streams", [2, 3, 8])
