@@ -184,6 +184,17 @@ typedef struct ddp_ctx ddp_ctx;
                                      run a gate and its announcement concurrently; ddp_create (and
                                      DDP_OPT_REDUCE_STREAMS) probe for that with a bounded test and such
                                      streams keep events.  0: events always */
+#define DDP_OPT_CHAIN_LAUNCHES 22 /* any time: 1 (default) = with flag ordering, a bucket launch that
+                                     follows another one of the same iteration on a different stream,
+                                     one that moves at least 160 MiB ((R + 1) x its bucket bytes),
+                                     starts when that one has started its last thread block (its gate
+                                     waits for that too, bounded like every wait; the iteration's
+                                     last launches on backward_stream get a one-wave kernel of their
+                                     own for it), so consecutive launches overlap where one drains
+                                     and the next starts up instead of sharing the memory system
+                                     from the start.  0 = launches on different streams start as
+                                     soon as their gradients are there.  Scheduling only: results
+                                     are unchanged */
 #define DDP_OPT_GATE_WAIT_US  19  /* any time: upper bound, in microseconds, on a gate's wait (0 = look
                                      once).  Default 100000.  A backward pass that lags further behind
                                      the host only loses overlap for that iteration, never correctness */

@@ -39,7 +39,7 @@ DDP_OPT_EMIT_BUSY_BLOCKS = 8
 DDP_OPT_COALESCE, DDP_OPT_FIND_UNUSED, DDP_OPT_REDUCE_STREAMS = 10, 11, 12
 DDP_OPT_REDUCE_BLOCKS_PER_CU, DDP_OPT_REDUCE_CAP_MIN_BYTES = 13, 14
 DDP_OPT_ACCUMULATE_BLOCKS_PER_CU, DDP_OPT_TAIL_ON_BACKWARD = 16, 17
-DDP_OPT_FLAG_ORDER, DDP_OPT_GATE_WAIT_US, DDP_OPT_LAUNCH_HOLD = 18, 19, 21
+DDP_OPT_FLAG_ORDER, DDP_OPT_GATE_WAIT_US, DDP_OPT_LAUNCH_HOLD, DDP_OPT_CHAIN_LAUNCHES = 18, 19, 21, 22
 DDP_STAT_REPAIRED_LAUNCHES = 100
 DDP_PIPELINE_STAGED, DDP_PIPELINE_FUSED = 0, 1
 DDP_STATIC_SCRATCH_BYTES = 32 << 20

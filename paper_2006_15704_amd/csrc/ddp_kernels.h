@@ -111,10 +111,16 @@ struct GateRecord;   // below, with the flag-ordering kernels
 
 // gate (may be null): the record of the gate kernel enqueued in front of this
 // launch; if gate->failed_tag == tag the launch does nothing.
+// sig: where (null = nowhere) and with which ordinal the launch's last thread block reports that it
+// has started (OrderState::dispatched)
+struct DispatchSignal {
+    unsigned long long* word;
+    unsigned long long ord;
+};
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
                                bool nontemporal, unsigned lds,
-                               const GateRecord* gate, uint32_t tag, hipStream_t s);
+                               const GateRecord* gate, uint32_t tag, DispatchSignal sig, hipStream_t s);
 // (with t.out set -- 16-bit gradients, binary32 averages written to t.out -- nwrite must be 1)
 
 // ---- stream ordering through device flags -------------------------------------
@@ -135,6 +141,8 @@ struct OrderState {
     uint32_t pad1[30];
     unsigned long long lane_done[16];   // per reduction stream: the latest iteration tag whose launches
                                         //    on that stream have all ended (monotonic)
+    unsigned long long dispatched;      // ordinal of the latest gated bucket launch whose last thread block
+    unsigned long long pad2[15];        //    has started (monotonic): the launch is draining or done
 };
 constexpr int kOrderLanes = 16;
 
@@ -155,6 +163,8 @@ hipError_t launch_announce(OrderState* st, unsigned long long seq, hipStream_t s
 // event that has not fired yet (slow on this system when the wait was enqueued long before):
 // the events of the same streams are recorded before the done kernels and waited for after
 // the join kernel, so a join that gives up changes nothing but the time.
+// backward stream, in front of a bucket launch that needs no gate there: the scheduling wait alone
+hipError_t launch_chain_wait(OrderState* st, unsigned long long chain_ord, long long chain_ticks, hipStream_t s);
 hipError_t launch_done(OrderState* st, int lane, unsigned long long tag, hipStream_t s);
 hipError_t launch_join(OrderState* st, uint32_t lane_mask, unsigned long long tag, long long wait_ticks,
                        hipStream_t s);
@@ -162,9 +172,14 @@ hipError_t launch_join(OrderState* st, uint32_t lane_mask, unsigned long long ta
 // reduction stream: wait (at most wait_ticks of the device wall clock) until
 // ready_seq >= need; on failure fill *rec, tag *row_summary (the record behind the last bucket's
 // in the iteration's row: "a gate of this row gave up") and raise abort_tag.
+// chain_ord / chain_ticks: once the number is there, the gate also waits (at most chain_ticks; 0 =
+// not at all) until the bucket launch with ordinal chain_ord on ANOTHER reduction stream has
+// started its last thread block, so that this launch fills the compute units as that one drains
+// instead of sharing the memory system with it from its start.  A pure scheduling hint: the
+// gate goes on when the bound is reached.
 hipError_t launch_gate(OrderState* st, unsigned long long need, long long wait_ticks, GateRecord* rec,
                        GateRecord* row_summary, int32_t tile_base, int32_t ntiles, int32_t dtype, uint32_t tag,
-                       hipStream_t s);
+                       unsigned long long chain_ord, long long chain_ticks, hipStream_t s);
 
 // Redo the launches of element type `dtype` whose gate gave up in iteration `tag`
 // (rec[0..nb)).  `blocks` persistent blocks; normally there is nothing to do.

@@ -617,7 +617,13 @@ __global__ __launch_bounds__(BLOCK) void fused_reduce_kernel(SegTables t, int64_
                                                              const uint8_t* __restrict__ local,
                                                              int keep_unused, Scale sc,
                                                              const GateRecord* __restrict__ gate,
-                                                             uint32_t tag) {
+                                                             uint32_t tag, DispatchSignal sig) {
+    // the last block of the grid tells that the launch has been dispatched in full (blocks start
+    // in index order): a launch chained behind this one may begin to fill the compute units
+    // (reporting a few hundred blocks earlier, to make up for the start-up of the next launch,
+    // measured no better; 1024 and more blocks earlier lose the gain)
+    if (sig.word != nullptr && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0)
+        __hip_atomic_fetch_max(sig.word, sig.ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     fused_tile<DT, NT, U, OUT32>(t, tile_base + blockIdx.x, R, nwrite, local, keep_unused, sc, gate, tag);
 }
 
@@ -645,7 +651,7 @@ __global__ __launch_bounds__(64) void announce_kernel(OrderState* st, unsigned l
 __global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long long need,
                                                   long long wait_ticks, GateRecord* rec, GateRecord* row_summary,
                                                   int32_t tile_base, int32_t ntiles, int32_t dtype,
-                                                  uint32_t tag) {
+                                                  uint32_t tag, unsigned long long chain_ord, long long chain_ticks) {
     if (threadIdx.x != 0) return;
     bool ok = false;
     if (__hip_atomic_load(&st->abort_tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tag) {
@@ -657,6 +663,15 @@ __global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long 
             }
             if (static_cast<long long>(wall_clock64() - t0) >= wait_ticks) break;
             __builtin_amdgcn_s_sleep(16);
+        }
+    }
+    if (ok && chain_ticks > 0) {
+        // scheduling only: let the launch this one is chained to reach its last block first
+        const uint64_t t1 = wall_clock64();
+        for (uint32_t poll = 0; poll < MAX_GATE_POLLS; ++poll) {
+            if (__hip_atomic_load(&st->dispatched, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= chain_ord) break;
+            if (static_cast<long long>(wall_clock64() - t1) >= chain_ticks) break;
+            __builtin_amdgcn_s_sleep(4);
         }
     }
     if (!ok) {
@@ -689,6 +704,16 @@ __global__ __launch_bounds__(64) void join_kernel(OrderState* st, uint32_t lane_
         if (!missing) break;
         if (static_cast<long long>(wall_clock64() - t0) >= wait_ticks) break;
         __builtin_amdgcn_s_sleep(8);
+    }
+}
+
+__global__ __launch_bounds__(64) void chain_wait_kernel(OrderState* st, unsigned long long chain_ord, long long chain_ticks) {
+    if (threadIdx.x != 0) return;
+    const uint64_t t0 = wall_clock64();
+    for (uint32_t poll = 0; poll < MAX_GATE_POLLS; ++poll) {
+        if (__hip_atomic_load(&st->dispatched, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= chain_ord) break;
+        if (static_cast<long long>(wall_clock64() - t0) >= chain_ticks) break;
+        __builtin_amdgcn_s_sleep(4);
     }
 }
 
@@ -948,16 +973,17 @@ hipError_t launch_flat_reduce(int dtype, const char* in0, int64_t stride, char* 
 template <int DT>
 static hipError_t fused_dispatch(bool nt, int64_t ntiles, unsigned lds, hipStream_t s,
                                  const SegTables& t, int64_t tile_base, int R, int nwrite,
-                                 const uint8_t* local, int keep, Scale sc, const GateRecord* gate, uint32_t tag) {
+                                 const uint8_t* local, int keep, Scale sc, const GateRecord* gate, uint32_t tag,
+                                 DispatchSignal sig) {
     dim3 grid(static_cast<unsigned>(ntiles));
-    if (nt) return launch(fused_reduce_kernel<DT, true, RU>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-    return launch(fused_reduce_kernel<DT, false, RU>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+    if (nt) return launch(fused_reduce_kernel<DT, true, RU>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag, sig);
+    return launch(fused_reduce_kernel<DT, false, RU>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag, sig);
 }
 
 hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base, int64_t ntiles,
                                int R, int nwrite, const uint8_t* local, bool keep_unused, Scale sc,
                                bool nontemporal, unsigned lds,
-                               const GateRecord* gate, uint32_t tag, hipStream_t s) {
+                               const GateRecord* gate, uint32_t tag, DispatchSignal sig, hipStream_t s) {
     if (ntiles <= 0) return hipSuccess;
     const int keep = keep_unused ? 1 : 0;
     if (t.out != nullptr) {
@@ -966,21 +992,26 @@ hipError_t launch_fused_reduce(int dtype, const SegTables& t, int64_t tile_base,
         if (nwrite != 1 || (dtype != 1 && dtype != 2)) return hipErrorInvalidValue;
         const dim3 grid(static_cast<unsigned>(ntiles));
         if (dtype == 1)
-            return nontemporal ? launch(fused_reduce_kernel<1, true, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag)
-                               : launch(fused_reduce_kernel<1, false, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-        return nontemporal ? launch(fused_reduce_kernel<2, true, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag)
-                           : launch(fused_reduce_kernel<2, false, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+            return nontemporal ? launch(fused_reduce_kernel<1, true, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag, sig)
+                               : launch(fused_reduce_kernel<1, false, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag, sig);
+        return nontemporal ? launch(fused_reduce_kernel<2, true, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag, sig)
+                           : launch(fused_reduce_kernel<2, false, U, true>, grid, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag, sig);
     }
     switch (dtype) {
-        case 0: return fused_dispatch<0>(nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-        case 1: return fused_dispatch<1>(nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
-        case 2: return fused_dispatch<2>(nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag);
+        case 0: return fused_dispatch<0>(nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag, sig);
+        case 1: return fused_dispatch<1>(nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag, sig);
+        case 2: return fused_dispatch<2>(nontemporal, ntiles, lds, s, t, tile_base, R, nwrite, local, keep, sc, gate, tag, sig);
         default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_announce(OrderState* st, unsigned long long seq, hipStream_t s) {
     hipLaunchKernelGGL(announce_kernel, dim3(1), dim3(64), 0, s, st, seq);
+    return after_launch();
+}
+
+hipError_t launch_chain_wait(OrderState* st, unsigned long long chain_ord, long long chain_ticks, hipStream_t s) {
+    hipLaunchKernelGGL(chain_wait_kernel, dim3(1), dim3(64), 0, s, st, chain_ord, chain_ticks);
     return after_launch();
 }
 
@@ -999,9 +1030,9 @@ hipError_t launch_join(OrderState* st, uint32_t lane_mask, unsigned long long ta
 
 hipError_t launch_gate(OrderState* st, unsigned long long need, long long wait_ticks, GateRecord* rec,
                        GateRecord* row_summary, int32_t tile_base, int32_t ntiles, int32_t dtype, uint32_t tag,
-                       hipStream_t s) {
+                       unsigned long long chain_ord, long long chain_ticks, hipStream_t s) {
     hipLaunchKernelGGL(gate_kernel, dim3(1), dim3(64), 0, s, st, need, wait_ticks, rec, row_summary, tile_base,
-                       ntiles, dtype, tag);
+                       ntiles, dtype, tag, chain_ord, chain_ticks);
     return after_launch();
 }
 

@@ -68,6 +68,7 @@ def test_model_shapes_r8_fp32(name, config_id, sigma, nb):
     configs = [(STAGED, (), False), (FUSED, (), False), (FUSED, ((d.DDP_OPT_COALESCE, 0),), False),
                (FUSED, per_bucket, False), (FUSED, per_bucket + ((d.DDP_OPT_REDUCE_STREAMS, 2),), False),
                (FUSED, (), True),                                    # the benchmark's headline: marks one call at a time
+               (FUSED, ((d.DDP_OPT_CHAIN_LAUNCHES, 0),), True),      # ... without chaining consecutive launches
                (FUSED, ((d.DDP_OPT_FLAG_ORDER, 0),), True)]          # ... and with events instead of device flags
     for pipeline, options, one_by_one in configs:
         progress(f"{name}: pipeline {pipeline} options {options} one_by_one {one_by_one}")

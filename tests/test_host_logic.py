@@ -362,7 +362,8 @@ def test_options_read_back_on_a_plan_only_context(d):
         assert d.ddp_get_option(ctx, d.DDP_OPT_COALESCE) > 0          # the limit chosen from R
         # every option that can be set can be read
         for opt, val in ((d.DDP_OPT_NONTEMPORAL, 0), (d.DDP_OPT_EMIT_BUSY_BLOCKS, 7), (d.DDP_OPT_REDUCE_BLOCKS_PER_CU, 3),
-                         (d.DDP_OPT_REDUCE_CAP_MIN_BYTES, 12345), (d.DDP_OPT_ACCUMULATE_BLOCKS_PER_CU, 4)):
+                         (d.DDP_OPT_REDUCE_CAP_MIN_BYTES, 12345), (d.DDP_OPT_ACCUMULATE_BLOCKS_PER_CU, 4),
+                         (d.DDP_OPT_CHAIN_LAUNCHES, 0)):
             d.ddp_set_option(ctx, opt, val)
             assert d.ddp_get_option(ctx, opt) == val
         with pytest.raises(d.DdpError) as e:
