@@ -53,11 +53,12 @@ struct ddp_ctx {
     int32_t emit_busy_blocks = 0;                 // synthetic backward: 0 = sleeping delay kernel
     int32_t n_streams = -1;                       // reduction streams taken in turn by the launches; -1 = two
                                                   // for launches below cap_min_traffic, one for larger ones
-    bool tail_chained = false;                    // this iteration's launches on the backward stream have their scheduling wait
     int32_t chain_launches = 1;                   // flag-ordered launches on alternating streams wait for their predecessor's last block
-    unsigned long long gated_ord = 0;             // ordinal of the latest gated bucket launch (monotonic over the context's life)
-    int prev_gated_lane = -1;                     // the stream it went to
-    int64_t prev_gated_traffic = 0;               // the bytes it moves, (R + 1) x its bucket bytes
+    unsigned long long launch_ord = 0;            // ordinal of the latest bucket launch that reports its dispatch (monotonic
+                                                  // over the context's life)
+    unsigned long long prev_launch_ord = 0;       // this iteration's latest such launch (0 = none yet), ...
+    int prev_launch_lane = -1;                    // ... the reduction stream it went to (-1 = the backward stream) ...
+    int64_t prev_launch_traffic = 0;              // ... and the bytes it moves, (R + 1) x its bucket bytes
     int32_t tail_on_backward = 1;                 // the call that completes an iteration launches on the backward stream
     int32_t blocks_per_cu = -1;                   // reduce kernels: resident blocks per compute unit (0 = no cap,
                                                   // -1 = chosen from R, see auto_blocks_per_cu)
@@ -318,10 +319,50 @@ bool flags_usable(const ddp_ctx* c) {
     return true;
 }
 
-// Enqueue on a reduction stream everything buckets [first, last] need, as one
-// launch per kernel.  The buckets are consecutive, hold one element type, and
-// their tiles and slab ranges are contiguous.
-int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) {
+// Order the launches of the running API call after the gradient-producing work enqueued so
+// far: one look at the backward stream, and at most one announcement or event on it, serves
+// every bucket the call launches (the caller cannot enqueue anything in the middle of a call).
+// If the backward stream has already drained there is nothing to wait for.
+int32_t order_call(ddp_ctx* c, int32_t first) {
+    if (c->ordered_in_call) return DDP_OK;
+    // (a stream that is being captured into a graph cannot be queried: treat it as busy)
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    const bool capturing = hipStreamIsCapturing(c->backward, &cap) == hipSuccess &&
+                           cap != hipStreamCaptureStatusNone;
+    const bool by_flag = !capturing && flags_usable(c);
+    // With flags the announcement is enqueued without first asking whether the backward
+    // stream has drained: the question (a stream query takes as long on the host as
+    // two launches) would only save the two small kernels when it has.
+    const hipError_t q = (capturing || by_flag) ? hipErrorNotReady : hipStreamQuery(c->backward);
+    if (q == hipErrorNotReady) {
+        if (by_flag) {
+            // a one-block kernel instead of an event record (which stalls the stream
+            // for about 12 us here)
+            c->call_seq = ++c->seq_issued;
+            HIPCHK(c, ddp::launch_announce(c->d_order, c->call_seq, c->backward));
+            c->call_by_flag = true;
+        } else {
+            HIPCHK(c, hipEventRecord(c->ev_ready[first], c->backward));
+            c->call_event = c->ev_ready[first];
+        }
+    } else if (q == hipSuccess) {
+        c->backward_idle_in_call = true;
+        c->safe_iteration = c->iteration;     // every earlier iteration has finished
+    } else {
+        return fail(c, DDP_ERR_HIP, std::string("hipStreamQuery: ") + hipGetErrorString(q));
+    }
+    c->ordered_in_call = true;
+    return DDP_OK;
+}
+
+// Where a launch goes: a reduction stream taken in turn, the backward stream (the API call that
+// completes the iteration, see flush_deferred), or the caller's reduction stream as the
+// partner of the backward stream when such a call makes several launches.
+enum class Target { kLane, kBackward, kPartner };
+
+// Enqueue everything buckets [first, last] need, as one launch per kernel.  The buckets are
+// consecutive, hold one element type, and their tiles and slab ranges are contiguous.
+int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, Target target) {
     const ddp::BucketInfo& bf = c->plan.buckets[first];
     const ddp::BucketInfo& bl = c->plan.buckets[last];
     const int seg_begin = bf.seg_begin;
@@ -330,70 +371,52 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
     const int64_t ntiles = c->h_tile0[seg_end] - tile_base;
     int64_t bytes = 0;
     for (int32_t b = first; b <= last; ++b) bytes += static_cast<int64_t>(c->plan.buckets[b].bytes());
+    const int64_t traffic = bytes * (c->R + 1);
     const int32_t id = first + 65536 * (last - first);
-    // The launches of an iteration take the reduction streams in turn -- except
-    // those of the API call that completes the iteration (see flush_deferred),
-    // which go to the backward stream itself.
-    int lane = -1;
+    int lane = -1;                    // -1: the backward stream
     hipStream_t st = c->backward;
-    if (!on_backward) {
+    if (target == Target::kLane) {
         // Short launches gain from a neighbour on a second stream (start-up and drain of one
         // overlap with the other); launches long enough for the cap on resident blocks lose
         // when two of them share the memory system, so by default those stay on one stream.
         const int lanes = c->n_streams < 0 ? (!long_launch(c, bytes) && c->lane[1] && c->lane_concurrent[1] ? 2 : 1) : c->n_streams;
         lane = static_cast<int>(c->launches_in_iter++ % lanes);
+    } else if (target == Target::kPartner) {
+        lane = 0;
+    }
+    if (lane >= 0 && c->lane[lane] != c->backward) {
         st = c->lane[lane];
         c->lane_used[lane] = true;
     } else {
+        lane = -1;
         c->tail_used = true;
     }
     const ddp::GateRecord* gate = nullptr;
     ddp::DispatchSignal sig{nullptr, 0};
-    if (on_backward && c->chain_launches != 0 && c->gates_in_iter > 0 && !c->tail_chained && ntiles > 0 &&
-        (c->prev_gated_traffic >= kChainMinTraffic || bytes * (c->R + 1) >= kChainMinTraffic)) {
-        // the iteration's last launch(es), on the backward stream: no gate needed there, but the
-        // scheduling wait alone (see the chained launches below) if this launch or the one in
-        // front is a long one -- with back-to-back iterations this launch would otherwise run
-        // next to the iteration's first ones for all of its time
-        HIPCHK(c, ddp::launch_chain_wait(c->d_order, c->gated_ord, c->gate_wait_us * c->wall_clock_khz / 1000, st));
-        c->tail_chained = true;
+    if (lane >= 0 && (!c->lane_ordered[lane] || c->call_by_flag)) {
+        const int32_t rc = order_call(c, first);
+        if (rc != DDP_OK) return rc;
     }
-    if (st != c->backward && (!c->lane_ordered[lane] || c->call_by_flag)) {
-        // Order the buckets after the gradient-producing work enqueued so far.
-        // If the backward stream has already drained there is nothing to wait
-        // for, and the queue packets are saved.  Within one API call the caller
-        // cannot enqueue anything in between, so one look at the backward stream
-        // (and at most one event or announcement on it) serves every bucket the
-        // call launches.
-        if (!c->ordered_in_call) {
-            // (a stream that is being captured into a graph cannot be queried: treat it as busy)
-            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-            const bool capturing = hipStreamIsCapturing(c->backward, &cap) == hipSuccess &&
-                                   cap != hipStreamCaptureStatusNone;
-            const bool by_flag = !capturing && flags_usable(c);
-            // With flags the announcement is enqueued without first asking whether the backward
-            // stream has drained: the question (a stream query takes as long on the host as
-            // two launches) would only save the two small kernels when it has.
-            const hipError_t q = (capturing || by_flag) ? hipErrorNotReady : hipStreamQuery(c->backward);
-            if (q == hipErrorNotReady) {
-                if (by_flag) {
-                    // a one-block kernel instead of an event record (which stalls the stream
-                    // for about 12 us here)
-                    c->call_seq = ++c->seq_issued;
-                    HIPCHK(c, ddp::launch_announce(c->d_order, c->call_seq, c->backward));
-                    c->call_by_flag = true;
-                } else {
-                    HIPCHK(c, hipEventRecord(c->ev_ready[first], c->backward));
-                    c->call_event = c->ev_ready[first];
-                }
-            } else if (q == hipSuccess) {
-                c->backward_idle_in_call = true;
-                c->safe_iteration = c->iteration;     // every earlier iteration has finished
-            } else {
-                return fail(c, DDP_ERR_HIP, std::string("hipStreamQuery: ") + hipGetErrorString(q));
-            }
-            c->ordered_in_call = true;
-        }
+    // Chained launches.  With flag ordering in use (so the streams are known to run side by
+    // side and nothing is being captured), a launch that follows another launch of this
+    // iteration on a DIFFERENT stream lets that one reach its last thread block first (a
+    // bounded wait: in the gate of a launch on a reduction stream, in a one-wave kernel of its
+    // own on the backward stream), so that the two overlap where one drains and the other
+    // starts up rather than sharing the memory system all the way (on one stream, stream order
+    // does more).  It pays from about 160 MiB moved by the launch in front (measured with one
+    // mark per call, gain of chaining: 225 MiB +4.7 to +6.1 %, 170-180 MiB +3.2 to +5.4 %,
+    // 125-135 MiB -1.2 to -3.0 %, 45-90 MiB -0.5 to -4.4 %: short launches are mostly start-up
+    // and drain, and those overlap best when both run at once).  A launch on the backward
+    // stream is also chained if it is long itself: with back-to-back iterations it would
+    // otherwise run next to the iteration's first launches for all of its time.
+    const bool flags_in_use = c->call_by_flag || c->gates_in_iter > 0;
+    const bool chained = c->chain_launches != 0 && flags_in_use && c->prev_launch_ord != 0 && c->prev_launch_lane != lane &&
+                         ntiles > 0 && c->pipeline == DDP_PIPELINE_FUSED &&
+                         (c->prev_launch_traffic >= kChainMinTraffic || (lane < 0 && traffic >= kChainMinTraffic));
+    const long long wait_ticks = c->gate_wait_us * c->wall_clock_khz / 1000;
+    if (lane < 0 && chained)
+        HIPCHK(c, ddp::launch_chain_wait(c->d_order, c->prev_launch_ord, wait_ticks, st));
+    if (lane >= 0 && (!c->lane_ordered[lane] || c->call_by_flag)) {
         if (c->call_by_flag) {
             // every launch gets a gate of its own: if the gate gives up, exactly this launch
             // is skipped and redone by the repair launch of the finalizing step
@@ -405,34 +428,26 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, bool on_backward) 
                 c->safe_iteration = c->iteration;
             }
             ddp::GateRecord* rec = c->gate_row() + first;
-            // Chained launches: a launch that follows a gated launch of this iteration on ANOTHER
-            // reduction stream lets that one reach its last thread block first (a bounded wait),
-            // so that the two overlap where one drains and the other starts up rather than
-            // sharing the memory system all the way (on one stream, stream order does more).
-            // It pays from about 160 MiB moved by the launch in front (measured with one mark per
-            // call, gain of chaining: 225 MiB +4.7 to +6.1 %, 170-180 MiB +3.2 to +5.4 %, 125-135 MiB
-            // -1.2 to -3.0 %, 45-90 MiB -0.5 to -4.4 %: short launches are mostly start-up and
-            // drain, and those overlap best when both run at once).
-            const bool chained = c->chain_launches != 0 && c->gates_in_iter > 0 && c->prev_gated_lane != lane &&
-                                 ntiles > 0 && c->prev_gated_traffic >= kChainMinTraffic;
-            HIPCHK(c, ddp::launch_gate(c->d_order, c->call_seq, c->gate_wait_us * c->wall_clock_khz / 1000, rec,
+            HIPCHK(c, ddp::launch_gate(c->d_order, c->call_seq, wait_ticks, rec,
                                        c->gate_row() + c->plan.buckets.size(),
                                        static_cast<int32_t>(tile_base), static_cast<int32_t>(ntiles), bf.dtype,
                                        static_cast<uint32_t>(c->iteration + 1),
-                                       chained ? c->gated_ord : 0ull,
-                                       chained ? c->gate_wait_us * c->wall_clock_khz / 1000 : 0, st));
+                                       chained ? c->prev_launch_ord : 0ull, chained ? wait_ticks : 0, st));
             gate = rec;
             ++c->gates_in_iter;
-            if (ntiles > 0) {
-                sig.word = &c->d_order->dispatched;
-                sig.ord = ++c->gated_ord;
-                c->prev_gated_lane = lane;
-                c->prev_gated_traffic = bytes * (c->R + 1);
-            }
         } else if (!c->backward_idle_in_call) {
             HIPCHK(c, hipStreamWaitEvent(st, c->call_event, 0));
         }
         c->lane_ordered[lane] = true;
+    }
+    if (c->chain_launches != 0 && (c->call_by_flag || c->gates_in_iter > 0) && ntiles > 0 &&
+        c->pipeline == DDP_PIPELINE_FUSED) {
+        // the launch reports when its last block starts, for whatever is chained behind it
+        sig.word = &c->d_order->dispatched;
+        sig.ord = ++c->launch_ord;
+        c->prev_launch_ord = sig.ord;
+        c->prev_launch_lane = lane;
+        c->prev_launch_traffic = traffic;
     }
     // Participation flags travel to the device only for launches that hold a
     // zero flag (a replica that did not use a parameter, or a parameter nobody
@@ -532,6 +547,7 @@ int32_t flush_deferred(ddp_ctx* c) {
         todo.resize(kept);
         if (todo.empty()) return DDP_OK;
     }
+    std::vector<std::pair<int32_t, int32_t>> ranges;      // [first, last] bucket of every launch
     size_t i = 0;
     while (i < todo.size()) {
         size_t j = i;
@@ -545,9 +561,24 @@ int32_t flush_deferred(ddp_ctx* c) {
                 ++j;
             }
         }
-        const int32_t st = launch_range(c, todo[i], todo[j], closing);
-        if (st != DDP_OK) return st;
+        ranges.emplace_back(todo[i], todo[j]);
         i = j + 1;
+    }
+    // A closing call that makes several launches: on one stream each launch would start when
+    // the one before has drained.  With chained launches they take the backward stream and the
+    // caller's reduction stream in turn instead, every launch starting as its predecessor
+    // reaches its last thread block.  The announcement that orders the reduction stream's
+    // share goes out first, ahead of the backward stream's own launches.
+    bool partner = false;
+    if (closing && ranges.size() > 1 && c->chain_launches != 0 && c->reduce != c->backward && flags_usable(c)) {
+        const int32_t rc = order_call(c, ranges[0].first);
+        if (rc != DDP_OK) return rc;
+        partner = c->call_by_flag;
+    }
+    for (size_t k = 0; k < ranges.size(); ++k) {
+        const Target target = !closing ? Target::kLane : (partner && (k & 1u)) ? Target::kPartner : Target::kBackward;
+        const int32_t st = launch_range(c, ranges[k].first, ranges[k].second, target);
+        if (st != DDP_OK) return st;
     }
     return DDP_OK;
 }
@@ -1286,7 +1317,7 @@ int32_t ddp_finalize_backward(ddp_ctx* c) {
     c->launches_in_iter = 0;
     c->tail_used = false;
     c->gates_in_iter = 0;
-    c->tail_chained = false;
+    c->prev_launch_ord = 0;
     ++c->iteration;
     c->tracker.new_iteration();
     return DDP_OK;
