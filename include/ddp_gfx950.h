@@ -186,7 +186,8 @@ typedef struct ddp_ctx ddp_ctx;
                                      streams keep events.  0: events always */
 #define DDP_OPT_CHAIN_LAUNCHES 22 /* any time: 1 (default) = with flag ordering, a bucket launch that
                                      follows another one of the same iteration on a different stream,
-                                     one that moves at least 160 MiB ((R + 1) x its bucket bytes),
+                                     one that moves at least 160 MiB ((R + 1) x its bucket bytes;
+                                     unless both move DDP_OPT_REDUCE_CAP_MIN_BYTES or more),
                                      starts when that one has started its last thread block (its gate
                                      waits for that too, bounded like every wait; the iteration's
                                      last launches on backward_stream get a one-wave kernel of their

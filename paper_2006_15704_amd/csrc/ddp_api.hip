@@ -406,13 +406,18 @@ int32_t launch_range(ddp_ctx* c, int32_t first, int32_t last, Target target) {
     // does more).  It pays from about 160 MiB moved by the launch in front (measured with one
     // mark per call, gain of chaining: 225 MiB +4.7 to +6.1 %, 170-180 MiB +3.2 to +5.4 %,
     // 125-135 MiB -1.2 to -3.0 %, 45-90 MiB -0.5 to -4.4 %: short launches are mostly start-up
-    // and drain, and those overlap best when both run at once).  A launch on the backward
-    // stream is also chained if it is long itself: with back-to-back iterations it would
-    // otherwise run next to the iteration's first launches for all of its time.
+    // and drain, and those overlap best when both run at once).  Two launches that are both
+    // long enough for the cap on resident blocks are left alone: in turn on two streams,
+    // chained, they lose 1.5 to 3 points against one stream (R = 16 and 32, binary32
+    // outputs).  A launch on the backward stream is chained whenever it moves 160 MiB itself:
+    // with back-to-back iterations it would otherwise run next to the iteration's first
+    // launches for all of its time.
     const bool flags_in_use = c->call_by_flag || c->gates_in_iter > 0;
+    const bool both_long = c->prev_launch_traffic >= c->cap_min_traffic && traffic >= c->cap_min_traffic;
     const bool chained = c->chain_launches != 0 && flags_in_use && c->prev_launch_ord != 0 && c->prev_launch_lane != lane &&
                          ntiles > 0 && c->pipeline == DDP_PIPELINE_FUSED &&
-                         (c->prev_launch_traffic >= kChainMinTraffic || (lane < 0 && traffic >= kChainMinTraffic));
+                         ((c->prev_launch_traffic >= kChainMinTraffic && !both_long) ||
+                          (lane < 0 && traffic >= kChainMinTraffic));
     const long long wait_ticks = c->gate_wait_us * c->wall_clock_khz / 1000;
     if (lane < 0 && chained)
         HIPCHK(c, ddp::launch_chain_wait(c->d_order, c->prev_launch_ord, wait_ticks, st));
@@ -575,10 +580,18 @@ int32_t flush_deferred(ddp_ctx* c) {
         if (rc != DDP_OK) return rc;
         partner = c->call_by_flag;
     }
+    bool prev_on_backward = false, prev_long = false;
     for (size_t k = 0; k < ranges.size(); ++k) {
-        const Target target = !closing ? Target::kLane : (partner && (k & 1u)) ? Target::kPartner : Target::kBackward;
+        int64_t bytes = 0;
+        for (int32_t b = ranges[k].first; b <= ranges[k].second; ++b) bytes += static_cast<int64_t>(c->plan.buckets[b].bytes());
+        const bool is_long = long_launch(c, bytes);
+        // (two long launches do best one after the other on one stream)
+        const bool to_partner = partner && k > 0 && prev_on_backward && !(prev_long && is_long);
+        const Target target = !closing ? Target::kLane : to_partner ? Target::kPartner : Target::kBackward;
         const int32_t st = launch_range(c, ranges[k].first, ranges[k].second, target);
         if (st != DDP_OK) return st;
+        prev_on_backward = target == Target::kBackward;
+        prev_long = is_long;
     }
     return DDP_OK;
 }
