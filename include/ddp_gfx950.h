@@ -193,9 +193,12 @@ typedef struct ddp_ctx ddp_ctx;
                                      last launches on backward_stream get a one-wave kernel of their
                                      own for it), so consecutive launches overlap where one drains
                                      and the next starts up instead of sharing the memory system
-                                     from the start.  0 = launches on different streams start as
-                                     soon as their gradients are there.  Scheduling only: results
-                                     are unchanged */
+                                     from the start; and an API call that completes the iteration
+                                     with several launches spreads them over backward_stream and
+                                     reduce_stream in turn under the same rule instead of queueing
+                                     them on backward_stream.  0 = launches on different streams
+                                     start as soon as their gradients are there.  Scheduling only:
+                                     results are unchanged */
 #define DDP_OPT_GATE_WAIT_US  19  /* any time: upper bound, in microseconds, on a gate's wait (0 = look
                                      once).  Default 100000.  A backward pass that lags further behind
                                      the host only loses overlap for that iteration, never correctness */
