@@ -197,6 +197,9 @@ def main() -> int:
                     help="comma list: numbers of reduction streams (DDP_OPT_REDUCE_STREAMS)")
     ap.add_argument("--coalesce-mib", type=float, default=0,
                     help="DDP_OPT_COALESCE in MiB (0 = off, negative = no limit)")
+    ap.add_argument("--hold", type=int, default=0,
+                    help="DDP_OPT_LAUNCH_HOLD: a launchable bucket waits for this many further ready marks so "
+                         "that its successors can share its launch (needs --coalesce-mib other than 0)")
     ap.add_argument("--shuffle-blocks", type=int, default=0,
                     help="backward order = reverse registration order cut into blocks of this many "
                          "parameters, the blocks shuffled (0 = plain reverse order).  Every "
@@ -251,6 +254,7 @@ def main() -> int:
                 by_flags = bool(lib.ddp_get_option(ctx, lib.DDP_OPT_FLAG_ORDER))
                 lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE,
                                    (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * MIB))
+                lib.ddp_set_option(ctx, lib.DDP_OPT_LAUNCH_HOLD, args.hold)
 
                 def sync():
                     lib.ddp_synchronize(ctx)
@@ -288,7 +292,7 @@ def main() -> int:
                         print(json.dumps({
                             "workload": args.workload, "dtype": args.dtype, "R": R, "pipeline": pipe,
                             "cap_mib": cap_mib, "n_buckets": n_buckets, "streams": n_streams,
-                            "coalesce_mib": args.coalesce_mib, "delay_us_per_param": d_us,
+                            "coalesce_mib": args.coalesce_mib, "launch_hold": args.hold, "delay_us_per_param": d_us,
                             "order": f"blocks of {args.shuffle_blocks} shuffled" if args.shuffle_blocks else "reverse",
                             "mapping": mapping, "ordered_by": "flags" if by_flags else "events",
                             "backward_writes_gradients": bool(src_ptrs), "busy_blocks": args.busy_blocks,
