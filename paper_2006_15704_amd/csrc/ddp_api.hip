@@ -269,41 +269,61 @@ void new_call(ddp_ctx* c) {
     for (bool& b : c->lane_ordered) b = false;
 }
 
-// Whether lane `l` makes progress while the backward stream is busy and vice versa.  HIP
-// streams that share a hardware queue run one after the other; a gate kernel on such a lane
-// would keep the announcement it waits for from running, so those pairs keep events.  The
-// probe is a bounded wait on the lane for a value written from the backward stream.
-int32_t probe_lane(ddp_ctx* c, int l) {
-    c->lane_concurrent[l] = false;
-    if (c->lane[l] == c->backward) return DDP_OK;
-    HIPCHK(c, hipStreamSynchronize(c->lane[l]));
-    HIPCHK(c, hipStreamSynchronize(c->backward));
+// Whether stream `waiter` makes progress while stream `other` is busy and vice versa.  HIP
+// streams that share a hardware queue run one after the other.  The probe is a bounded wait on
+// `waiter` for a value written from `other`.
+int32_t probe_pair(ddp_ctx* c, hipStream_t waiter, hipStream_t other, bool* concurrent) {
+    *concurrent = false;
+    if (waiter == other) return DDP_OK;
+    HIPCHK(c, hipStreamSynchronize(waiter));
+    HIPCHK(c, hipStreamSynchronize(other));
     ++c->probe_value;
-    HIPCHK(c, ddp::launch_probe(c->d_probe, c->probe_value, 300 * c->wall_clock_khz / 1000, c->lane[l], c->backward));
-    HIPCHK(c, hipStreamSynchronize(c->lane[l]));
-    HIPCHK(c, hipStreamSynchronize(c->backward));
+    HIPCHK(c, ddp::launch_probe(c->d_probe, c->probe_value, 300 * c->wall_clock_khz / 1000, waiter, other));
+    HIPCHK(c, hipStreamSynchronize(waiter));
+    HIPCHK(c, hipStreamSynchronize(other));
     unsigned long long seen = 0;
     HIPCHK(c, hipMemcpy(&seen, c->d_probe + 1, sizeof(seen), hipMemcpyDeviceToHost));
-    c->lane_concurrent[l] = seen == 1;
+    *concurrent = seen == 1;
     return DDP_OK;
 }
 
+// Lane l against the backward stream: a gate kernel on a lane that shares the backward
+// stream's hardware queue would keep the announcement it waits for from running, so such
+// pairs keep events.
+int32_t probe_lane(ddp_ctx* c, int l) {
+    return probe_pair(c, c->lane[l], c->backward, &c->lane_concurrent[l]);
+}
+
 // Creates reduction stream l (default priority, no implicit ordering with the legacy
-// default stream).  A new stream may land on the hardware queue of the backward stream; a
-// few more are tried then (the misfits are destroyed once one fits, so that the next try
-// does not get the same queue again).
+// default stream).  A new stream may land on the hardware queue of the backward stream, or
+// on that of the caller's reduction stream, next to which it is meant to run; a few more are
+// tried then (the misfits are destroyed once one fits, so that the next try does not get the
+// same queue again).  A stream that runs side by side with both is taken at once; failing
+// that, the first one that does so with the backward stream.
 int32_t create_lane(ddp_ctx* c, int l) {
     if (c->lane[l]) return DDP_OK;
-    hipStream_t misfit[6];
-    int misfits = 0;
-    for (;;) {
-        HIPCHK(c, hipStreamCreateWithFlags(&c->lane[l], hipStreamNonBlocking));
-        const int32_t rc = probe_lane(c, l);
-        if (rc != DDP_OK) return rc;
-        if (c->lane_concurrent[l] || misfits == 6) break;
-        misfit[misfits++] = c->lane[l];
+    hipStream_t tried[7];
+    int n_tried = 0, second_best = -1, best = -1;
+    while (n_tried < 7 && best < 0) {
+        hipStream_t s = nullptr;
+        HIPCHK(c, hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        tried[n_tried] = s;
+        bool with_backward = false, with_first = true;
+        int32_t rc = probe_pair(c, s, c->backward, &with_backward);
+        if (rc == DDP_OK && with_backward && c->lane[0] != c->backward) rc = probe_pair(c, s, c->lane[0], &with_first);
+        if (rc != DDP_OK) {
+            for (int k = 0; k <= n_tried; ++k) (void)hipStreamDestroy(tried[k]);
+            return rc;
+        }
+        if (with_backward && with_first) best = n_tried;
+        else if (with_backward && second_best < 0) second_best = n_tried;
+        ++n_tried;
     }
-    for (int k = 0; k < misfits; ++k) (void)hipStreamDestroy(misfit[k]);
+    const int pick = best >= 0 ? best : second_best >= 0 ? second_best : n_tried - 1;
+    c->lane[l] = tried[pick];
+    c->lane_concurrent[l] = best >= 0 || second_best >= 0;
+    for (int k = 0; k < n_tried; ++k)
+        if (k != pick) (void)hipStreamDestroy(tried[k]);
     HIPCHK(c, hipEventCreateWithFlags(&c->ev_join[l], kOrderEvent));
     return DDP_OK;
 }
