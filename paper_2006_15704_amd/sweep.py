@@ -200,6 +200,8 @@ def main() -> int:
     ap.add_argument("--hold", type=int, default=0,
                     help="DDP_OPT_LAUNCH_HOLD: a launchable bucket waits for this many further ready marks so "
                          "that its successors can share its launch (needs --coalesce-mib other than 0)")
+    ap.add_argument("--chain", type=int, default=1, choices=[0, 1],
+                    help="DDP_OPT_CHAIN_LAUNCHES: 1 = a launch behind a long one on another stream starts as that one drains")
     ap.add_argument("--shuffle-blocks", type=int, default=0,
                     help="backward order = reverse registration order cut into blocks of this many "
                          "parameters, the blocks shuffled (0 = plain reverse order).  Every "
@@ -255,6 +257,7 @@ def main() -> int:
                 lib.ddp_set_option(ctx, lib.DDP_OPT_COALESCE,
                                    (1 << 62) if args.coalesce_mib < 0 else int(args.coalesce_mib * MIB))
                 lib.ddp_set_option(ctx, lib.DDP_OPT_LAUNCH_HOLD, args.hold)
+                lib.ddp_set_option(ctx, lib.DDP_OPT_CHAIN_LAUNCHES, args.chain)
 
                 def sync():
                     lib.ddp_synchronize(ctx)
