@@ -105,6 +105,8 @@ class Rig:
     """`sets` independent sets of replica gradients of one workload, one context
     per set, all contexts on the same pair of streams."""
 
+    every_rig_options = ()        # (option, value) pairs applied to every context (--launch-ordering)
+
     def __init__(self, lib, harness, torch, workload, sets, pipeline, options=(), same_stream=False,
                  binary32_outputs=False):
         self.lib, self.torch = lib, torch
@@ -128,7 +130,7 @@ class Rig:
         for g, o in zip(self.grads, self.outputs):
             s = harness.Session(g, self.cap, pipeline, same_stream=same_stream, streams=streams, outputs=o)
             streams = (s.reduce_stream, s.backward_stream)
-            for opt, val in options:
+            for opt, val in tuple(Rig.every_rig_options) + tuple(options):
                 lib.ddp_set_option(s.ctx, opt, val)
             self.sessions.append(s)
         self.backward_stream = self.sessions[0].backward_stream
@@ -628,8 +630,9 @@ def main() -> int:
         del src, dst
 
     sets = args.sets if args.workload == "resnet50" else min(args.sets, 2)
-    options = ((lib.DDP_OPT_FLAG_ORDER, 0),) if args.launch_ordering == "events" else ()
-    head = shape_leg(lib, harness, torch, args.workload, sets, args.steps, args.warmup, legs, "per_call", options)
+    if args.launch_ordering == "events":
+        Rig.every_rig_options = ((lib.DDP_OPT_FLAG_ORDER, 0),)
+    head = shape_leg(lib, harness, torch, args.workload, sets, args.steps, args.warmup, legs, "per_call")
     _, _, R, _, dtype, _ = WORKLOADS[args.workload]
     out = {
         "metric": "bucketed grad-sync throughput ((R+W)*B per synchronization)",

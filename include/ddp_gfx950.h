@@ -131,8 +131,7 @@ typedef struct ddp_ctx ddp_ctx;
                                      unit fill the memory system; more only interleave more request
                                      streams at the DRAM channels and throughput drops.  0 = no cap
                                      (wave slots decide: 8).  Default -1 =
-                                     chosen from R: no cap up to R = 4 (few loads per block), else 2
-                                     (4 with ddp_set_outputs, where a block stores twice as much) */
+                                     chosen from R: no cap up to R = 4 (few loads per block), else 2 */
 #define DDP_OPT_REDUCE_CAP_MIN_BYTES 14 /* any time: the cap applies to launches that move at least this
                                      many bytes, counted as (R + 1) x the launch's bucket bytes
                                      (measured at R = 8: it gains 1 to 2.5 points of HBM peak from

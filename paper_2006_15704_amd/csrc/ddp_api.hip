@@ -184,11 +184,10 @@ int32_t fail(ddp_ctx* c, int32_t code, const std::string& msg) {
 // one block is 1 to 1.5 points better on lists of large tensors (a block runs
 // several eight-replica phases) but 6 points worse on the ResNet-50 list in
 // fp16, whose many small tensors put slow boundary tiles on a unit that then
-// has nothing else to run -- so two it is.  With binary32 outputs next to 16-bit
-// inputs (ddp_set_outputs) a block stores twice the bytes per byte it loads, and
-// four blocks are best (BERT-large shape, R = 8, launches of <= 100 MiB: 74.6 % with
-// four or five, 73.7 % without a cap, 71 % with two or three).
-int32_t auto_blocks_per_cu(int32_t R, bool binary32_outputs) { return R <= 4 ? 0 : binary32_outputs ? 4 : 2; }
+// has nothing else to run -- so two it is, also with binary32 outputs next to 16-bit
+// inputs (BERT-large shape in bf16, R = 8, launches of <= 100 MiB: 77.6 % with two or three
+// blocks, 74.8 % with four or none, 74.3 % with five).
+int32_t auto_blocks_per_cu(int32_t R) { return R <= 4 ? 0 : 2; }
 
 // A launch should run for roughly 150 to 300 us: shorter ones pay their start-up
 // and drain, much longer ones lose throughput again.  Bytes of bucket data per
@@ -213,7 +212,7 @@ bool long_launch(const ddp_ctx* c, int64_t launch_bytes) {
 }
 
 unsigned occupancy_lds(const ddp_ctx* c, int64_t launch_bytes) {
-    const int32_t blocks = c->blocks_per_cu < 0 ? auto_blocks_per_cu(c->R, !c->out_ptrs.empty()) : c->blocks_per_cu;
+    const int32_t blocks = c->blocks_per_cu < 0 ? auto_blocks_per_cu(c->R) : c->blocks_per_cu;
     if (blocks <= 0 || !long_launch(c, launch_bytes)) return 0;
     return static_cast<unsigned>((c->lds_per_cu / blocks) & ~int64_t(1023));
 }
