@@ -88,7 +88,7 @@ def device_grads(harness, torch, numel, dtype, R, sigma, seed, fill_noise=True):
 
 def read_traffic(workload, mode):
     """HBM bytes per reduce launch from the committed counter summary, if any."""
-    path = os.path.join(ROOT, "profiles", f"reduce_traffic_{workload}_{mode}.json")
+    path = os.path.join(ROOT, "profiles", f"reduce_traffic_{workload}_{mode}.txt")
     try:
         with open(path) as fh:
             return json.load(fh).get("traffic_bytes_per_launch")
