@@ -228,6 +228,7 @@ class Rig:
             "pct_hbm_peak_end_to_end": round(100.0 * alg / ms_per_step / 1e6 / HBM_PEAK_GBPS, 2),
             "host_enqueue_ms_per_step": round((t_enq - t0) * 1e3 / steps, 4),
             "launches_per_step": launches_per_step,
+            "repaired_launches": int(sum(lib.ddp_get_option(s.ctx, lib.DDP_STAT_REPAIRED_LAUNCHES) for s in self.sessions)),
             "roofline": {
                 "kernel": "fused_reduce_kernel",
                 "bound": "hbm",
@@ -653,6 +654,7 @@ def main() -> int:
         "pct_hbm_peak_end_to_end": head["pct_hbm_peak_end_to_end"],
         "host_enqueue_ms_per_step": head["host_enqueue_ms_per_step"],
         "launches_per_step": head["launches_per_step"],
+        "repaired_launches": head["repaired_launches"],
         "roofline": head["roofline"],
     }
     for key in ("marks_in_one_call", "marks_one_by_one_hold_16", "one_launch_per_bucket", "single_replica_set"):
