@@ -264,7 +264,7 @@ class Rig:
         one_stream = ((lib.DDP_OPT_REDUCE_STREAMS, 1), (lib.DDP_OPT_COALESCE, 0),
                       (lib.DDP_OPT_TAIL_ON_BACKWARD, 0), (lib.DDP_OPT_FLAG_ORDER, 0))
         defaults = ((lib.DDP_OPT_REDUCE_STREAMS, -1), (lib.DDP_OPT_COALESCE, -1),
-                    (lib.DDP_OPT_TAIL_ON_BACKWARD, 1), (lib.DDP_OPT_FLAG_ORDER, -1))
+                    (lib.DDP_OPT_TAIL_ON_BACKWARD, 1), (lib.DDP_OPT_FLAG_ORDER, -1)) + tuple(Rig.every_rig_options)
         for s in self.sessions:
             for o, v in one_stream:
                 lib.ddp_set_option(s.ctx, o, v)
