@@ -688,7 +688,7 @@ __global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long 
                 break;
             }
             if (static_cast<long long>(wall_clock64() - t0) >= wait_ticks) break;
-            __builtin_amdgcn_s_sleep(16);
+            __builtin_amdgcn_s_sleep(2);
         }
     }
     if (ok && chain_ticks > 0) {
@@ -697,7 +697,7 @@ __global__ __launch_bounds__(64) void gate_kernel(OrderState* st, unsigned long 
         for (uint32_t poll = 0; poll < MAX_GATE_POLLS; ++poll) {
             if (__hip_atomic_load(&st->dispatched, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= chain_ord) break;
             if (static_cast<long long>(wall_clock64() - t1) >= chain_ticks) break;
-            __builtin_amdgcn_s_sleep(4);
+            __builtin_amdgcn_s_sleep(2);
         }
     }
     if (!ok) {
@@ -729,7 +729,7 @@ __global__ __launch_bounds__(64) void join_kernel(OrderState* st, uint32_t lane_
                 missing |= __hip_atomic_load(&st->lane_done[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < tag ? 1u : 0u;
         if (!missing) break;
         if (static_cast<long long>(wall_clock64() - t0) >= wait_ticks) break;
-        __builtin_amdgcn_s_sleep(8);
+        __builtin_amdgcn_s_sleep(2);
     }
 }
 
@@ -739,7 +739,7 @@ __global__ __launch_bounds__(64) void chain_wait_kernel(OrderState* st, unsigned
     for (uint32_t poll = 0; poll < MAX_GATE_POLLS; ++poll) {
         if (__hip_atomic_load(&st->dispatched, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= chain_ord) break;
         if (static_cast<long long>(wall_clock64() - t0) >= chain_ticks) break;
-        __builtin_amdgcn_s_sleep(4);
+        __builtin_amdgcn_s_sleep(2);
     }
 }
 
